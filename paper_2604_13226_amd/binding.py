@@ -1,0 +1,316 @@
+"""ctypes binding of libkvp.so: the same entry points as include/kvp.h, taking torch
+tensors for device memory.  Argument marshalling only -- every step of the path runs in
+the library's HIP kernels.  There is no CPU fallback: if the library is missing, loading
+fails.
+"""
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkvp.so")
+
+KVP_F32, KVP_BF16 = 0, 1
+KVP_CONTIG, KVP_PAGED = 0, 1
+KVP_OK, KVP_E_INVAL, KVP_E_EXISTS, KVP_E_NOTFOUND = 0, -1, -2, -3
+KVP_E_NOSPACE, KVP_E_CAPACITY, KVP_E_HIP = -4, -5, -6
+KVP_PREROTATED = 1
+KVP_DEVICE_NONE = -1
+
+_vp, _i32, _i64, _u64, _u32 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64,
+                               ctypes.c_uint32)
+
+
+class kvp_config_t(ctypes.Structure):
+    _fields_ = [("n_layers", _i32), ("n_q_heads", _i32), ("n_kv_heads", _i32), ("head_dim", _i32),
+                ("n_header", _i32), ("n_trailer", _i32), ("dtype", _i32), ("max_positions", _i32),
+                ("rope_base", ctypes.c_double), ("inv_freq", _vp), ("arena", _vp),
+                ("arena_bytes", _u64), ("device", _i32)]
+
+
+class kvp_request_t(ctypes.Structure):
+    _fields_ = [("packet_ids", _vp), ("k", _i32), ("base_pos", _i32)]
+
+
+class kvp_cache_t(ctypes.Structure):
+    _fields_ = [("layout", _i32), ("k", _vp), ("v", _vp), ("t_cap", _i32), ("n_blocks", _i32),
+                ("block_size", _i32), ("block_table", _vp), ("max_blocks_per_req", _i32),
+                ("ctx_len", _vp)]
+
+
+EXPORTS = {
+    "kvp_store_create": (_i32, [ctypes.POINTER(kvp_config_t), ctypes.POINTER(_vp)]),
+    "kvp_store_destroy": (_i32, [_vp]),
+    "kvp_store_put": (_i32, [_vp, _i64, _i32, _vp, _vp, _i32, _vp]),
+    "kvp_store_packet_len": (_i32, [_vp, _i64]),
+    "kvp_store_bytes_used": (_u64, [_vp]),
+    "kvp_packet_bytes": (_u64, [ctypes.POINTER(kvp_config_t), _i32]),
+    "kvp_assemble": (_i32, [_vp, ctypes.POINTER(kvp_request_t), _i32, _i32, _i32,
+                            ctypes.POINTER(kvp_cache_t), _vp]),
+    "kvp_query_prefill": (_i32, [_vp, ctypes.POINTER(kvp_cache_t), _i32, _vp, _vp, _vp, _vp, _i32,
+                                 _u32, _vp, _u64, _vp, _vp]),
+    "kvp_prefill_workspace_bytes": (_u64, [_vp, _i32, _i32, _i32]),
+    "kvp_last_error": (ctypes.c_char_p, [_vp]),
+    "kvp_debug_last_plan": (_i64, [_vp, _i32, _vp, _i64]),
+    "kvp_version": (ctypes.c_char_p, []),
+}
+
+_lib = None
+
+
+def load():
+    """Loads libkvp.so (built by paper_2604_13226_amd.build).  Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libkvp.so is not built: run `python -m paper_2604_13226_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+class KvpError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("kvp error %d: %s" % (code, text))
+        self.code = code
+
+
+def _check(store, rc):
+    if rc != 0:
+        raise KvpError(rc, (load().kvp_last_error(store) or b"").decode())
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+
+
+def _dtype_code(dt):
+    return {torch.float32: KVP_F32, torch.bfloat16: KVP_BF16, "f32": KVP_F32, "bf16": KVP_BF16}[dt]
+
+
+class Store:
+    """Handle of a kvp_store_t plus the arena tensor it points into (the caller's memory)."""
+
+    def __init__(self, handle, cfg, arena):
+        self.handle, self.cfg, self.arena = handle, cfg, arena
+        self.dry = cfg.device == KVP_DEVICE_NONE
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.cfg.dtype == KVP_BF16 else torch.float32
+
+    def __del__(self):
+        try:
+            kvp_store_destroy(self)
+        except Exception:
+            pass
+
+
+def kvp_store_create(n_layers, n_q_heads, n_kv_heads, head_dim, dtype, rope_base, max_positions,
+                     arena_bytes, n_header=0, n_trailer=0, device=0, inv_freq=None):
+    """kvp_store_create: allocates the arena with torch on `device` and creates the store.
+    device=KVP_DEVICE_NONE makes a planning-only store (no GPU touched)."""
+    L = load()
+    cfg = kvp_config_t()
+    cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim = n_layers, n_q_heads, n_kv_heads, head_dim
+    cfg.n_header, cfg.n_trailer = n_header, n_trailer
+    cfg.dtype = _dtype_code(dtype)
+    cfg.max_positions = max_positions
+    cfg.rope_base = float(rope_base)
+    keep = None
+    if inv_freq is not None:
+        keep = np.ascontiguousarray(inv_freq, np.float32)
+        cfg.inv_freq = keep.ctypes.data
+    arena = None
+    if device != KVP_DEVICE_NONE:
+        arena = torch.empty(int(arena_bytes) + 256, dtype=torch.uint8, device="cuda:%d" % device)
+        base = (arena.data_ptr() + 255) // 256 * 256
+        cfg.arena = base
+    cfg.arena_bytes = int(arena_bytes)
+    cfg.device = device
+    h = _vp()
+    rc = L.kvp_store_create(ctypes.byref(cfg), ctypes.byref(h))
+    if rc != 0:
+        raise KvpError(rc, (L.kvp_last_error(None) or b"").decode())
+    return Store(h, cfg, arena)
+
+
+def kvp_store_destroy(store):
+    if store.handle is not None:
+        h, store.handle = store.handle, None
+        load().kvp_store_destroy(h)
+
+
+def kvp_store_put(store, packet_id, k, v, stream=None, n_tokens=None):
+    """k, v: torch tensors [n_layers][n_kv_heads][n_tokens][head_dim] on the GPU or the CPU."""
+    if store.dry:
+        rc = load().kvp_store_put(store.handle, int(packet_id), int(n_tokens), None, None, 0, None)
+        return _check(store.handle, rc)
+    assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
+    assert k.dtype == store.torch_dtype and v.dtype == store.torch_dtype
+    c = store.cfg
+    assert tuple(k.shape[:2]) == (c.n_layers, c.n_kv_heads) and k.shape[3] == c.head_dim
+    on_dev = 1 if k.is_cuda else 0
+    assert v.is_cuda == k.is_cuda
+    rc = load().kvp_store_put(store.handle, int(packet_id), int(k.shape[2]), k.data_ptr(), v.data_ptr(),
+                              on_dev, _stream(stream))
+    _check(store.handle, rc)
+
+
+def kvp_store_packet_len(store, packet_id):
+    return int(load().kvp_store_packet_len(store.handle, int(packet_id)))
+
+
+def kvp_store_bytes_used(store):
+    return int(load().kvp_store_bytes_used(store.handle))
+
+
+def kvp_packet_bytes(store, n_tokens):
+    return int(load().kvp_packet_bytes(ctypes.byref(store.cfg), int(n_tokens)))
+
+
+class Cache:
+    """kvp_cache_t plus the tensors/arrays it points to.
+
+    CONTIG: k, v [n_req][n_layers][n_kv_heads][t_cap][d].
+    PAGED : k, v pools [n_layers][n_blocks][n_kv_heads][block_size][d]; block_table is a
+            host int32 array [n_req][max_blocks_per_req].
+    """
+
+    def __init__(self, k, v, n_req, layout=KVP_CONTIG, block_table=None, block_size=16):
+        self.k, self.v, self.n_req, self.layout = k, v, n_req, layout
+        self.ctx_len = np.zeros(max(n_req, 1), np.int32)
+        self.block_table = None
+        c = kvp_cache_t()
+        c.layout = layout
+        c.k = k.data_ptr() if k is not None else None
+        c.v = v.data_ptr() if v is not None else None
+        if layout == KVP_CONTIG:
+            c.t_cap = int(k.shape[3])
+        else:
+            self.block_table = np.ascontiguousarray(block_table, np.int32)
+            assert self.block_table.ndim == 2 and self.block_table.shape[0] == n_req
+            c.n_blocks = int(k.shape[1])
+            c.block_size = int(block_size)
+            c.block_table = self.block_table.ctypes.data
+            c.max_blocks_per_req = int(self.block_table.shape[1])
+        c.ctx_len = self.ctx_len.ctypes.data
+        self.c = c
+
+    @staticmethod
+    def contiguous(store, n_req, t_cap, device="cuda:0"):
+        g = store.cfg
+        shape = (n_req, g.n_layers, g.n_kv_heads, t_cap, g.head_dim)
+        k = torch.zeros(shape, dtype=store.torch_dtype, device=device)
+        v = torch.zeros(shape, dtype=store.torch_dtype, device=device)
+        return Cache(k, v, n_req)
+
+    @staticmethod
+    def dry(n_req, t_cap=0, layout=KVP_CONTIG, n_blocks=0, block_table=None, block_size=16):
+        """Cache descriptor without device memory, for planning-only stores."""
+        class _Fake:
+            def __init__(self, shape): self.shape = shape
+            def data_ptr(self): return 4096
+        if layout == KVP_CONTIG:
+            f = _Fake((n_req, 0, 0, t_cap, 0))
+            return Cache(f, f, n_req)
+        f = _Fake((0, n_blocks, 0, block_size, 0))
+        return Cache(f, f, n_req, KVP_PAGED, block_table, block_size)
+
+    @staticmethod
+    def paged(store, n_req, n_blocks, block_table, block_size=16, device="cuda:0"):
+        g = store.cfg
+        shape = (g.n_layers, n_blocks, g.n_kv_heads, block_size, g.head_dim)
+        k = torch.zeros(shape, dtype=store.torch_dtype, device=device)
+        v = torch.zeros(shape, dtype=store.torch_dtype, device=device)
+        return Cache(k, v, n_req, KVP_PAGED, block_table, block_size)
+
+    def logical(self, r, layer, n_rows):
+        """(K, V) rows 0..n_rows-1 of request r at `layer` as [n_kv_heads][n_rows][d] tensors."""
+        if self.layout == KVP_CONTIG:
+            return self.k[r, layer, :, :n_rows], self.v[r, layer, :, :n_rows]
+        bs = self.c.block_size
+        nb = (n_rows + bs - 1) // bs
+        blocks = torch.as_tensor(self.block_table[r, :nb].astype(np.int64), device=self.k.device)
+        def gather(pool):
+            x = pool[layer, blocks]                       # [nb][Hkv][bs][d]
+            x = x.permute(1, 0, 2, 3).reshape(pool.shape[2], nb * bs, pool.shape[4])
+            return x[:, :n_rows]
+        return gather(self.k), gather(self.v)
+
+
+def kvp_assemble(store, requests, cache, layer_begin=0, layer_end=None, stream=None):
+    """requests: list of (packet_ids, base_pos).  Fills cache.ctx_len."""
+    n_req = len(requests)
+    arr = (kvp_request_t * max(n_req, 1))()
+    keep = []
+    for i, (ids, base_pos) in enumerate(requests):
+        a = np.ascontiguousarray(ids, np.int64)
+        keep.append(a)
+        arr[i].packet_ids = a.ctypes.data if len(a) else None
+        arr[i].k = len(a)
+        arr[i].base_pos = int(base_pos)
+    if layer_end is None:
+        layer_end = store.cfg.n_layers
+    rc = load().kvp_assemble(store.handle, arr, n_req, int(layer_begin), int(layer_end),
+                             ctypes.byref(cache.c), _stream(stream))
+    _check(store.handle, rc)
+
+
+def kvp_prefill_workspace_bytes(store, n_req, max_tot_q, max_ctx):
+    return int(load().kvp_prefill_workspace_bytes(store.handle, int(n_req), int(max_tot_q), int(max_ctx)))
+
+
+def kvp_query_prefill(store, cache, layer, q, k_new, v_new, q_offsets, workspace, out, flags=0,
+                      stream=None):
+    """q [tot_q][Hq][d], k_new/v_new [tot_q][Hkv][d], out like q: torch tensors on the GPU;
+    q_offsets: host int32 [n_req+1]; workspace: torch uint8 tensor, 256-byte aligned."""
+    qo = np.ascontiguousarray(q_offsets, np.int32)
+    n_req = len(qo) - 1
+    if store.dry:
+        rc = load().kvp_query_prefill(store.handle, ctypes.byref(cache.c), int(layer), None, None, None,
+                                      qo.ctypes.data, n_req, int(flags), None, 1 << 60, None, None)
+        return _check(store.handle, rc)
+    for t in (q, k_new, v_new, out):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == store.torch_dtype
+    g = store.cfg
+    tot_q = int(qo[-1])
+    assert tuple(q.shape) == (tot_q, g.n_q_heads, g.head_dim) and out.shape == q.shape
+    assert tuple(k_new.shape) == (tot_q, g.n_kv_heads, g.head_dim) and v_new.shape == k_new.shape
+    rc = load().kvp_query_prefill(store.handle, ctypes.byref(cache.c), int(layer), q.data_ptr(),
+                                  k_new.data_ptr(), v_new.data_ptr(), qo.ctypes.data, n_req, int(flags),
+                                  workspace.data_ptr(), int(workspace.numel()), out.data_ptr(),
+                                  _stream(stream))
+    _check(store.handle, rc)
+
+
+def kvp_last_error(store):
+    return (load().kvp_last_error(store.handle if store else None) or b"").decode()
+
+
+def kvp_debug_last_plan(store, which):
+    n = int(load().kvp_debug_last_plan(store.handle, int(which), None, 0))
+    out = np.zeros(max(n, 1), np.int64)
+    load().kvp_debug_last_plan(store.handle, int(which), out.ctypes.data, n)
+    return out[:n]
+
+
+def kvp_version():
+    return load().kvp_version().decode()
+
+
+def alloc_workspace(nbytes, device="cuda:0"):
+    """256-byte aligned uint8 workspace tensor of at least nbytes."""
+    t = torch.empty(int(nbytes) + 256, dtype=torch.uint8, device=device)
+    off = (-t.data_ptr()) % 256
+    return t[off:off + int(nbytes)]

@@ -1,0 +1,176 @@
+// kvp_assemble.hip -- K1: gather the retrieved packets into the per-layer cache and
+// realign their keys (Sec. 3.1, Eq. 1; Sec. 4.2.1 step 4).
+//
+// HBM-bound: every K and V element of the context is read once and written once; the
+// rotation is 3 flop per K element.  The rotation angle Delta_j * theta_i does not depend
+// on the row inside a packet, so each thread keeps the cos/sin of its column chunk in
+// registers for the whole tile and only streams 16-byte K/V vectors through.
+#include "kvp_device.h"
+
+#pragma clang fp contract(off)  // products and sums are rounded separately, as the oracle's
+
+namespace kvp {
+
+template <typename T> struct Vec16;
+template <> struct Vec16<float> { static constexpr int N = 4; };
+template <> struct Vec16<bf16_t> { static constexpr int N = 8; };
+
+__device__ __forceinline__ void unpack(const uint4 &u, float (&x)[4])
+{
+    x[0] = __uint_as_float(u.x); x[1] = __uint_as_float(u.y);
+    x[2] = __uint_as_float(u.z); x[3] = __uint_as_float(u.w);
+}
+__device__ __forceinline__ void unpack(const uint4 &u, float (&x)[8])
+{
+    x[0] = __uint_as_float(u.x << 16); x[1] = __uint_as_float(u.x & 0xFFFF0000u);
+    x[2] = __uint_as_float(u.y << 16); x[3] = __uint_as_float(u.y & 0xFFFF0000u);
+    x[4] = __uint_as_float(u.z << 16); x[5] = __uint_as_float(u.z & 0xFFFF0000u);
+    x[6] = __uint_as_float(u.w << 16); x[7] = __uint_as_float(u.w & 0xFFFF0000u);
+}
+__device__ __forceinline__ uint4 pack(const float (&x)[4])
+{
+    return make_uint4(__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]),
+                      __float_as_uint(x[3]));
+}
+__device__ __forceinline__ uint4 pack(const float (&x)[8])
+{
+    uint4 u;
+    u.x = (uint32_t)f32_to_bf16(x[0]) | ((uint32_t)f32_to_bf16(x[1]) << 16);
+    u.y = (uint32_t)f32_to_bf16(x[2]) | ((uint32_t)f32_to_bf16(x[3]) << 16);
+    u.z = (uint32_t)f32_to_bf16(x[4]) | ((uint32_t)f32_to_bf16(x[5]) << 16);
+    u.w = (uint32_t)f32_to_bf16(x[6]) | ((uint32_t)f32_to_bf16(x[7]) << 16);
+    return u;
+}
+
+constexpr int ASM_THREADS = 256;
+
+// Vector path: D (head_dim) is a compile-time power of two with D/2 a multiple of the
+// 16-byte vector width, so a thread's column chunk is the same in every pass.
+template <typename T, int D>
+__global__ __launch_bounds__(ASM_THREADS) void assemble_vec_kernel(AsmArgs a)
+{
+    constexpr int N = Vec16<T>::N;
+    constexpr int HALF = D / 2;
+    constexpr int CPR = HALF / N;                  // K: (lo, hi) chunk pairs per row
+    constexpr int KROWS = ASM_THREADS / CPR;       // rows per pass
+    constexpr int KPASS = ASM_TILE_ROWS / KROWS;
+    constexpr int VCPR = D / N;                    // V: chunks per row
+    constexpr int VROWS = ASM_THREADS / VCPR;
+    constexpr int VPASS = ASM_TILE_ROWS / VROWS;
+    static_assert(CPR >= 1 && ASM_THREADS % CPR == 0 && KPASS >= 1 && VPASS >= 1, "shape");
+
+    const AsmTile tile = a.tiles[blockIdx.x];
+    const int layer = a.layer_begin + (int)blockIdx.y / a.n_kv;
+    const int head = (int)blockIdx.y % a.n_kv;
+    const int tid = threadIdx.x;
+
+    const T *arena = (const T *)a.arena;
+    const int64_t blob = (int64_t)a.n_layers_total * a.n_kv * tile.n_pkt * D;
+    const T *ksrc = arena + tile.src_base + (((int64_t)layer * a.n_kv + head) * tile.n_pkt + tile.tok0) * D;
+    const T *vsrc = ksrc + blob;
+    T *kdst = (T *)a.cache.k;
+    T *vdst = (T *)a.cache.v;
+
+    // issue every load of the tile first
+    const int kc = tid % CPR, kr0 = tid / CPR;
+    uint4 klo[KPASS], khi[KPASS];
+#pragma unroll
+    for (int p = 0; p < KPASS; ++p) {
+        int r = kr0 + p * KROWS;
+        if (r < tile.n_tok) {
+            klo[p] = *(const uint4 *)(ksrc + (int64_t)r * D + kc * N);
+            khi[p] = *(const uint4 *)(ksrc + (int64_t)r * D + HALF + kc * N);
+        }
+    }
+    const int vc = tid % VCPR, vr0 = tid / VCPR;
+    uint4 vv[VPASS];
+#pragma unroll
+    for (int p = 0; p < VPASS; ++p) {
+        int r = vr0 + p * VROWS;
+        if (r < tile.n_tok) vv[p] = *(const uint4 *)(vsrc + (int64_t)r * D + vc * N);
+    }
+    float c[N], s[N];
+    {
+        const float2 *cs = a.cs + (int64_t)tile.pos * HALF + kc * N;
+#pragma unroll
+        for (int i = 0; i < N; ++i) { float2 t = cs[i]; c[i] = t.x; s[i] = t.y; }
+    }
+
+#pragma unroll
+    for (int p = 0; p < VPASS; ++p) {
+        int r = vr0 + p * VROWS;
+        if (r < tile.n_tok) {
+            int64_t o = cache_row_off(a.cache, tile.req, layer, head, tile.dst_row + r, a.n_kv, D);
+            *(uint4 *)(vdst + o + vc * N) = vv[p];
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < KPASS; ++p) {
+        int r = kr0 + p * KROWS;
+        if (r < tile.n_tok) {
+            float x[N], y[N], lo[N], hi[N];
+            unpack(klo[p], x);
+            unpack(khi[p], y);
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                float xc = x[i] * c[i], ys = y[i] * s[i];
+                float yc = y[i] * c[i], xs = x[i] * s[i];
+                lo[i] = xc - ys;
+                hi[i] = yc + xs;
+            }
+            int64_t o = cache_row_off(a.cache, tile.req, layer, head, tile.dst_row + r, a.n_kv, D);
+            *(uint4 *)(kdst + o + kc * N) = pack(lo);
+            *(uint4 *)(kdst + o + HALF + kc * N) = pack(hi);
+        }
+    }
+}
+
+// Scalar path for any even head_dim.
+template <typename T>
+__global__ __launch_bounds__(ASM_THREADS) void assemble_scalar_kernel(AsmArgs a)
+{
+    const AsmTile tile = a.tiles[blockIdx.x];
+    const int layer = a.layer_begin + (int)blockIdx.y / a.n_kv;
+    const int head = (int)blockIdx.y % a.n_kv;
+    const int d = a.d, half = d / 2;
+    const T *arena = (const T *)a.arena;
+    const int64_t blob = (int64_t)a.n_layers_total * a.n_kv * tile.n_pkt * d;
+    const T *ksrc = arena + tile.src_base + (((int64_t)layer * a.n_kv + head) * tile.n_pkt + tile.tok0) * d;
+    const T *vsrc = ksrc + blob;
+    T *kdst = (T *)a.cache.k;
+    T *vdst = (T *)a.cache.v;
+    const float2 *cs = a.cs + (int64_t)tile.pos * half;
+    for (int idx = threadIdx.x; idx < tile.n_tok * half; idx += ASM_THREADS) {
+        int r = idx / half, i = idx % half;
+        float x = ld_elem(ksrc + (int64_t)r * d + i), y = ld_elem(ksrc + (int64_t)r * d + half + i);
+        float2 t = cs[i];
+        float xc = x * t.x, ys = y * t.y, yc = y * t.x, xs = x * t.y;
+        int64_t o = cache_row_off(a.cache, tile.req, layer, head, tile.dst_row + r, a.n_kv, d);
+        st_elem(kdst + o + i, xc - ys);
+        st_elem(kdst + o + half + i, yc + xs);
+        vdst[o + i] = vsrc[(int64_t)r * d + i];
+        vdst[o + half + i] = vsrc[(int64_t)r * d + half + i];
+    }
+}
+
+int launch_assemble(int dtype, const AsmArgs &a, int n_layers_launch, void *stream)
+{
+    if (a.n_tiles == 0 || n_layers_launch == 0) return 0;
+    dim3 grid((unsigned)a.n_tiles, (unsigned)(n_layers_launch * a.n_kv));
+    dim3 block(ASM_THREADS);
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == 1) {
+        if (a.d == 128) hipLaunchKernelGGL((assemble_vec_kernel<bf16_t, 128>), grid, block, 0, st, a);
+        else if (a.d == 64) hipLaunchKernelGGL((assemble_vec_kernel<bf16_t, 64>), grid, block, 0, st, a);
+        else if (a.d == 256) hipLaunchKernelGGL((assemble_vec_kernel<bf16_t, 256>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((assemble_scalar_kernel<bf16_t>), grid, block, 0, st, a);
+    } else {
+        if (a.d == 128) hipLaunchKernelGGL((assemble_vec_kernel<float, 128>), grid, block, 0, st, a);
+        else if (a.d == 64) hipLaunchKernelGGL((assemble_vec_kernel<float, 64>), grid, block, 0, st, a);
+        else if (a.d == 256) hipLaunchKernelGGL((assemble_vec_kernel<float, 256>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((assemble_scalar_kernel<float>), grid, block, 0, st, a);
+    }
+    return (int)hipGetLastError();
+}
+
+}  // namespace kvp

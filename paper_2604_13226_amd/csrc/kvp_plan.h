@@ -1,0 +1,89 @@
+// kvp_plan.h -- plain-data plans the host builds per call and the kernels consume.
+// Shared by the host runtime and the HIP kernels of this library only.
+#pragma once
+#include <stdint.h>
+
+namespace kvp {
+
+// One tile of the gather: up to ASM_TILE_ROWS consecutive rows of one retrieved packet.
+// The same tile list serves every (layer, kv head): blockIdx.y selects those.
+struct AsmTile {
+    int64_t src_base;  // element offset of the packet's K blob in the arena
+    int32_t n_pkt;     // rows of the packet (stride between heads in the blob)
+    int32_t tok0;      // first packet row of this tile
+    int32_t n_tok;     // rows in this tile
+    int32_t dst_row;   // cache row (absolute position) of tok0
+    int32_t pos;       // Delta_j: rotation offset of the packet (Eq. 1)
+    int32_t req;       // request index
+};
+static_assert(sizeof(AsmTile) == 32, "AsmTile is 32 bytes");
+
+constexpr int ASM_TILE_ROWS = 64;
+
+struct CacheView {
+    void *k, *v;
+    const int32_t *block_table;  // device, [n_req][max_blocks] (paged)
+    int64_t req_stride;          // contig: elements between requests
+    int64_t layer_stride;        // elements between layers (contig: per request; paged: pool)
+    int32_t layout, t_cap, n_blocks, block_shift, max_blocks;
+};
+
+struct AsmArgs {
+    const void *arena;
+    const float2 *cs;  // [max_positions][d/2] (cos, sin)
+    const AsmTile *tiles;
+    CacheView cache;
+    int32_t n_tiles, layer_begin, n_layers_total, n_kv, d;
+};
+
+// ---- query prefill -------------------------------------------------------------
+struct ReqMeta {
+    int32_t ctx_len;  // rows already in the cache = position of query row 0
+    int32_t q_off;    // first query row in q / out
+    int32_t n_q;
+    int32_t pad;
+};
+
+// Packed row m of a (request, kv head) pair: query token t = m / g, query head
+// hq = h * g + m % g, so the g heads that share KV head h sit next to each other.
+// A group is rows [m0, m0 + bm) of one pair; a work item is one kv range of a group.
+struct AttnGroup {
+    int32_t req, kv_head, m0, n_rows;  // n_rows <= bm
+    int32_t part0, n_splits;           // partial slots part0 .. part0 + n_splits - 1
+    int32_t pad0, pad1;
+};
+struct AttnItem {
+    int32_t group, split, kv_begin, kv_end;  // kv rows [kv_begin, kv_end)
+};
+
+struct AttnArgs {
+    const void *q_rot;  // [tot_q][Hq][d], store dtype, rotated
+    CacheView cache;
+    const ReqMeta *reqs;
+    const AttnGroup *groups;
+    const AttnItem *items;
+    float *partials;  // [slot][bm][d + 2]: O~ rows, then m[bm], then l[bm]
+    void *out;        // [tot_q][Hq][d]
+    int32_t n_items, n_groups, layer, n_q_heads, n_kv, d, bm, g;
+    float scale_log2e;  // log2(e) / sqrt(d)
+};
+
+struct AppendArgs {
+    const void *q, *k_new, *v_new;
+    void *q_rot;
+    const float2 *cs;
+    CacheView cache;
+    const ReqMeta *reqs;
+    const int32_t *row_req;  // [tot_q] -> request
+    int32_t tot_q, layer, n_q_heads, n_kv, d, prerotated;
+};
+
+// launchers (defined next to their kernels)
+int launch_assemble(int dtype, const AsmArgs &a, int n_layers_launch, void *stream);
+int launch_append(int dtype, const AppendArgs &a, void *stream);
+int launch_attention(int dtype, const AttnArgs &a, int kernel_kind, void *stream);
+int launch_combine(int dtype, const AttnArgs &a, void *stream);
+
+enum { ATTN_GENERIC = 0, ATTN_MFMA = 1 };
+
+}  // namespace kvp

@@ -1,0 +1,202 @@
+// kvp_query.hip -- K2: query-side RoPE + append; generic (any dtype, any head_dim)
+// split-KV attention; K4: split-KV combine.  (Sec. 4.2.1 step 4; Fig. 2(d).)
+#include "kvp_device.h"
+
+namespace kvp {
+
+// ---------------------------------------------------------------------------------
+// K2.  One thread per (query row, head, pair i): rotates Q and K_new from position 0 to
+// ctx_len + t, writes the rotated Q to the workspace (store dtype), the rotated K_new and
+// the raw V_new to cache rows ctx_len + t.
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void append_kernel(AppendArgs a)
+{
+#pragma clang fp contract(off)
+    const int half = a.d / 2;
+    const int heads = a.n_q_heads + a.n_kv;
+    const int64_t total = (int64_t)a.tot_q * heads * half;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (int64_t)gridDim.x * blockDim.x) {
+        int i = (int)(idx % half);
+        int64_t rh = idx / half;
+        int hh = (int)(rh % heads);
+        int row = (int)(rh / heads);
+        int req = a.row_req[row];
+        ReqMeta m = a.reqs[req];
+        int pos = m.ctx_len + (row - m.q_off);
+        float c = 1.f, s = 0.f;
+        if (!a.prerotated) {
+            float2 t = a.cs[(int64_t)pos * half + i];
+            c = t.x;
+            s = t.y;
+        }
+        if (hh < a.n_q_heads) {
+            int64_t o = ((int64_t)row * a.n_q_heads + hh) * a.d;
+            const T *src = (const T *)a.q + o;
+            T *dst = (T *)a.q_rot + o;
+            float x = ld_elem(src + i), y = ld_elem(src + half + i);
+            float xc = x * c, ys = y * s, yc = y * c, xs = x * s;
+            st_elem(dst + i, xc - ys);
+            st_elem(dst + half + i, yc + xs);
+        } else {
+            int h = hh - a.n_q_heads;
+            int64_t o = ((int64_t)row * a.n_kv + h) * a.d;
+            const T *ks = (const T *)a.k_new + o;
+            const T *vs = (const T *)a.v_new + o;
+            int64_t co = cache_row_off(a.cache, req, a.layer, h, pos, a.n_kv, a.d);
+            T *kd = (T *)a.cache.k + co;
+            T *vd = (T *)a.cache.v + co;
+            float x = ld_elem(ks + i), y = ld_elem(ks + half + i);
+            float xc = x * c, ys = y * s, yc = y * c, xs = x * s;
+            st_elem(kd + i, xc - ys);
+            st_elem(kd + half + i, yc + xs);
+            vd[i] = vs[i];
+            vd[half + i] = vs[half + i];
+        }
+    }
+}
+
+int launch_append(int dtype, const AppendArgs &a, void *stream)
+{
+    if (a.tot_q == 0) return 0;
+    int64_t total = (int64_t)a.tot_q * (a.n_q_heads + a.n_kv) * (a.d / 2);
+    unsigned blocks = (unsigned)((total + 255) / 256);
+    if (blocks > 65536u) blocks = 65536u;
+    if (dtype == 1) hipLaunchKernelGGL((append_kernel<bf16_t>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL((append_kernel<float>), dim3(blocks), dim3(256), 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// Generic attention: one wavefront per packed row, lanes own head_dim/64 columns
+// (head_dim <= 256), online softmax over the item's kv range in fp32.  Slow but
+// shape-agnostic: the fp32 path and any shape the MFMA kernel does not take.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void attention_generic_kernel(AttnArgs a)
+{
+    const AttnItem it = a.items[blockIdx.x];
+    const AttnGroup gp = a.groups[it.group];
+    const ReqMeta rq = a.reqs[gp.req];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int d = a.d;
+    const T *kc = (const T *)a.cache.k;
+    const T *vc = (const T *)a.cache.v;
+
+    for (int rr = wave; rr < gp.n_rows; rr += 4) {
+        const int m = gp.m0 + rr;
+        const int t = m / a.g, hq = gp.kv_head * a.g + m % a.g;
+        const T *qp = (const T *)a.q_rot + ((int64_t)(rq.q_off + t) * a.n_q_heads + hq) * d;
+        float q[4], o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int e = lane + 64 * j;
+            q[j] = e < d ? ld_elem(qp + e) : 0.f;
+            o[j] = 0.f;
+        }
+        float mx = -INFINITY, l = 0.f;
+        int vis_end = rq.ctx_len + t + 1;  // causal among the query rows, full over the prefix
+        int end = it.kv_end < vis_end ? it.kv_end : vis_end;
+        for (int u = it.kv_begin; u < end; ++u) {
+            int64_t off = cache_row_off(a.cache, gp.req, a.layer, gp.kv_head, u, a.n_kv, d);
+            float part = 0.f, v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                int e = lane + 64 * j;
+                float kk = e < d ? ld_elem(kc + off + e) : 0.f;
+                v[j] = e < d ? ld_elem(vc + off + e) : 0.f;
+                part += q[j] * kk;
+            }
+            float sc = wave_sum(part) * a.scale_log2e;
+            float mn = fmaxf(mx, sc);
+            float alpha = exp2f(mx - mn);  // exp2f(-inf) = 0 on the first row
+            float p = exp2f(sc - mn);
+            l = l * alpha + p;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[j] = o[j] * alpha + p * v[j];
+            mx = mn;
+        }
+        if (gp.n_splits == 1) {
+            T *op = (T *)a.out + ((int64_t)(rq.q_off + t) * a.n_q_heads + hq) * d;
+            float inv = 1.f / l;  // the row always sees itself, so l > 0
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                int e = lane + 64 * j;
+                if (e < d) st_elem(op + e, o[j] * inv);
+            }
+        } else {
+            float *pp = a.partials + (int64_t)(gp.part0 + it.split) * a.bm * (d + 2);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                int e = lane + 64 * j;
+                if (e < d) pp[(int64_t)rr * d + e] = o[j];
+            }
+            if (lane == 0) {
+                pp[(int64_t)a.bm * d + rr] = mx;
+                pp[(int64_t)a.bm * d + a.bm + rr] = l;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// K4.  Merge the splits of one group by log-sum-exp:
+//   m = max m_i;  l = sum l_i 2^(m_i - m);  O = sum O~_i 2^(m_i - m) / l.
+// A split that saw no visible row has m_i = -inf, l_i = 0 and contributes nothing.
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void combine_kernel(AttnArgs a)
+{
+    const AttnGroup gp = a.groups[blockIdx.x];
+    if (gp.n_splits <= 1) return;
+    const ReqMeta rq = a.reqs[gp.req];
+    const int d = a.d;
+    const int64_t slot = (int64_t)a.bm * (d + 2);
+    const float *base = a.partials + (int64_t)gp.part0 * slot;
+    for (int idx = threadIdx.x; idx < gp.n_rows * d; idx += blockDim.x) {
+        int rr = idx / d, e = idx % d;
+        float mx = -INFINITY;
+        for (int s = 0; s < gp.n_splits; ++s) mx = fmaxf(mx, base[s * slot + (int64_t)a.bm * d + rr]);
+        float l = 0.f, acc = 0.f;
+        for (int s = 0; s < gp.n_splits; ++s) {
+            float mi = base[s * slot + (int64_t)a.bm * d + rr];
+            float li = base[s * slot + (int64_t)a.bm * d + a.bm + rr];
+            float w = (mi == -INFINITY) ? 0.f : exp2f(mi - mx);
+            l += li * w;
+            acc += base[s * slot + (int64_t)rr * d + e] * w;
+        }
+        int m = gp.m0 + rr;
+        int t = m / a.g, hq = gp.kv_head * a.g + m % a.g;
+        T *op = (T *)a.out + ((int64_t)(rq.q_off + t) * a.n_q_heads + hq) * d;
+        st_elem(op + e, acc / l);
+    }
+}
+
+int launch_combine(int dtype, const AttnArgs &a, void *stream)
+{
+    if (a.n_groups == 0) return 0;
+    if (dtype == 1) hipLaunchKernelGGL((combine_kernel<bf16_t>), dim3(a.n_groups), dim3(256), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL((combine_kernel<float>), dim3(a.n_groups), dim3(256), 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+}
+
+int launch_attention_mfma(const AttnArgs &a, void *stream);  // kvp_attention_mfma.hip
+
+int launch_attention(int dtype, const AttnArgs &a, int kernel_kind, void *stream)
+{
+    if (a.n_items == 0) return 0;
+    if (kernel_kind == ATTN_MFMA) return launch_attention_mfma(a, stream);
+    if (dtype == 1) hipLaunchKernelGGL((attention_generic_kernel<bf16_t>), dim3(a.n_items), dim3(256), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL((attention_generic_kernel<float>), dim3(a.n_items), dim3(256), 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+}
+
+}  // namespace kvp

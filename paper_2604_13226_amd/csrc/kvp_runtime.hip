@@ -1,0 +1,701 @@
+// kvp_runtime.hip -- host runtime behind the C ABI: packet directory over the caller's
+// arena, the host-built cos/sin table, per-call plans (offsets Delta_j, gather tiles,
+// attention groups / split-KV items, block tables) and the kernel launches.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <string>
+#include <thread>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/kvp.h"
+#include "kvp_plan.h"
+
+using namespace kvp;
+
+namespace {
+
+constexpr uint64_t ALIGN = 256;
+inline uint64_t align_up(uint64_t x, uint64_t a = ALIGN) { return (x + a - 1) / a * a; }
+
+struct PacketRec {
+    int64_t elem_off;  // element offset of the blob in the arena
+    int32_t n_tokens;
+};
+
+// Ring of pinned-host / device twin buffers that carry one call's plan each.  A slot is
+// reused only after the work that read it has finished (event recorded behind it).
+struct PlanRing {
+    static constexpr int SLOTS = 8;
+    struct Slot {
+        char *host = nullptr;
+        char *dev = nullptr;
+        uint64_t cap = 0;
+        hipEvent_t ev = nullptr;
+        bool pending = false;
+    } slot[SLOTS];
+    int next = 0;
+    bool dry = false;
+
+    int acquire(uint64_t bytes, Slot **out)
+    {
+        Slot &s = slot[next];
+        next = (next + 1) % SLOTS;
+        if (dry) {
+            if (s.cap < bytes) {
+                free(s.host);
+                s.host = (char *)malloc(bytes);
+                s.cap = bytes;
+            }
+            *out = &s;
+            return 0;
+        }
+        if (s.pending) {
+            hipError_t e = hipEventSynchronize(s.ev);
+            if (e != hipSuccess) return (int)e;
+            s.pending = false;
+        }
+        if (!s.ev) {
+            hipError_t e = hipEventCreateWithFlags(&s.ev, hipEventDisableTiming);
+            if (e != hipSuccess) return (int)e;
+        }
+        if (s.cap < bytes) {
+            uint64_t cap = std::max<uint64_t>(align_up(bytes, 4096), 1 << 16);
+            if (s.host) (void)hipHostFree(s.host);
+            if (s.dev) (void)hipFree(s.dev);
+            s.host = s.dev = nullptr;
+            s.cap = 0;
+            hipError_t e = hipHostMalloc((void **)&s.host, cap, hipHostMallocDefault);
+            if (e != hipSuccess) return (int)e;
+            e = hipMalloc((void **)&s.dev, cap);
+            if (e != hipSuccess) return (int)e;
+            s.cap = cap;
+        }
+        *out = &s;
+        return 0;
+    }
+    void release()
+    {
+        for (auto &s : slot) {
+            if (dry) {
+                free(s.host);
+            } else {
+                if (s.pending) (void)hipEventSynchronize(s.ev);
+                if (s.host) (void)hipHostFree(s.host);
+                if (s.dev) (void)hipFree(s.dev);
+                if (s.ev) (void)hipEventDestroy(s.ev);
+            }
+            s = Slot();
+        }
+    }
+};
+
+thread_local std::string g_create_error;
+
+}  // namespace
+
+struct kvp_store {
+    kvp_config_t cfg;
+    std::vector<float> inv_freq;
+    std::unordered_map<int64_t, PacketRec> dir;
+    uint64_t used_bytes = 0;
+    float2 *cs_dev = nullptr;
+    PlanRing ring;
+    std::string err;
+    std::vector<int64_t> dbg_asm, dbg_attn;
+    bool dry = false;
+    int n_cu = 256;
+    int force_generic = 0;
+    int target_items = 0;  // 0: twice the CU count
+    size_t esize = 2;
+};
+
+namespace {
+
+int fail(kvp_store *s, int code, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (s) s->err = buf;
+    else g_create_error = buf;
+    return code;
+}
+
+int hip_fail(kvp_store *s, hipError_t e, const char *what)
+{
+    return fail(s, KVP_E_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HIP_TRY(s, call)                                          \
+    do {                                                          \
+        hipError_t e_ = (call);                                   \
+        if (e_ != hipSuccess) return hip_fail((s), e_, #call);    \
+    } while (0)
+
+bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+int ilog2(int x) { int s = 0; while ((1 << s) < x) ++s; return s; }
+
+// (cos, sin) of pos * theta_i for every position: double libm, rounded to fp32.
+void build_cos_sin(const std::vector<float> &inv_freq, int max_pos, std::vector<float2> &out)
+{
+    const int half = (int)inv_freq.size();
+    out.resize((size_t)max_pos * half);
+    unsigned hw = std::thread::hardware_concurrency();
+    int nt = (int)std::min<unsigned>(hw ? hw : 1, 16);
+    if ((int64_t)max_pos * half < (1 << 16)) nt = 1;
+    auto work = [&](int t) {
+        for (int p = t; p < max_pos; p += nt)
+            for (int i = 0; i < half; ++i) {
+                double a = (double)p * (double)inv_freq[i];
+                out[(size_t)p * half + i] = make_float2((float)cos(a), (float)sin(a));
+            }
+    };
+    if (nt == 1) { work(0); return; }
+    std::vector<std::thread> th;
+    for (int t = 0; t < nt; ++t) th.emplace_back(work, t);
+    for (auto &t : th) t.join();
+}
+
+struct CacheCheck {
+    int shift = 0;
+    int64_t cap_rows = 0;  // rows a request can hold
+};
+
+int check_cache(kvp_store *s, const kvp_cache_t *c, int n_req, CacheCheck &cc)
+{
+    if (!c) return fail(s, KVP_E_INVAL, "cache is null");
+    if (c->layout != KVP_CONTIG && c->layout != KVP_PAGED) return fail(s, KVP_E_INVAL, "unknown cache layout %d", c->layout);
+    if (!c->k || !c->v) return fail(s, KVP_E_INVAL, "cache k/v pointer is null");
+    if (((uintptr_t)c->k | (uintptr_t)c->v) & 15) return fail(s, KVP_E_INVAL, "cache k/v must be 16-byte aligned");
+    if (!c->ctx_len && n_req > 0) return fail(s, KVP_E_INVAL, "cache ctx_len is null");
+    if (c->layout == KVP_CONTIG) {
+        if (c->t_cap < 0) return fail(s, KVP_E_INVAL, "t_cap < 0");
+        cc.cap_rows = c->t_cap;
+    } else {
+        if (!is_pow2(c->block_size)) return fail(s, KVP_E_INVAL, "block_size must be a power of two");
+        if (c->n_blocks < 0 || c->max_blocks_per_req < 0) return fail(s, KVP_E_INVAL, "negative block counts");
+        if (!c->block_table && n_req > 0 && c->max_blocks_per_req > 0) return fail(s, KVP_E_INVAL, "block_table is null");
+        cc.shift = ilog2(c->block_size);
+        cc.cap_rows = (int64_t)c->max_blocks_per_req * c->block_size;
+    }
+    return 0;
+}
+
+// Copies the first n_blk[r] table entries of every request into a compact
+// [n_req][stride] table, checking the block ids.
+int compact_block_table(kvp_store *s, const kvp_cache_t *c, int n_req, const std::vector<int> &first_blk,
+                        const std::vector<int> &n_blk, int stride, int32_t *dst)
+{
+    for (int r = 0; r < n_req; ++r) {
+        const int32_t *row = c->block_table + (int64_t)r * c->max_blocks_per_req;
+        for (int b = 0; b < stride; ++b) dst[(int64_t)r * stride + b] = 0;
+        for (int b = first_blk[r]; b < n_blk[r]; ++b) {
+            if (row[b] < 0 || row[b] >= c->n_blocks)
+                return fail(s, KVP_E_INVAL, "block_table[%d][%d] = %d is outside [0, %d)", r, b, row[b], c->n_blocks);
+            dst[(int64_t)r * stride + b] = row[b];
+        }
+    }
+    return 0;
+}
+
+CacheView make_view(const kvp_store *s, const kvp_cache_t *c, int shift, const int32_t *bt_dev, int bt_stride)
+{
+    const kvp_config_t &g = s->cfg;
+    CacheView v;
+    v.k = c->k;
+    v.v = c->v;
+    v.block_table = bt_dev;
+    v.layout = c->layout;
+    v.t_cap = c->t_cap;
+    v.n_blocks = c->n_blocks;
+    v.block_shift = shift;
+    v.max_blocks = bt_stride;
+    if (c->layout == KVP_CONTIG) {
+        v.layer_stride = (int64_t)g.n_kv_heads * c->t_cap * g.head_dim;
+        v.req_stride = v.layer_stride * g.n_layers;
+    } else {
+        v.layer_stride = (int64_t)c->n_blocks * g.n_kv_heads * c->block_size * g.head_dim;
+        v.req_stride = 0;
+    }
+    return v;
+}
+
+// Sub-allocator over one plan slot.
+struct PlanWriter {
+    char *host, *dev;
+    uint64_t off = 0;
+    template <typename T> T *put(uint64_t n, const T **dev_ptr)
+    {
+        off = align_up(off, 64);
+        T *h = (T *)(host + off);
+        *dev_ptr = (const T *)(dev ? dev + off : host + off);
+        off += n * sizeof(T);
+        return h;
+    }
+};
+
+}  // namespace
+
+// =====================================================================================
+extern "C" {
+
+const char *kvp_version(void) { return "kvp 0.1 gfx950"; }
+
+const char *kvp_last_error(const kvp_store_t *store) { return store ? store->err.c_str() : g_create_error.c_str(); }
+
+uint64_t kvp_packet_bytes(const kvp_config_t *cfg, int32_t n_tokens)
+{
+    if (!cfg || n_tokens < 0) return 0;
+    uint64_t es = cfg->dtype == KVP_BF16 ? 2 : 4;
+    return align_up(2ull * cfg->n_layers * cfg->n_kv_heads * (uint64_t)n_tokens * cfg->head_dim * es);
+}
+
+int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
+{
+    if (!cfg || !out) return fail(nullptr, KVP_E_INVAL, "cfg or out is null");
+    if (cfg->n_layers < 1 || cfg->n_q_heads < 1 || cfg->n_kv_heads < 1)
+        return fail(nullptr, KVP_E_INVAL, "n_layers, n_q_heads, n_kv_heads must be >= 1");
+    if (cfg->n_q_heads % cfg->n_kv_heads) return fail(nullptr, KVP_E_INVAL, "n_q_heads must be a multiple of n_kv_heads");
+    if (cfg->head_dim < 2 || cfg->head_dim > 256 || (cfg->head_dim & 1))
+        return fail(nullptr, KVP_E_INVAL, "head_dim must be even and in [2, 256]");
+    if (cfg->dtype != KVP_F32 && cfg->dtype != KVP_BF16) return fail(nullptr, KVP_E_INVAL, "unknown dtype %d", cfg->dtype);
+    if (cfg->n_header < 0 || cfg->n_trailer < 0) return fail(nullptr, KVP_E_INVAL, "negative adapter length");
+    if (cfg->max_positions < 1 || cfg->max_positions > (1 << 22)) return fail(nullptr, KVP_E_INVAL, "max_positions must be in [1, 2^22]");
+    if (!cfg->inv_freq && !(cfg->rope_base > 0.0)) return fail(nullptr, KVP_E_INVAL, "rope_base must be positive");
+    const bool dry = cfg->device == KVP_DEVICE_NONE;
+    if (!dry) {
+        if (cfg->device < 0) return fail(nullptr, KVP_E_INVAL, "bad device %d", cfg->device);
+        if (!cfg->arena && cfg->arena_bytes) return fail(nullptr, KVP_E_INVAL, "arena is null");
+        if ((uintptr_t)cfg->arena & (ALIGN - 1)) return fail(nullptr, KVP_E_INVAL, "arena must be 256-byte aligned");
+    }
+    kvp_store *s = new kvp_store();
+    s->cfg = *cfg;
+    s->dry = dry;
+    s->ring.dry = dry;
+    s->esize = cfg->dtype == KVP_BF16 ? 2 : 4;
+    const int half = cfg->head_dim / 2;
+    s->inv_freq.resize(half);
+    for (int i = 0; i < half; ++i)
+        s->inv_freq[i] = cfg->inv_freq ? cfg->inv_freq[i]
+                                       : (float)pow(cfg->rope_base, -2.0 * (double)i / (double)cfg->head_dim);
+    s->cfg.inv_freq = nullptr;
+    const char *fg = getenv("KVP_FORCE_GENERIC_ATTENTION");
+    s->force_generic = fg && fg[0] == '1';
+    const char *ti = getenv("KVP_ATTN_TARGET_ITEMS");  // test knob: how finely split-KV cuts
+    if (ti && atoi(ti) > 0) s->target_items = std::min(atoi(ti), 1 << 16);
+    if (!dry) {
+        hipError_t e = hipSetDevice(cfg->device);
+        if (e == hipSuccess) {
+            hipDeviceProp_t prop;
+            if (hipGetDeviceProperties(&prop, cfg->device) == hipSuccess && prop.multiProcessorCount > 0)
+                s->n_cu = prop.multiProcessorCount;
+            std::vector<float2> cs;
+            build_cos_sin(s->inv_freq, cfg->max_positions, cs);
+            e = hipMalloc((void **)&s->cs_dev, cs.size() * sizeof(float2));
+            if (e == hipSuccess) e = hipMemcpy(s->cs_dev, cs.data(), cs.size() * sizeof(float2), hipMemcpyHostToDevice);
+        }
+        if (e != hipSuccess) {
+            int rc = hip_fail(nullptr, e, "store create");
+            if (s->cs_dev) (void)hipFree(s->cs_dev);
+            delete s;
+            return rc;
+        }
+    }
+    *out = s;
+    return KVP_OK;
+}
+
+int kvp_store_destroy(kvp_store_t *s)
+{
+    if (!s) return KVP_E_INVAL;
+    if (!s->dry) {
+        (void)hipSetDevice(s->cfg.device);
+        s->ring.release();
+        if (s->cs_dev) (void)hipFree(s->cs_dev);
+    } else {
+        s->ring.release();
+    }
+    delete s;
+    return KVP_OK;
+}
+
+int kvp_store_put(kvp_store_t *s, int64_t packet_id, int32_t n_tokens, const void *k, const void *v,
+                  int32_t src_on_device, void *hip_stream)
+{
+    if (!s) return KVP_E_INVAL;
+    if (packet_id < 0) return fail(s, KVP_E_INVAL, "packet id %lld < 0", (long long)packet_id);
+    if (n_tokens < 1) return fail(s, KVP_E_INVAL, "n_tokens %d < 1", n_tokens);
+    if (!s->dry && (!k || !v)) return fail(s, KVP_E_INVAL, "k or v is null");
+    if (s->dir.count(packet_id)) return fail(s, KVP_E_EXISTS, "packet %lld already stored", (long long)packet_id);
+    const kvp_config_t &g = s->cfg;
+    const uint64_t half_bytes = (uint64_t)g.n_layers * g.n_kv_heads * (uint64_t)n_tokens * g.head_dim * s->esize;
+    const uint64_t need = align_up(2 * half_bytes);
+    if (s->used_bytes + need > g.arena_bytes)
+        return fail(s, KVP_E_NOSPACE, "arena full: %llu used + %llu needed > %llu", (unsigned long long)s->used_bytes,
+                    (unsigned long long)need, (unsigned long long)g.arena_bytes);
+    if (!s->dry) {
+        HIP_TRY(s, hipSetDevice(g.device));
+        char *dst = (char *)g.arena + s->used_bytes;
+        hipMemcpyKind kind = src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+        hipStream_t st = (hipStream_t)hip_stream;
+        HIP_TRY(s, hipMemcpyAsync(dst, k, half_bytes, kind, st));
+        HIP_TRY(s, hipMemcpyAsync(dst + half_bytes, v, half_bytes, kind, st));
+        if (!src_on_device) HIP_TRY(s, hipStreamSynchronize(st));  // host buffers may be reused on return
+    }
+    s->dir[packet_id] = PacketRec{(int64_t)(s->used_bytes / s->esize), n_tokens};
+    s->used_bytes += need;
+    return KVP_OK;
+}
+
+int32_t kvp_store_packet_len(const kvp_store_t *s, int64_t packet_id)
+{
+    if (!s) return KVP_E_INVAL;
+    auto it = s->dir.find(packet_id);
+    return it == s->dir.end() ? KVP_E_NOTFOUND : it->second.n_tokens;
+}
+
+uint64_t kvp_store_bytes_used(const kvp_store_t *s) { return s ? s->used_bytes : 0; }
+
+// -------------------------------------------------------------------------------------
+int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32_t layer_begin,
+                 int32_t layer_end, kvp_cache_t *cache, void *hip_stream)
+{
+    if (!s) return KVP_E_INVAL;
+    const kvp_config_t &g = s->cfg;
+    if (n_req < 0 || (n_req > 0 && !reqs)) return fail(s, KVP_E_INVAL, "bad request list");
+    if (layer_begin < 0 || layer_end > g.n_layers || layer_begin > layer_end)
+        return fail(s, KVP_E_INVAL, "layer range [%d, %d) outside [0, %d]", layer_begin, layer_end, g.n_layers);
+    CacheCheck cc;
+    int rc = check_cache(s, cache, n_req, cc);
+    if (rc) return rc;
+
+    // offsets Delta_j (Sec. 4.2.1 step 4: realign, then concatenate) and gather tiles
+    std::vector<AsmTile> tiles;
+    std::vector<int> ctx(n_req), first_blk(n_req, 0), n_blk(n_req, 0);
+    for (int r = 0; r < n_req; ++r) {
+        const kvp_request_t &q = reqs[r];
+        if (q.k < 0 || (q.k > 0 && !q.packet_ids)) return fail(s, KVP_E_INVAL, "request %d: bad packet list", r);
+        if (q.base_pos < 0) return fail(s, KVP_E_INVAL, "request %d: base_pos %d < 0", r, q.base_pos);
+        int64_t pos = q.base_pos;
+        for (int j = 0; j < q.k; ++j) {
+            auto it = s->dir.find(q.packet_ids[j]);
+            if (it == s->dir.end()) return fail(s, KVP_E_NOTFOUND, "request %d: packet %lld not in the store", r, (long long)q.packet_ids[j]);
+            const PacketRec &p = it->second;
+            if (pos + p.n_tokens > g.max_positions)
+                return fail(s, KVP_E_CAPACITY, "request %d: context exceeds max_positions %d", r, g.max_positions);
+            for (int t0 = 0; t0 < p.n_tokens; t0 += ASM_TILE_ROWS) {
+                AsmTile t;
+                t.src_base = p.elem_off;
+                t.n_pkt = p.n_tokens;
+                t.tok0 = t0;
+                t.n_tok = std::min(ASM_TILE_ROWS, p.n_tokens - t0);
+                t.dst_row = (int32_t)pos + t0;
+                t.pos = (int32_t)pos;
+                t.req = r;
+                tiles.push_back(t);
+            }
+            pos += p.n_tokens;
+        }
+        if (pos > cc.cap_rows) return fail(s, KVP_E_CAPACITY, "request %d: %lld rows do not fit the cache (%lld)", r, (long long)pos, (long long)cc.cap_rows);
+        ctx[r] = (int)pos;
+        if (cache->layout == KVP_PAGED && pos > q.base_pos) {
+            first_blk[r] = q.base_pos >> cc.shift;
+            n_blk[r] = (int)((pos - 1) >> cc.shift) + 1;
+        }
+    }
+    int bt_stride = 0;
+    for (int r = 0; r < n_req; ++r) bt_stride = std::max(bt_stride, n_blk[r]);
+
+    const int n_layers_launch = layer_end - layer_begin;
+    const uint64_t bytes = align_up(tiles.size() * sizeof(AsmTile), 64) + (uint64_t)n_req * bt_stride * 4 + 256;
+    PlanRing::Slot *slot = nullptr;
+    if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
+    int hrc = s->ring.acquire(bytes, &slot);
+    if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
+    PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
+    const AsmTile *tiles_dev = nullptr;
+    const int32_t *bt_dev = nullptr;
+    AsmTile *th = w.put<AsmTile>(tiles.size(), &tiles_dev);
+    if (!tiles.empty()) memcpy(th, tiles.data(), tiles.size() * sizeof(AsmTile));
+    if (cache->layout == KVP_PAGED && bt_stride > 0) {
+        int32_t *bh = w.put<int32_t>((uint64_t)n_req * bt_stride, &bt_dev);
+        rc = compact_block_table(s, cache, n_req, first_blk, n_blk, bt_stride, bh);
+        if (rc) return rc;
+    }
+
+    s->dbg_asm.clear();
+    s->dbg_asm.push_back((int64_t)tiles.size());
+    for (const AsmTile &t : tiles) {
+        int64_t row[8] = {t.src_base, t.n_pkt, t.tok0, t.n_tok, t.dst_row, t.pos, t.req, 0};
+        s->dbg_asm.insert(s->dbg_asm.end(), row, row + 8);
+    }
+
+    if (!s->dry && !tiles.empty() && n_layers_launch > 0) {
+        hipStream_t st = (hipStream_t)hip_stream;
+        HIP_TRY(s, hipMemcpyAsync(slot->dev, slot->host, w.off, hipMemcpyHostToDevice, st));
+        AsmArgs a;
+        a.arena = g.arena;
+        a.cs = s->cs_dev;
+        a.tiles = tiles_dev;
+        a.cache = make_view(s, cache, cc.shift, bt_dev, bt_stride);
+        a.n_tiles = (int)tiles.size();
+        a.layer_begin = layer_begin;
+        a.n_layers_total = g.n_layers;
+        a.n_kv = g.n_kv_heads;
+        a.d = g.head_dim;
+        int e = launch_assemble(g.dtype, a, n_layers_launch, hip_stream);
+        if (e) return hip_fail(s, (hipError_t)e, "assemble launch");
+        HIP_TRY(s, hipEventRecord(slot->ev, st));
+        slot->pending = true;
+    }
+    for (int r = 0; r < n_req; ++r) cache->ctx_len[r] = ctx[r];
+    return KVP_OK;
+}
+
+// -------------------------------------------------------------------------------------
+namespace {
+
+struct PrefillPlan {
+    int kind = ATTN_GENERIC, bm = 8, bn = 64;
+    std::vector<ReqMeta> reqs;
+    std::vector<int32_t> row_req;
+    std::vector<AttnGroup> groups;
+    std::vector<AttnItem> items;
+    int n_slots = 0;
+    bool any_split = false;
+};
+
+constexpr int MFMA_BM = 128;
+constexpr int GENERIC_BM = 8;
+constexpr int MAX_SPLITS = 64;
+
+int target_items(const kvp_store *s) { return s->target_items > 0 ? s->target_items : 2 * s->n_cu; }
+
+// Groups of packed rows and their split-KV items.  Every group of a request gets the same
+// split length (a multiple of bn rows), chosen so the launch has about target_items work
+// items; a group's kv range stops at the last row any of its query rows may see.
+void plan_prefill(const kvp_store *s, int n_req, const int32_t *ctx_len, const int32_t *q_off, PrefillPlan &p)
+{
+    const kvp_config_t &g = s->cfg;
+    const int gq = g.n_q_heads / g.n_kv_heads;
+    const bool mfma = g.dtype == KVP_BF16 && g.head_dim == 128 && !s->force_generic;
+    p.kind = mfma ? ATTN_MFMA : ATTN_GENERIC;
+    p.bm = mfma ? MFMA_BM : GENERIC_BM;
+    const int min_split = mfma ? 256 : 64;
+    p.reqs.resize(n_req);
+    int64_t n_groups = 0;
+    for (int r = 0; r < n_req; ++r) {
+        int n_q = q_off[r + 1] - q_off[r];
+        p.reqs[r] = ReqMeta{ctx_len[r], q_off[r], n_q, 0};
+        for (int t = 0; t < n_q; ++t) p.row_req.push_back(r);
+        n_groups += (int64_t)g.n_kv_heads * (((int64_t)n_q * gq + p.bm - 1) / p.bm);
+    }
+    if (n_groups == 0) return;
+    int want = (int)std::min<int64_t>(MAX_SPLITS, (target_items(s) + n_groups - 1) / n_groups);
+    if (want < 1) want = 1;
+    for (int r = 0; r < n_req; ++r) {
+        const ReqMeta &rq = p.reqs[r];
+        if (rq.n_q == 0) continue;
+        const int total = rq.ctx_len + rq.n_q;
+        int split_len = (total + want - 1) / want;
+        split_len = std::max(split_len, min_split);
+        split_len = (split_len + p.bn - 1) / p.bn * p.bn;
+        const int M = rq.n_q * gq;
+        for (int h = 0; h < g.n_kv_heads; ++h)
+            for (int m0 = 0; m0 < M; m0 += p.bm) {
+                AttnGroup gp;
+                gp.req = r;
+                gp.kv_head = h;
+                gp.m0 = m0;
+                gp.n_rows = std::min(p.bm, M - m0);
+                const int t_last = (m0 + gp.n_rows - 1) / gq;
+                const int vis = rq.ctx_len + t_last + 1;
+                gp.n_splits = (vis + split_len - 1) / split_len;
+                gp.part0 = p.n_slots;
+                gp.pad0 = gp.pad1 = 0;
+                if (gp.n_splits > 1) {
+                    p.n_slots += gp.n_splits;
+                    p.any_split = true;
+                }
+                for (int sp = 0; sp < gp.n_splits; ++sp)
+                    p.items.push_back(AttnItem{(int)p.groups.size(), sp, sp * split_len, std::min(vis, (sp + 1) * split_len)});
+                p.groups.push_back(gp);
+            }
+    }
+}
+
+uint64_t q_rot_bytes(const kvp_store *s, int64_t tot_q)
+{
+    return align_up((uint64_t)tot_q * s->cfg.n_q_heads * s->cfg.head_dim * s->esize);
+}
+
+}  // namespace
+
+uint64_t kvp_prefill_workspace_bytes(const kvp_store_t *s, int32_t n_req, int32_t max_tot_q, int32_t max_ctx)
+{
+    if (!s || n_req < 0 || max_tot_q < 0 || max_ctx < 0) return 0;
+    const kvp_config_t &g = s->cfg;
+    const int gq = g.n_q_heads / g.n_kv_heads;
+    const bool mfma = g.dtype == KVP_BF16 && g.head_dim == 128 && !s->force_generic;
+    const int bm = mfma ? MFMA_BM : GENERIC_BM;
+    // groups <= Hkv * (rows / bm + one ragged block per request); every group has at most
+    // ceil(target / groups) <= target / groups + 1 splits (and never more than MAX_SPLITS)
+    const uint64_t groups = (uint64_t)g.n_kv_heads * ((uint64_t)max_tot_q * gq / bm + (uint64_t)n_req);
+    const uint64_t slots = std::min<uint64_t>((uint64_t)target_items(s) + 2 * groups, groups * MAX_SPLITS);
+    (void)max_ctx;
+    return q_rot_bytes(s, max_tot_q) + slots * bm * (g.head_dim + 2) * sizeof(float) + ALIGN;
+}
+
+int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const void *q, const void *k_new,
+                      const void *v_new, const int32_t *q_offsets, int32_t n_req, uint32_t flags, void *workspace,
+                      uint64_t workspace_bytes, void *out, void *hip_stream)
+{
+    if (!s) return KVP_E_INVAL;
+    const kvp_config_t &g = s->cfg;
+    if (n_req < 0 || !q_offsets) return fail(s, KVP_E_INVAL, "bad request count or q_offsets is null");
+    if (layer < 0 || layer >= g.n_layers) return fail(s, KVP_E_INVAL, "layer %d outside [0, %d)", layer, g.n_layers);
+    if (flags & ~KVP_PREROTATED) return fail(s, KVP_E_INVAL, "unknown flags 0x%x", flags);
+    CacheCheck cc;
+    int rc = check_cache(s, cache, n_req, cc);
+    if (rc) return rc;
+    if (q_offsets[0] != 0) return fail(s, KVP_E_INVAL, "q_offsets[0] must be 0");
+    std::vector<int> first_blk(n_req, 0), n_blk(n_req, 0);
+    for (int r = 0; r < n_req; ++r) {
+        int n_q = q_offsets[r + 1] - q_offsets[r];
+        if (n_q < 0) return fail(s, KVP_E_INVAL, "q_offsets is not non-decreasing at %d", r);
+        int c = cache->ctx_len[r];
+        if (c < 0) return fail(s, KVP_E_INVAL, "request %d: ctx_len %d < 0", r, c);
+        int64_t total = (int64_t)c + n_q;
+        if (total > g.max_positions) return fail(s, KVP_E_CAPACITY, "request %d: %lld rows exceed max_positions %d", r, (long long)total, g.max_positions);
+        if (total > cc.cap_rows) return fail(s, KVP_E_CAPACITY, "request %d: %lld rows do not fit the cache (%lld)", r, (long long)total, (long long)cc.cap_rows);
+        if (cache->layout == KVP_PAGED && n_q > 0) n_blk[r] = (int)((total - 1) >> cc.shift) + 1;
+    }
+    const int tot_q = q_offsets[n_req];
+    if (tot_q > 0 && !s->dry) {
+        if (!q || !k_new || !v_new || !out) return fail(s, KVP_E_INVAL, "q, k_new, v_new or out is null");
+        if (((uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)out) & 15)
+            return fail(s, KVP_E_INVAL, "q, k_new, v_new, out must be 16-byte aligned");
+    }
+
+    PrefillPlan p;
+    plan_prefill(s, n_req, cache->ctx_len, q_offsets, p);
+    const uint64_t qrb = q_rot_bytes(s, tot_q);
+    const uint64_t need = qrb + (uint64_t)p.n_slots * p.bm * (g.head_dim + 2) * sizeof(float);
+    if (tot_q > 0) {
+        if (!s->dry && !workspace) return fail(s, KVP_E_INVAL, "workspace is null");
+        if ((uintptr_t)workspace & (ALIGN - 1)) return fail(s, KVP_E_INVAL, "workspace must be 256-byte aligned");
+        if (workspace_bytes < need)
+            return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)need);
+    }
+    int bt_stride = 0;
+    for (int r = 0; r < n_req; ++r) bt_stride = std::max(bt_stride, n_blk[r]);
+
+    const uint64_t bytes = p.reqs.size() * sizeof(ReqMeta) + p.row_req.size() * 4 + p.groups.size() * sizeof(AttnGroup) +
+                           p.items.size() * sizeof(AttnItem) + (uint64_t)n_req * bt_stride * 4 + 6 * 64;
+    if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
+    PlanRing::Slot *slot = nullptr;
+    int hrc = s->ring.acquire(bytes, &slot);
+    if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
+    PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
+    const ReqMeta *reqs_dev = nullptr;
+    const int32_t *row_req_dev = nullptr, *bt_dev = nullptr;
+    const AttnGroup *groups_dev = nullptr;
+    const AttnItem *items_dev = nullptr;
+    ReqMeta *rh = w.put<ReqMeta>(p.reqs.size(), &reqs_dev);
+    if (!p.reqs.empty()) memcpy(rh, p.reqs.data(), p.reqs.size() * sizeof(ReqMeta));
+    int32_t *rr = w.put<int32_t>(p.row_req.size(), &row_req_dev);
+    if (!p.row_req.empty()) memcpy(rr, p.row_req.data(), p.row_req.size() * 4);
+    AttnGroup *gh = w.put<AttnGroup>(p.groups.size(), &groups_dev);
+    if (!p.groups.empty()) memcpy(gh, p.groups.data(), p.groups.size() * sizeof(AttnGroup));
+    AttnItem *ih = w.put<AttnItem>(p.items.size(), &items_dev);
+    if (!p.items.empty()) memcpy(ih, p.items.data(), p.items.size() * sizeof(AttnItem));
+    if (cache->layout == KVP_PAGED && bt_stride > 0) {
+        int32_t *bh = w.put<int32_t>((uint64_t)n_req * bt_stride, &bt_dev);
+        rc = compact_block_table(s, cache, n_req, first_blk, n_blk, bt_stride, bh);
+        if (rc) return rc;
+    }
+
+    s->dbg_attn.clear();
+    {
+        int64_t head[6] = {p.kind, p.bm, (int64_t)p.groups.size(), (int64_t)p.items.size(), p.n_slots, (int64_t)need};
+        s->dbg_attn.insert(s->dbg_attn.end(), head, head + 6);
+        for (const AttnGroup &x : p.groups) {
+            int64_t row[6] = {x.req, x.kv_head, x.m0, x.n_rows, x.part0, x.n_splits};
+            s->dbg_attn.insert(s->dbg_attn.end(), row, row + 6);
+        }
+        for (const AttnItem &x : p.items) {
+            int64_t row[4] = {x.group, x.split, x.kv_begin, x.kv_end};
+            s->dbg_attn.insert(s->dbg_attn.end(), row, row + 4);
+        }
+    }
+
+    if (s->dry || tot_q == 0) return KVP_OK;
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    HIP_TRY(s, hipMemcpyAsync(slot->dev, slot->host, w.off, hipMemcpyHostToDevice, st));
+    CacheView view = make_view(s, cache, cc.shift, bt_dev, bt_stride);
+
+    AppendArgs ap;
+    ap.q = q;
+    ap.k_new = k_new;
+    ap.v_new = v_new;
+    ap.q_rot = workspace;
+    ap.cs = s->cs_dev;
+    ap.cache = view;
+    ap.reqs = reqs_dev;
+    ap.row_req = row_req_dev;
+    ap.tot_q = tot_q;
+    ap.layer = layer;
+    ap.n_q_heads = g.n_q_heads;
+    ap.n_kv = g.n_kv_heads;
+    ap.d = g.head_dim;
+    ap.prerotated = (flags & KVP_PREROTATED) ? 1 : 0;
+    int e = launch_append(g.dtype, ap, hip_stream);
+    if (e) return hip_fail(s, (hipError_t)e, "append launch");
+
+    AttnArgs at;
+    at.q_rot = workspace;
+    at.cache = view;
+    at.reqs = reqs_dev;
+    at.groups = groups_dev;
+    at.items = items_dev;
+    at.partials = (float *)((char *)workspace + qrb);
+    at.out = out;
+    at.n_items = (int)p.items.size();
+    at.n_groups = (int)p.groups.size();
+    at.layer = layer;
+    at.n_q_heads = g.n_q_heads;
+    at.n_kv = g.n_kv_heads;
+    at.d = g.head_dim;
+    at.bm = p.bm;
+    at.g = g.n_q_heads / g.n_kv_heads;
+    at.scale_log2e = (float)(1.4426950408889634 / sqrt((double)g.head_dim));
+    e = launch_attention(g.dtype, at, p.kind, hip_stream);
+    if (e) return hip_fail(s, (hipError_t)e, "attention launch");
+    if (p.any_split) {
+        e = launch_combine(g.dtype, at, hip_stream);
+        if (e) return hip_fail(s, (hipError_t)e, "combine launch");
+    }
+    HIP_TRY(s, hipEventRecord(slot->ev, st));
+    slot->pending = true;
+    return KVP_OK;
+}
+
+int64_t kvp_debug_last_plan(const kvp_store_t *s, int32_t which, int64_t *out, int64_t cap)
+{
+    if (!s) return KVP_E_INVAL;
+    const std::vector<int64_t> &v = which == 0 ? s->dbg_asm : s->dbg_attn;
+    for (int64_t i = 0; i < (int64_t)v.size() && i < cap && out; ++i) out[i] = v[i];
+    return (int64_t)v.size();
+}
+
+}  // extern "C"

@@ -1,0 +1,227 @@
+"""CPU-only tests of the C-ABI library: it loads, exports what include/kvp.h declares, and
+its host logic (directory, offsets Delta_j, gather tiles, split-KV plan, every error code)
+is right.  A store created with KVP_DEVICE_NONE plans and validates but launches nothing."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2604_13226_amd as kvp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def dry_store(**kw):
+    a = dict(n_layers=2, n_q_heads=8, n_kv_heads=2, head_dim=128, dtype="bf16", rope_base=5.0e5,
+             max_positions=1 << 16, arena_bytes=1 << 30, n_header=8, n_trailer=8,
+             device=kvp.KVP_DEVICE_NONE)
+    a.update(kw)
+    return kvp.kvp_store_create(**a)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "kvp.h")).read()
+    declared = set(re.findall(r"\b(kvp_[a-z_]+)\s*\(", header))
+    declared -= {"kvp_prefill_workspace_bytes()"}
+    assert {"kvp_store_put", "kvp_assemble", "kvp_query_prefill"} <= declared
+    lib = kvp.load()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert set(kvp.binding.EXPORTS) == declared
+    assert kvp.kvp_version().startswith("kvp ")
+
+
+@pytest.mark.parametrize("bad", [
+    dict(head_dim=127), dict(head_dim=0), dict(head_dim=512), dict(n_q_heads=7),
+    dict(n_layers=0), dict(dtype_code=5), dict(max_positions=0), dict(rope_base=-1.0),
+    dict(n_header=-1),
+])
+def test_create_rejects_bad_config(bad):
+    bad = dict(bad)
+    code = bad.pop("dtype_code", None)
+    if code is not None:
+        kvp.binding._dtype_code  # noqa
+        orig = kvp.binding._dtype_code
+        kvp.binding._dtype_code = lambda _: code
+        try:
+            with pytest.raises(kvp.KvpError) as e:
+                dry_store()
+        finally:
+            kvp.binding._dtype_code = orig
+    else:
+        with pytest.raises(kvp.KvpError) as e:
+            dry_store(**bad)
+    assert e.value.code == kvp.KVP_E_INVAL
+    assert str(e.value)
+
+
+def test_directory_and_arena_accounting():
+    s = dry_store(arena_bytes=3 * 2 * 2 * 2 * 100 * 128 * 2)
+    per100 = 2 * 2 * 2 * 100 * 128 * 2
+    assert kvp.kvp_packet_bytes(s, 100) == per100
+    assert kvp.kvp_packet_bytes(s, 1) == 2 * 2 * 2 * 128 * 2
+    kvp.kvp_store_put(s, 7, None, None, n_tokens=100)
+    assert kvp.kvp_store_packet_len(s, 7) == 100
+    assert kvp.kvp_store_packet_len(s, 8) == kvp.KVP_E_NOTFOUND
+    assert kvp.kvp_store_bytes_used(s) == per100
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_store_put(s, 7, None, None, n_tokens=5)       # immutable: no overwrite
+    assert e.value.code == kvp.KVP_E_EXISTS
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_store_put(s, -1, None, None, n_tokens=5)
+    assert e.value.code == kvp.KVP_E_INVAL
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_store_put(s, 9, None, None, n_tokens=0)
+    assert e.value.code == kvp.KVP_E_INVAL
+    kvp.kvp_store_put(s, 9, None, None, n_tokens=200)
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_store_put(s, 10, None, None, n_tokens=1)
+    assert e.value.code == kvp.KVP_E_NOSPACE
+    assert kvp.kvp_store_bytes_used(s) == 3 * per100          # failed puts changed nothing
+    assert kvp.kvp_store_packet_len(s, 10) == kvp.KVP_E_NOTFOUND
+
+
+def _tiles(s):
+    p = kvp.kvp_debug_last_plan(s, 0)
+    n = int(p[0])
+    return p[1:].reshape(n, 8)
+
+
+def test_assemble_plan_offsets_and_tiles():
+    s = dry_store()
+    lens = {0: 72, 1: 1, 2: 64, 3: 130}
+    for pid, n in lens.items():
+        kvp.kvp_store_put(s, pid, None, None, n_tokens=n)
+    cache = kvp.Cache.dry(2, t_cap=600)
+    kvp.kvp_assemble(s, [([3, 1, 0, 3], 0), ([2], 10)], cache)
+    assert list(cache.ctx_len[:2]) == [130 + 1 + 72 + 130, 74]
+    t = _tiles(s)
+    # request 0: Delta = 0, 130, 131, 203 (every adapter/document row occupies a position)
+    want_pos = {0: [0, 130, 131, 203], 1: [10]}
+    for r in (0, 1):
+        rows = t[t[:, 6] == r]
+        assert sorted(set(rows[:, 5])) == want_pos[r]
+        covered = np.zeros(int(cache.ctx_len[r]), int)
+        for src, n_pkt, tok0, n_tok, dst, pos, _, _ in rows:
+            assert 1 <= n_tok <= 64 and tok0 + n_tok <= n_pkt
+            assert dst == pos + tok0
+            covered[dst:dst + n_tok] += 1
+        base = 0 if r == 0 else 10
+        assert np.all(covered[base:] == 1) and not covered[:base].any()
+    # blobs are 256-byte aligned and disjoint
+    starts = sorted(set(int(x) for x in t[:, 0]))
+    assert all((x * 2) % 256 == 0 for x in starts)
+
+
+def test_assemble_errors_leave_ctx_len_alone():
+    s = dry_store(max_positions=300)
+    kvp.kvp_store_put(s, 0, None, None, n_tokens=100)
+    cache = kvp.Cache.dry(1, t_cap=150)
+    cache.ctx_len[0] = -7
+    for reqs, code in [([([5], 0)], kvp.KVP_E_NOTFOUND), ([([0, 0], 0)], kvp.KVP_E_CAPACITY),
+                       ([([0], -1)], kvp.KVP_E_INVAL)]:
+        with pytest.raises(kvp.KvpError) as e:
+            kvp.kvp_assemble(s, reqs, cache)
+        assert e.value.code == code and cache.ctx_len[0] == -7
+    big = kvp.Cache.dry(1, t_cap=1000)
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_assemble(s, [([0, 0, 0, 0], 0)], big)        # 400 rows > max_positions 300
+    assert e.value.code == kvp.KVP_E_CAPACITY
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_assemble(s, [([0], 0)], big, layer_begin=1, layer_end=3)
+    assert e.value.code == kvp.KVP_E_INVAL
+    kvp.kvp_assemble(s, [([], 0)], big)                       # k = 0 is legal
+    assert big.ctx_len[0] == 0 and len(_tiles(s)) == 0
+
+
+def test_paged_block_table_is_validated():
+    s = dry_store()
+    kvp.kvp_store_put(s, 0, None, None, n_tokens=40)
+    table = np.array([[3, 1, 2, 0]], np.int32)
+    cache = kvp.Cache.dry(1, layout=kvp.KVP_PAGED, n_blocks=4, block_table=table)
+    kvp.kvp_assemble(s, [([0], 0)], cache)
+    assert cache.ctx_len[0] == 40
+    with pytest.raises(kvp.KvpError) as e:                    # 80 rows need 5 blocks, table has 4
+        kvp.kvp_assemble(s, [([0, 0], 0)], cache)
+    assert e.value.code == kvp.KVP_E_CAPACITY
+    bad = kvp.Cache.dry(1, layout=kvp.KVP_PAGED, n_blocks=4, block_table=np.array([[0, 9, 1, 2]], np.int32))
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_assemble(s, [([0], 0)], bad)
+    assert e.value.code == kvp.KVP_E_INVAL
+    odd = kvp.Cache.dry(1, layout=kvp.KVP_PAGED, n_blocks=4, block_table=table, block_size=12)
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_assemble(s, [([0], 0)], odd)
+    assert e.value.code == kvp.KVP_E_INVAL
+
+
+def _attn_plan(s):
+    p = kvp.kvp_debug_last_plan(s, 1)
+    kind, bm, ng, ni, slots, need = (int(x) for x in p[:6])
+    groups = p[6:6 + 6 * ng].reshape(ng, 6)
+    items = p[6 + 6 * ng:].reshape(ni, 4)
+    return kind, bm, groups, items, slots, need
+
+
+@pytest.mark.parametrize("cfg", [
+    dict(n_q_heads=32, n_kv_heads=8, ctx=[8192], n_q=[32]),
+    dict(n_q_heads=28, n_kv_heads=4, ctx=[6720], n_q=[64]),
+    dict(n_q_heads=32, n_kv_heads=8, ctx=[16896] * 8, n_q=[128] * 8),
+    dict(n_q_heads=32, n_kv_heads=8, ctx=[0, 5, 1000, 77], n_q=[16, 0, 255, 1]),
+    dict(n_q_heads=4, n_kv_heads=2, ctx=[144], n_q=[16], head_dim=64, dtype="f32"),
+])
+def test_prefill_plan_covers_every_row_and_kv_exactly_once(cfg):
+    cfg = dict(cfg)
+    ctx, n_q = cfg.pop("ctx"), cfg.pop("n_q")
+    s = dry_store(**cfg)
+    g = s.cfg.n_q_heads // s.cfg.n_kv_heads
+    n_req = len(ctx)
+    cache = kvp.Cache.dry(n_req, t_cap=max(c + q for c, q in zip(ctx, n_q)))
+    cache.ctx_len[:n_req] = ctx
+    q_off = np.concatenate([[0], np.cumsum(n_q)]).astype(np.int32)
+    kvp.kvp_query_prefill(s, cache, 0, None, None, None, q_off, None, None)
+    kind, bm, groups, items, slots, need = _attn_plan(s)
+    assert kind == (1 if (s.cfg.dtype == kvp.KVP_BF16 and s.cfg.head_dim == 128) else 0)
+    seen = {}
+    for gi, (r, h, m0, n_rows, part0, n_splits) in enumerate(groups):
+        assert 1 <= n_rows <= bm and m0 % bm == 0
+        rng = sorted((int(b), int(e)) for g_, sp, b, e in items if g_ == gi)
+        assert len(rng) == n_splits
+        t_last = (m0 + n_rows - 1) // g
+        assert rng[0][0] == 0 and rng[-1][1] == ctx[r] + t_last + 1     # causal bound of the group
+        for (b0, e0), (b1, e1) in zip(rng, rng[1:]):
+            assert e0 == b1 and b0 < e0
+        for m in range(m0, m0 + n_rows):
+            assert (r, h, m) not in seen
+            seen[(r, h, m)] = 1
+    for r in range(n_req):
+        for h in range(s.cfg.n_kv_heads):
+            for m in range(n_q[r] * g):
+                assert (r, h, m) in seen
+    assert len(seen) == sum(n_q) * s.cfg.n_q_heads
+    # split groups own disjoint partial slots; the workspace bound covers the need
+    used = []
+    for r, h, m0, n_rows, part0, n_splits in groups:
+        if n_splits > 1:
+            used += list(range(part0, part0 + n_splits))
+    assert sorted(used) == list(range(slots))
+    bound = kvp.kvp_prefill_workspace_bytes(s, n_req, int(q_off[-1]), max(c + q for c, q in zip(ctx, n_q)))
+    assert bound >= need
+
+
+def test_prefill_errors():
+    s = dry_store(max_positions=1000)
+    cache = kvp.Cache.dry(1, t_cap=100)
+    cache.ctx_len[0] = 90
+    for q_off, code in [([0, 20], kvp.KVP_E_CAPACITY), ([1, 5], kvp.KVP_E_INVAL), ([0, -1], kvp.KVP_E_INVAL)]:
+        with pytest.raises(kvp.KvpError) as e:
+            kvp.kvp_query_prefill(s, cache, 0, None, None, None, np.array(q_off, np.int32), None, None)
+        assert e.value.code == code
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_query_prefill(s, cache, 5, None, None, None, np.array([0, 4], np.int32), None, None)
+    assert e.value.code == kvp.KVP_E_INVAL
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_query_prefill(s, cache, 0, None, None, None, np.array([0, 4], np.int32), None, None, flags=8)
+    assert e.value.code == kvp.KVP_E_INVAL
+    kvp.kvp_query_prefill(s, cache, 0, None, None, None, np.array([0, 10], np.int32), None, None)
+    assert cache.ctx_len[0] == 90                             # prefill never advances ctx_len

@@ -1,0 +1,246 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Assembly (and the appended query K/V) must match bit for bit; attention
+within 1e-5 (fp32 path) / 2e-2 (bf16 inputs, fp32 accumulation) max abs error."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import kvp_workloads as W
+from tests.gpu_harness import build_store, make_cache, oracle_workload, run_workload
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def compare(w, got, ref, layers=None):
+    layers = range(w.n_layers) if layers is None else layers
+    worst = 0.0
+    for r in range(len(w.requests)):
+        assert got["ctx"][r] == ref["ctx"][r]
+        for layer in layers:
+            assert np.array_equal(got["k"][r][layer], ref["k"][r][layer]), (w.name, "K", r, layer)
+            assert np.array_equal(got["v"][r][layer], ref["v"][r][layer]), (w.name, "V", r, layer)
+            if w.requests[r].n_q == 0:
+                continue
+            o = got["out"][r][layer]
+            assert np.all(np.isfinite(o)), (w.name, "non-finite output", r, layer)
+            err = float(np.max(np.abs(o - ref["out"][r][layer])))
+            worst = max(worst, err)
+            assert err <= TOL[w.dtype], (w.name, r, layer, err)
+    return worst
+
+
+def test_config1_tiny_fp32(gpu_device):
+    w = W.tiny_fp32()
+    err = compare(w, run_workload(w), oracle_workload(w))
+    print("tiny_fp32 max abs err", err)
+
+
+@pytest.mark.parametrize("case", [
+    dict(seed=11, d=2, n_q_heads=1, n_kv_heads=1, k=1, n_q=1, max_len=1),
+    dict(seed=12, d=8, n_q_heads=4, n_kv_heads=2, k=3, n_q=5),
+    dict(seed=13, d=8, n_q_heads=7, n_kv_heads=1, k=3, n_q=5, n_req=3),
+    dict(seed=14, d=16, n_q_heads=4, n_kv_heads=2, k=0, n_q=6),
+    dict(seed=15, d=24, n_q_heads=4, n_kv_heads=2, k=3, n_q=3, base_pos=11),
+    dict(seed=16, d=64, n_q_heads=14, n_kv_heads=2, k=6, n_q=9, max_len=150, n_packets=4),
+    dict(seed=17, d=256, n_q_heads=2, n_kv_heads=2, k=2, n_q=3, max_len=70),
+])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_small_ragged_shapes(gpu_device, case, dtype):
+    w = W.random_small(dtype=dtype, **case)
+    compare(w, run_workload(w), oracle_workload(w))
+
+
+@pytest.mark.parametrize("mk", [
+    lambda: W.llama_k5(n_layers=2, n_packets=16),
+    lambda: W.qwen_k20(n_layers=2, n_packets=40),
+    lambda: W.llama_8k(n_layers=1, n_packets=16),
+])
+def test_model_shapes_reduced_depth(gpu_device, mk):
+    w = mk()
+    err = compare(w, run_workload(w), oracle_workload(w))
+    print(w.name, "max abs err", err)
+
+
+def test_batch_with_shared_packets(gpu_device):
+    # several requests, the same packet in more than one of them and twice in one
+    w = W.llama_long_b8(n_layers=1, n_packets=6, batch=3, k=4, n_q=40)
+    w.requests[1].packet_ids = [2, 2, 5, 2]
+    w.requests[2].n_q = 0
+    compare(w, run_workload(w), oracle_workload(w))
+
+
+@pytest.mark.parametrize("order", ["random", "sequential"])
+def test_paged_serving_mix_small(gpu_device, order):
+    w = W.serving_mix(n_packets=64, n_req=6)
+    for rq in w.requests:
+        rq.packet_ids = rq.packet_ids[:4]
+        rq.n_q = min(rq.n_q, 70)
+    got = run_workload(w, block_order=order)
+    compare(w, got, oracle_workload(w))
+
+
+def test_paged_fp32_small_blocks(gpu_device):
+    w = W.random_small(31, dtype="f32", d=64, k=5, n_q=7, max_len=40, n_req=2, n_packets=6)
+    w.paged, w.block_size = True, 4
+    compare(w, run_workload(w), oracle_workload(w))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_prerotated_flag(gpu_device, dtype):
+    import oracle
+    import paper_2604_13226_amd as kvp
+    w = W.random_small(41, dtype=dtype, d=64, k=3, n_q=6, max_len=50, n_layers=1)
+    f = oracle.inv_freq(w.rope_base, w.head_dim)
+
+    def prerot(r, layer, q, kn, ctx):
+        # the caller's own rotation: oracle arithmetic on the CPU, then back to the device
+        dev = q.device
+        qn, knn = W.to_numpy(q), W.to_numpy(kn)
+        if dtype == "bf16":
+            widen = lambda a: (a.astype(np.uint32) << 16).view(np.float32)
+        else:
+            widen = lambda a: a
+        def rot(a):
+            a = widen(a)
+            out = np.empty_like(a)
+            for t in range(a.shape[0]):
+                for h in range(a.shape[1]):
+                    out[t, h] = oracle.rotate(np.ascontiguousarray(a[t, h]), ctx + t, f)
+            return torch.from_numpy(out).to(w.torch_dtype).to(dev)
+        return rot(qn), rot(knn)
+
+    got = run_workload(w, flags=kvp.KVP_PREROTATED, prerotate_with=prerot)
+    ref = oracle_workload(w, prerotated=True, prerotate_with=prerot)
+    compare(w, got, ref)
+
+
+def test_special_values_bit_exact(gpu_device):
+    """Denormals, signed zeros, large magnitudes and rounding ties go through the same
+    arithmetic on both sides."""
+    import oracle
+    import paper_2604_13226_amd as kvp
+    rng = np.random.default_rng(5)
+    n_layers, n_kv, d = 1, 2, 128
+    lens = [3, 70, 64]
+    pk, pv = [], []
+    for n in lens:
+        bits = rng.integers(0, 1 << 16, size=(n_layers, n_kv, n, d), dtype=np.uint16)
+        exp = (bits >> 7) & 0xFF
+        bits[exp == 0xFF] &= 0x807F                      # no inf / nan: make them denormals
+        big = exp >= 0xF0
+        bits[big] = (bits[big] & 0x807F) | (0x7E << 7)   # keep products finite
+        bits[0, 0, 0, :8] = [0x0000, 0x8000, 0x0001, 0x8001, 0x007F, 0x0080, 0x3F80, 0xBF80]
+        pk.append(bits)
+        pv.append(rng.integers(0, 1 << 16, size=(n_layers, n_kv, n, d), dtype=np.uint16))
+    f = oracle.inv_freq(5.0e5, d)
+    ko, vo, ctx = oracle.assemble("bf16", pk, pv, f, 0, sum(lens))
+    store = kvp.kvp_store_create(n_layers, 8, n_kv, d, "bf16", 5.0e5, 1024, 1 << 22)
+    for i, (a, b) in enumerate(zip(pk, pv)):
+        ta = torch.from_numpy(a.view(np.int16)).view(torch.bfloat16)
+        tb = torch.from_numpy(b.view(np.int16)).view(torch.bfloat16)
+        kvp.kvp_store_put(store, i, ta, tb)              # host source
+    cache = kvp.Cache.contiguous(store, 1, sum(lens))
+    kvp.kvp_assemble(store, [([0, 1, 2], 0)], cache)
+    torch.cuda.synchronize()
+    k, v = cache.logical(0, 0, ctx)
+    assert np.array_equal(W.to_numpy(k), ko[0])
+    assert np.array_equal(W.to_numpy(v), vo[0])
+
+
+def test_layer_range_and_untouched_rows(gpu_device):
+    import paper_2604_13226_amd as kvp
+    w = W.llama_k5(n_layers=3, n_packets=8)
+    w.requests[0].packet_ids = w.requests[0].packet_ids[:2]
+    w.requests[0].base_pos = 5
+    store = build_store(w, kvp)
+    cache = make_cache(w, kvp, store, t_slack=9)
+    cache.k.fill_(7.0)
+    cache.v.fill_(7.0)
+    kvp.kvp_assemble(store, [(w.requests[0].packet_ids, 5)], cache, layer_begin=1, layer_end=2)
+    torch.cuda.synchronize()
+    ctx = int(cache.ctx_len[0])
+    ref = oracle_workload(w, layers=[])
+    for layer in range(3):
+        k = W.to_numpy(cache.k[0, layer])
+        v = W.to_numpy(cache.v[0, layer])
+        seven = W.to_numpy(torch.tensor([7.0], dtype=torch.bfloat16))[0]
+        if layer == 1:
+            assert np.array_equal(k[:, 5:ctx], ref["k"][0][1][:, 5:ctx])
+            assert np.array_equal(v[:, 5:ctx], ref["v"][0][1][:, 5:ctx])
+            assert np.all(k[:, :5] == seven) and np.all(k[:, ctx:] == seven)
+            assert np.all(v[:, :5] == seven) and np.all(v[:, ctx:] == seven)
+        else:
+            assert np.all(k == seven) and np.all(v == seven)
+
+
+def test_failed_calls_change_nothing_on_device(gpu_device):
+    import paper_2604_13226_amd as kvp
+    w = W.llama_k5(n_layers=1, n_packets=8)
+    store = build_store(w, kvp)
+    cache = kvp.Cache.contiguous(store, 1, 100)              # far too small
+    cache.k.fill_(3.0)
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_assemble(store, [(w.requests[0].packet_ids, 0)], cache)
+    assert e.value.code == kvp.KVP_E_CAPACITY
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_assemble(store, [([123456], 0)], cache)
+    assert e.value.code == kvp.KVP_E_NOTFOUND
+    torch.cuda.synchronize()
+    assert bool((cache.k == 3.0).all())
+    ws = kvp.alloc_workspace(256)
+    q = torch.zeros(4, 32, 128, dtype=torch.bfloat16, device="cuda")
+    kn = torch.zeros(4, 8, 128, dtype=torch.bfloat16, device="cuda")
+    out = torch.full_like(q, 9.0)
+    cache.ctx_len[0] = 10
+    with pytest.raises(kvp.KvpError) as e:                   # workspace too small
+        kvp.kvp_query_prefill(store, cache, 0, q, kn, kn, [0, 4], ws, out)
+    assert e.value.code == kvp.KVP_E_CAPACITY
+    torch.cuda.synchronize()
+    assert bool((out == 9.0).all()) and bool((cache.k == 3.0).all())
+
+
+def test_split_invariance(gpu_device):
+    """The split-KV reduction is exact algebra: any number of splits gives the same result
+    within tolerance, including splits that see no visible row."""
+    w = W.llama_k5(n_layers=1, n_packets=8)
+    ref = oracle_workload(w)
+    for target in ("1", "16", "200", "4000"):
+        os.environ["KVP_ATTN_TARGET_ITEMS"] = target
+        try:
+            got = run_workload(w)
+        finally:
+            del os.environ["KVP_ATTN_TARGET_ITEMS"]
+        compare(w, got, ref)
+
+
+def test_generic_kernel_on_bf16_model_shape(gpu_device):
+    w = W.llama_k5(n_layers=1, n_packets=8)
+    w.requests[0].packet_ids = w.requests[0].packet_ids[:2]
+    os.environ["KVP_FORCE_GENERIC_ATTENTION"] = "1"
+    try:
+        got = run_workload(w)
+    finally:
+        del os.environ["KVP_FORCE_GENERIC_ATTENTION"]
+    compare(w, got, oracle_workload(w))
+
+
+def test_full_size_llama_k5_sampled(gpu_device):
+    """Config 2 at full depth (32 layers, the launch configuration the benchmark times):
+    assembly bit-exact on every layer, attention on sampled layers."""
+    w = W.llama_k5()
+    layers = [0, 13, 31]
+    got = run_workload(w, layers=layers)
+    ref = oracle_workload(w, layers=layers)
+    r = 0
+    ctx = ref["ctx"][0]
+    for layer in range(w.n_layers):
+        rows = ctx if layer not in layers else ctx + w.requests[0].n_q
+        assert np.array_equal(got["k"][r][layer][:, :rows], ref["k"][r][layer][:, :rows]), layer
+        assert np.array_equal(got["v"][r][layer][:, :rows], ref["v"][r][layer][:, :rows]), layer
+    for layer in layers:
+        err = float(np.max(np.abs(got["out"][r][layer] - ref["out"][r][layer])))
+        assert err <= 2e-2, (layer, err)
