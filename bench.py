@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV Packet serving hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic requests: one
+kvp_assemble launch covering every layer, then kvp_query_prefill for each layer.  Inputs
+(packet store, Q / K_new / V_new of every layer) are resident in HBM before the timed
+region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+BF16_PEAK_TFLOPS = 2500.0
+
+
+def make_workload(name):
+    import kvp_workloads as W
+    return {
+        "llama_8k": lambda: W.llama_8k(),
+        "llama_k5": lambda: W.llama_k5(),
+        "qwen_k20": lambda: W.qwen_k20(),
+        "llama_long_b8": lambda: W.llama_long_b8(n_layers=4),
+        "serving_mix": lambda: W.serving_mix(n_layers=1),
+        "tiny_fp32": lambda: W.tiny_fp32(),
+    }[name]()
+
+
+def cpu_baseline(w, sample_layers):
+    """Times the CPU oracle, as it stands, on `sample_layers` layers of request 0."""
+    import numpy as np
+    import kvp_workloads as W
+    import oracle
+    f = oracle.inv_freq(w.rope_base, w.head_dim)
+    rq = w.requests[0]
+    pk, pv = [], []
+    for p in rq.packet_ids:
+        k, v = w.packet_kv(p, layers=sample_layers)
+        pk.append(W.to_numpy(k)), pv.append(W.to_numpy(v))
+    rows = w.ctx_len(0) + rq.n_q
+    npdt = np.float32 if w.dtype == "f32" else np.uint16
+    ko = np.zeros((sample_layers, w.n_kv_heads, rows, w.head_dim), npdt)
+    vo = np.zeros_like(ko)
+    qs = [tuple(W.to_numpy(x) for x in w.query(0, l)) for l in range(sample_layers)]
+    t0 = time.perf_counter()
+    ko, vo, ctx = oracle.assemble(w.dtype, pk, pv, f, rq.base_pos, rows, ko, vo)
+    t1 = time.perf_counter()
+    for l in range(sample_layers):
+        q, kn, vn = qs[l]
+        oracle.query_prefill(w.dtype, q, kn, vn, f, ctx, ko[l], vo[l])
+    t2 = time.perf_counter()
+    return dict(value=(t2 - t0) * 1e6 / sample_layers, unit="us/layer", cores=oracle.num_threads(),
+                kind="oracle",
+                sample="request 0, %d of %d layers of %s (assemble %.0f us/layer, prefill %.0f us/layer)"
+                % (sample_layers, w.n_layers, w.name, (t1 - t0) * 1e6 / sample_layers,
+                   (t2 - t1) * 1e6 / sample_layers))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama_8k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2604_13226_amd as kvp
+    from tests.gpu_harness import build_store, make_cache
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    w = make_workload(args.workload)
+    n_req = len(w.requests)
+    store = build_store(w, kvp, dev, packets=list(range(len(w.packet_lens)))
+                        if len(w.packet_lens) <= 256 else None)
+    cache = make_cache(w, kvp, store, dev, t_slack=0)
+    reqs = [(rq.packet_ids, rq.base_pos) for rq in w.requests]
+    q_off = np.zeros(n_req + 1, np.int32)
+    for r in range(n_req):
+        q_off[r + 1] = q_off[r] + w.requests[r].n_q
+    tot_q = int(q_off[-1])
+    ctx = [w.ctx_len(r) for r in range(n_req)]
+    max_ctx = max(c + rq.n_q for c, rq in zip(ctx, w.requests))
+    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, n_req, tot_q, max_ctx), dev)
+    qkv = []
+    for layer in range(w.n_layers):
+        parts = [w.query(r, layer, dev) for r in range(n_req)]
+        qkv.append(tuple(torch.cat([p[i] for p in parts]).contiguous() for i in range(3)))
+    out = torch.empty_like(qkv[0][0])
+    torch.cuda.synchronize()
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        kvp.kvp_assemble(store, reqs, cache)
+        if ev:
+            ev[1].record()
+        for layer in range(w.n_layers):
+            q, kn, vn = qkv[layer]
+            kvp.kvp_query_prefill(store, cache, layer, q, kn, vn, q_off, ws, out)
+        if ev:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    asm_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    pre_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+
+    # algorithmic bytes / flops
+    tok_bytes = w.kv_bytes_per_token_layer()
+    T = sum(c - rq.base_pos for c, rq in zip(ctx, w.requests))
+    asm_bytes = 2.0 * T * tok_bytes * w.n_layers                      # read + write every K/V row
+    pre_bytes = sum((c + rq.n_q) * tok_bytes for c, rq in zip(ctx, w.requests))       # per layer
+    pre_flops = sum(4.0 * rq.n_q * c * w.n_q_heads * w.head_dim
+                    + 2.0 * rq.n_q * rq.n_q * w.n_q_heads * w.head_dim
+                    for c, rq in zip(ctx, w.requests))                                 # per layer
+    asm_gbs = asm_bytes / (asm_ms * 1e-3) / 1e9
+    pre_us_layer = pre_ms * 1e3 / w.n_layers
+    pre_gbs = pre_bytes / (pre_us_layer * 1e-6) / 1e9
+    pre_tflops = pre_flops / (pre_us_layer * 1e-6) / 1e12
+
+    res = {
+        "metric": "per-layer assemble+query-prefill us at 8K ctx",
+        "value": ms_per_step * 1e3 / w.n_layers,
+        "unit": "us/layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": "%s: %d layers, Hq %d / Hkv %d, d %d, %d request(s), ctx %s, n_q %s"
+                   % (w.name, w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, n_req,
+                      ctx[:4], [rq.n_q for rq in w.requests[:4]]),
+                   "layout": "paged" if w.paged else "contiguous"},
+        "roofline": {"bound": "hbm", "kernel": "assemble_vec_kernel (all layers, one launch)",
+                     "achieved": asm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": asm_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": asm_bytes, "us_per_launch": asm_ms * 1e3},
+        "prefill": {"us_per_layer": pre_us_layer, "bytes_per_layer": pre_bytes,
+                    "flops_per_layer": pre_flops, "achieved_GBs": pre_gbs,
+                    "hbm_frac": pre_gbs / HBM_PEAK_GBS, "achieved_TFLOPs": pre_tflops,
+                    "mfma_frac": pre_tflops / BF16_PEAK_TFLOPS},
+        "assemble_us_per_layer": asm_ms * 1e3 / w.n_layers,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, min(args.cpu_layers, w.n_layers))
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

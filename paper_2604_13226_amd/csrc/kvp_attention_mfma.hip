@@ -3,16 +3,22 @@
 //
 // One workgroup = 4 wavefronts = one work item: rows [m0, m0+128) of the packed
 // (query token, query head) rows that share one KV head, over one kv range (split-KV).
-// Wave w owns 32 rows.  Per 64-row K/V tile, staged once through LDS for all 128 rows:
+// Wave w owns 32 rows.  K/V tiles of 64 rows travel HBM -> LDS directly
+// (global_load_lds_dwordx4, no staging registers) through a ring of STAGES tiles, so
+// STAGES-1 tiles are in flight while one is being consumed.  Per tile:
 //
-//   S^T = K Q^T      v_mfma_f32_32x32x16_bf16, A = K tile rows from LDS (16-byte reads),
+//   S^T = K Q^T      v_mfma_f32_32x32x16_bf16, A = K rows from LDS (16-byte reads),
 //                    B = Q^T held in registers for the whole item
-//   online softmax   a lane owns one query row (column of S^T): row max / row sum are
+//   online softmax   a lane owns one query row (a column of S^T): row max / row sum are
 //                    in-lane reductions plus one exchange with lane ^ 32
-//   O^T += V^T P^T   A = V^T read straight out of the row-major V tile with the
-//                    transposing LDS read (ds_read_b64_tr_b16), B = P^T taken from the
-//                    S^T accumulators in place: the kv order inside each 16-row k-step is
-//                    whatever the accumulator layout gives, applied to both operands.
+//   O^T += V^T P^T   A = V^T read out of the row-major V tile with the transposing LDS
+//                    read (ds_read_b64_tr_b16), B = P^T taken from the S^T accumulators in
+//                    place: the kv order inside each 16-row k-step is whatever the
+//                    accumulator layout gives, applied to both operands.
+//
+// LDS tiles are unpadded (a direct load writes 64 lanes x 16 B contiguously); bank
+// conflicts are avoided by choosing WHICH 16-byte chunk of a row each lane fetches:
+// K row r keeps logical chunk c at physical chunk c ^ (r & 15), V row r at c ^ 4 (r & 3).
 //
 // HBM traffic: every K/V row of the range is read once per group of 128 packed rows.
 #include "kvp_device.h"
@@ -20,223 +26,299 @@
 namespace kvp {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void *lds_void_p;
+typedef __attribute__((address_space(1))) const void *glb_void_p;
 
-constexpr int BM = 128;          // packed rows per workgroup
-constexpr int BN = 64;           // kv rows per tile
-constexpr int D = 128;           // head_dim
-constexpr int K_STRIDE = D + 8;  // LDS row strides (elements): 272 B and 320 B keep the
-constexpr int V_STRIDE = D + 32; // 16-byte K reads and the transposing V reads conflict-free
-constexpr int K_TILE = BN * K_STRIDE;
-constexpr int V_TILE = BN * V_STRIDE;
-constexpr int LDS_BYTES = 2 * (K_TILE + V_TILE) * 2;
+constexpr int BM = 128;  // packed rows per workgroup
+constexpr int BN = 64;   // kv rows per tile
+constexpr int D = 128;   // head_dim
+constexpr int ROW_BYTES = D * 2;
+constexpr int TILE_BYTES = BN * ROW_BYTES;   // 16 KiB for K, same for V
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;  // K tile then V tile
+constexpr int MAX_BLOCK_IDS = MFMA_MAX_ITEM_BLOCKS;  // paged: block ids of one item kept in LDS
 
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b)
+__device__ __forceinline__ uint32_t pack_bf16_hw(float a, float b)
 {
-    return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+    floatx2 f = {a, b};
+    bf16x2 v = __builtin_convertvector(f, bf16x2);  // v_cvt_pk_bf16_f32, round to nearest even
+    return __builtin_bit_cast(uint32_t, v);
 }
 
+// wait until at most n of this wave's vector-memory operations are outstanding
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// HBM -> LDS without staging registers: each lane names its own 16 global bytes; the
+// wavefront's 64 x 16 B land contiguously at the wave-uniform LDS byte address lds_addr.
+// Written as inline assembly so that the compiler's wait-count insertion does not treat
+// every later LDS read as dependent on every outstanding load: the waits are explicit
+// (wait_vmcnt + wg_barrier) in the tile loop.
+__device__ __forceinline__ void load_to_lds_16(const void *gptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+}
+
+// If the running reference maximum lags the true row maximum by at most this many
+// powers of two, the accumulators are not rescaled (probabilities then reach at most 2^8,
+// harmless in fp32 accumulators and scale-free in bf16); the final (m, l, O) stay consistent
+// because all three are relative to the same reference.
+constexpr float RESCALE_SLACK = 8.f;
+
+template <int STAGES>
 __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
 {
-    extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+#ifdef KVP_TIMING
+    if (threadIdx.x == 0) a.dbg[blockIdx.x * 8 + 0] = wall_clock64();
+#endif
     const AttnItem it = a.items[blockIdx.x];
-    const AttnGroup gp = a.groups[it.group];
-    const ReqMeta rq = a.reqs[gp.req];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
     const int g = a.g;
 
+    const bf16_t *kc = (const bf16_t *)a.cache.k;
+    const bf16_t *vc = (const bf16_t *)a.cache.v;
+    const int kv_last = it.kv_end - 1;
+    const int n_tiles = (it.kv_end - it.kv_begin + BN - 1) / BN;
+
+    // paged layout: this item's block ids go to LDS once, so the tile loop issues no
+    // ordinary global loads (its in-flight count is what the waits below rely on)
+    int *blk_ids = (int *)(lds + STAGES * STAGE_BYTES);
+    const bool paged = a.cache.layout != 0;
+    const int blk0 = paged ? (it.kv_begin >> a.cache.block_shift) : 0;
+    if (paged) {
+        const int nb = (kv_last >> a.cache.block_shift) - blk0 + 1;
+        for (int i = tid; i < nb; i += 256)
+            blk_ids[i] = a.cache.block_table[(int64_t)it.req * a.cache.max_blocks + blk0 + i];
+        __syncthreads();
+    }
+    const int64_t contig_base = (int64_t)it.req * a.cache.req_stride + (int64_t)a.layer * a.cache.layer_stride +
+                                (int64_t)it.kv_head * a.cache.t_cap * D;
+    const int64_t paged_base = (int64_t)a.layer * a.cache.layer_stride;
+
+    // direct HBM -> LDS load of tile tj: wave w, instruction i fills tile rows
+    // 16 i + 4 w .. +3 (1 KiB contiguous in LDS); lane l owns slot (row + l / 16, chunk l % 16)
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds);
+    const int slot_row = lane >> 4, slot_chunk = lane & 15;
+    const int k_chunk = slot_chunk ^ ((4 * wave + slot_row) & 15);  // logical chunk fetched
+    const int v_chunk = slot_chunk ^ (4 * slot_row);
+    auto issue = [&](int tj) {
+        const uint32_t st = lds_base + (uint32_t)((tj % STAGES) * STAGE_BYTES);
+        const int kv0 = it.kv_begin + tj * BN;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = 16 * i + 4 * wave + slot_row;
+            int kv = kv0 + r;
+            kv = kv < kv_last ? kv : kv_last;  // rows past the range repeat the last row (masked)
+            int64_t off;
+            if (!paged) {
+                off = contig_base + (int64_t)kv * D;
+            } else {
+                int b = blk_ids[(kv >> a.cache.block_shift) - blk0];
+                int slot = kv & ((1 << a.cache.block_shift) - 1);
+                off = paged_base + ((((int64_t)b * a.n_kv + it.kv_head) << a.cache.block_shift) + slot) * D;
+            }
+            const uint32_t dst = st + (uint32_t)((16 * i + 4 * wave) * ROW_BYTES);
+            load_to_lds_16(kc + off + 8 * k_chunk, dst);
+            load_to_lds_16(vc + off + 8 * v_chunk, dst + TILE_BYTES);
+        }
+    };
+    // the first tiles start their trip before anything else is fetched
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < n_tiles) issue(s);
+
     // this lane's query row
     const int rr = 32 * wave + n;
-    const bool row_ok = rr < gp.n_rows;
-    const int m = gp.m0 + (row_ok ? rr : 0);
-    const int t = m / g, hq = gp.kv_head * g + m % g;
-    const int limit = row_ok ? rq.ctx_len + t + 1 : 0;  // kv rows [0, limit) are visible
+    const bool row_ok = rr < it.n_rows;
+    const int m = it.m0 + (row_ok ? rr : 0);
+    const int t = m / g, hq = it.kv_head * g + m % g;
+    const int limit = row_ok ? it.ctx_len + t + 1 : 0;  // kv rows [0, limit) are visible
+    // smallest limit among the wave's rows (rows are ordered by query token)
+    const int wave_limit = it.ctx_len + (it.m0 + 32 * wave) / g + 1;
 
     // B operand of S^T = K Q^T: lane holds Q[m][16 ks + 8 h .. +7] for ks = 0..7
     bf16x8 qf[8];
     {
-        const bf16_t *qp = (const bf16_t *)a.q_rot + ((int64_t)(rq.q_off + t) * a.n_q_heads + hq) * D + 8 * h;
+        const bf16_t *qp = (const bf16_t *)a.q_rot + ((int64_t)(it.q_off + t) * a.n_q_heads + hq) * D + 8 * h;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             uint4 u = row_ok ? *(const uint4 *)(qp + 16 * ks) : make_uint4(0, 0, 0, 0);
             qf[ks] = __builtin_bit_cast(bf16x8, u);
         }
     }
+    // Pin Q in registers here: the compiler then places its wait for the Q loads before the
+    // tile loop instead of at their first use inside it (where it would also drain every
+    // tile load in flight).
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));
 
     floatx16 oacc[4];
 #pragma unroll
     for (int eb = 0; eb < 4; ++eb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[eb][r] = 0.f;
-    float m_i = -INFINITY, l_i = 0.f;
+    float m_ref = -INFINITY, l_i = 0.f;  // reference max (scaled log2 units) and running sum
 
-    const bf16_t *kc = (const bf16_t *)a.cache.k;
-    const bf16_t *vc = (const bf16_t *)a.cache.v;
-    // staging: thread copies 16-byte chunk (tid % 16) of tile rows tid / 16 + 16 i
-    const int ld_row = tid >> 4, ld_chunk = tid & 15;
-    uint4 kreg[4], vreg[4];
-    auto fetch = [&](int kv0) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int kv = kv0 + ld_row + 16 * i;
-            if (kv < it.kv_end) {
-                int64_t off = cache_row_off(a.cache, gp.req, a.layer, gp.kv_head, kv, a.n_kv, D) + 8 * ld_chunk;
-                kreg[i] = *(const uint4 *)(kc + off);
-                vreg[i] = *(const uint4 *)(vc + off);
-            } else {  // rows past the range: zeros, so masked probabilities meet finite values
-                kreg[i] = make_uint4(0, 0, 0, 0);
-                vreg[i] = make_uint4(0, 0, 0, 0);
-            }
-        }
-    };
-    auto stage = [&](int buf) {
-        bf16_t *kl = lds + buf * (K_TILE + V_TILE);
-        bf16_t *vl = kl + K_TILE;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int row = ld_row + 16 * i;
-            *(uint4 *)(kl + row * K_STRIDE + 8 * ld_chunk) = kreg[i];
-            *(uint4 *)(vl + row * V_STRIDE + 8 * ld_chunk) = vreg[i];
-        }
-    };
-
-    const int n_tiles = (it.kv_end - it.kv_begin + BN - 1) / BN;
-    if (n_tiles > 0) {
-        fetch(it.kv_begin);
-        stage(0);
-    }
-    __syncthreads();
+#ifdef KVP_TIMING
+    if (threadIdx.x == 0) a.dbg[blockIdx.x * 8 + 1] = wall_clock64();
+#endif
+    const int tr_row = (lane & 15) >> 2;
+    const int tr_x = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);  // 16-byte chunk inside the 64-byte column group
+    const int tr_half = 8 * (lane & 1);
+    const float c = a.scale_log2e;
 
     for (int ti = 0; ti < n_tiles; ++ti) {
+        // tile ti has landed once at most the loads of the tiles issued after it remain
+        const int ahead = n_tiles - 1 - ti < STAGES - 2 ? n_tiles - 1 - ti : STAGES - 2;
+        if (ahead >= 3) wait_vmcnt<24>();
+        else if (ahead == 2) wait_vmcnt<16>();
+        else if (ahead == 1) wait_vmcnt<8>();
+        else wait_vmcnt<0>();
+        wg_barrier();  // every wave's part of tile ti is in LDS; everyone is done with tile ti-1
+        if (ti + STAGES - 1 < n_tiles) issue(ti + STAGES - 1);  // refills the stage tile ti-1 used
+
         const int kv0 = it.kv_begin + ti * BN;
-        const int buf = ti & 1;
-        if (ti + 1 < n_tiles) fetch(kv0 + BN);
-        const bf16_t *kl = lds + buf * (K_TILE + V_TILE);
-        const bf16_t *vl = kl + K_TILE;
+        const char *kl = lds + (ti % STAGES) * STAGE_BYTES;
+        const char *vl = kl + TILE_BYTES;
 
         // ---- S^T = K Q^T : 2 blocks of 32 kv rows x 32 query rows
         floatx16 sacc[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
-            const bf16_t *kp = kl + (32 * kb + n) * K_STRIDE + 8 * h;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                bf16x8 af = __builtin_bit_cast(bf16x8, *(const uint4 *)(kp + 16 * ks));
-                sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, qf[ks], sacc[kb], 0, 0, 0);
-            }
+        for (int ks = 0; ks < 8; ++ks) {
+            const int coff = 16 * ((2 * ks + h) ^ (n & 15));
+            bf16x8 a0 = __builtin_bit_cast(bf16x8, *(const uint4 *)(kl + n * ROW_BYTES + coff));
+            bf16x8 a1 = __builtin_bit_cast(bf16x8, *(const uint4 *)(kl + (32 + n) * ROW_BYTES + coff));
+            sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], sacc[0], 0, 0, 0);
+            sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], sacc[1], 0, 0, 0);
         }
 
         // ---- online softmax; accumulator r of block kb is kv row kv0 + 32 kb + 8 (r/4) + 4 h + r%4
-        const int tile_end = kv0 + BN < it.kv_end ? kv0 + BN : it.kv_end;
-        const bool need_mask = tile_end > limit || kv0 + BN > it.kv_end;
-        float mx = -INFINITY;
+        if (kv0 + BN > wave_limit || kv0 + BN > it.kv_end) {  // wave-uniform: tail tiles only
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float s = sacc[kb][r] * a.scale_log2e;
-                if (need_mask) {
+                for (int r = 0; r < 16; ++r) {
                     int kv = kv0 + 32 * kb + 8 * (r >> 2) + 4 * h + (r & 3);
-                    if (kv >= limit || kv >= it.kv_end) s = -INFINITY;
+                    if (kv >= limit || kv >= it.kv_end) sacc[kb][r] = -INFINITY;
                 }
-                sacc[kb][r] = s;
-                mx = fmaxf(mx, s);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_i, mx);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;  // nothing visible yet: p = 0
-        const float alpha = exp2f(m_i - m_use);
+        }
+        float mx = fmaxf(sacc[0][0], sacc[1][0]);
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(sacc[0][r], sacc[1][r]));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;
+        if (__any(mx > m_ref + RESCALE_SLACK)) {  // wave-uniform; rare once the maxima settle
+            const float m_new = fmaxf(m_ref, mx);
+            const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
+            m_ref = m_new;
+            l_i *= alpha;
+#pragma unroll
+            for (int eb = 0; eb < 4; ++eb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[eb][r] *= alpha;
+        }
+        const float m_sub = m_ref == -INFINITY ? 0.f : m_ref;  // nothing visible yet: p = 0
         float rs = 0.f;
         uint32_t pk[2][8];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
-                float p0 = exp2f(sacc[kb][r] - m_use), p1 = exp2f(sacc[kb][r + 1] - m_use);
+                float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][r], c, -m_sub));
+                float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][r + 1], c, -m_sub));
                 rs += p0 + p1;
-                pk[kb][r >> 1] = pack_bf16(p0, p1);
+                pk[kb][r >> 1] = pack_bf16_hw(p0, p1);
             }
-        rs += __shfl_xor(rs, 32, 64);
-        l_i = l_i * alpha + rs;
-        m_i = m_new;
-        if (alpha != 1.f) {
-#pragma unroll
-            for (int eb = 0; eb < 4; ++eb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[eb][r] *= alpha;
-        }
+        l_i += rs;  // this lane's half of the row; the halves are added once, at the end
 
         // ---- O^T += V^T P^T.  k-step j of block kb covers kv rows 32 kb + 16 j + [0, 16);
         // P^T slots 0..7 of lane-half h are rows 4h+{0..3} and 8+4h+{0..3} of that step, so
         // the two transposing reads fetch exactly those rows of V for column 32 eb + n.
-        const int tr_row = (lane & 15) >> 2, tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 uint4 pu = make_uint4(pk[kb][4 * j], pk[kb][4 * j + 1], pk[kb][4 * j + 2], pk[kb][4 * j + 3]);
                 bf16x8 pf = __builtin_bit_cast(bf16x8, pu);
-                const bf16_t *vp = vl + (32 * kb + 16 * j + 4 * h + tr_row) * V_STRIDE + tr_col;
+                const char *vp = vl + (32 * kb + 16 * j + 4 * h + tr_row) * ROW_BYTES + tr_half;
 #pragma unroll
                 for (int eb = 0; eb < 4; ++eb) {
-                    typedef __attribute__((address_space(3))) short4v *lds_p;
-                    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(vp + 32 * eb));
-                    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(vp + 8 * V_STRIDE + 32 * eb));
+                    typedef __attribute__((address_space(3))) short4v *lds_s4;
+                    const int coff = 16 * (4 * (eb ^ tr_row) + tr_x);
+                    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(vp + coff));
+                    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(vp + 8 * ROW_BYTES + coff));
                     union { short4v s[2]; bf16x8 v; } vf;
                     vf.s[0] = lo;
                     vf.s[1] = hi;
                     oacc[eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf, oacc[eb], 0, 0, 0);
                 }
             }
-
-        if (ti + 1 < n_tiles) stage(buf ^ 1);
-        __syncthreads();
     }
+    l_i += __shfl_xor(l_i, 32, 64);
 
+#ifdef KVP_TIMING
+    if (threadIdx.x == 0) a.dbg[blockIdx.x * 8 + 2] = wall_clock64();
+#endif
     // ---- epilogue: lane holds O[m][32 eb + 8 (r/4) + 4 h + r%4]
-    if (!row_ok) return;
-    if (gp.n_splits == 1) {
-        bf16_t *op = (bf16_t *)a.out + ((int64_t)(rq.q_off + t) * a.n_q_heads + hq) * D;
-        const float inv = 1.f / l_i;
+    if (row_ok) {
+        if (it.part_slot < 0) {
+            bf16_t *op = (bf16_t *)a.out + ((int64_t)(it.q_off + t) * a.n_q_heads + hq) * D;
+            const float inv = 1.f / l_i;
 #pragma unroll
-        for (int eb = 0; eb < 4; ++eb)
+            for (int eb = 0; eb < 4; ++eb)
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                uint2 u;
-                u.x = pack_bf16(oacc[eb][4 * q4] * inv, oacc[eb][4 * q4 + 1] * inv);
-                u.y = pack_bf16(oacc[eb][4 * q4 + 2] * inv, oacc[eb][4 * q4 + 3] * inv);
-                *(uint2 *)(op + 32 * eb + 8 * q4 + 4 * h) = u;
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    uint2 u;
+                    u.x = pack_bf16_hw(oacc[eb][4 * q4] * inv, oacc[eb][4 * q4 + 1] * inv);
+                    u.y = pack_bf16_hw(oacc[eb][4 * q4 + 2] * inv, oacc[eb][4 * q4 + 3] * inv);
+                    *(uint2 *)(op + 32 * eb + 8 * q4 + 4 * h) = u;
+                }
+        } else {
+            float *pp = a.partials + (int64_t)it.part_slot * BM * (D + 2);
+#pragma unroll
+            for (int eb = 0; eb < 4; ++eb)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    float4 f = make_float4(oacc[eb][4 * q4], oacc[eb][4 * q4 + 1], oacc[eb][4 * q4 + 2], oacc[eb][4 * q4 + 3]);
+                    *(float4 *)(pp + (int64_t)rr * D + 32 * eb + 8 * q4 + 4 * h) = f;
+                }
+            if (h == 0) {
+                pp[BM * D + rr] = m_ref;
+                pp[BM * D + BM + rr] = l_i;
             }
-    } else {
-        float *pp = a.partials + (int64_t)(gp.part0 + it.split) * BM * (D + 2);
-#pragma unroll
-        for (int eb = 0; eb < 4; ++eb)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                float4 f = make_float4(oacc[eb][4 * q4], oacc[eb][4 * q4 + 1], oacc[eb][4 * q4 + 2], oacc[eb][4 * q4 + 3]);
-                *(float4 *)(pp + (int64_t)rr * D + 32 * eb + 8 * q4 + 4 * h) = f;
-            }
-        if (h == 0) {
-            pp[BM * D + rr] = m_i;
-            pp[BM * D + BM + rr] = l_i;
         }
     }
+#ifdef KVP_TIMING
+    if (threadIdx.x == 0) a.dbg[blockIdx.x * 8 + 3] = wall_clock64();
+#endif
 }
+
+constexpr int ATTN_STAGES = 2;  // 64 KiB of tiles + block ids: two workgroups share a CU
 
 int launch_attention_mfma(const AttnArgs &a, void *stream)
 {
     if (a.d != D || a.bm != BM) return (int)hipErrorInvalidValue;
+    constexpr int lds_bytes = ATTN_STAGES * STAGE_BYTES + MAX_BLOCK_IDS * 4;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<ATTN_STAGES>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(attention_mfma_kernel, dim3(a.n_items), dim3(256), LDS_BYTES, (hipStream_t)stream, a);
+    hipLaunchKernelGGL(attention_mfma_kernel<ATTN_STAGES>, dim3(a.n_items), dim3(256), lds_bytes, (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 

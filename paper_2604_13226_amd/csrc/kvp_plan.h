@@ -52,9 +52,15 @@ struct AttnGroup {
     int32_t part0, n_splits;           // partial slots part0 .. part0 + n_splits - 1
     int32_t pad0, pad1;
 };
+// Self-contained (one 64-byte read tells a workgroup everything it needs).
 struct AttnItem {
     int32_t group, split, kv_begin, kv_end;  // kv rows [kv_begin, kv_end)
+    int32_t req, kv_head, m0, n_rows;        // copy of the group
+    int32_t ctx_len, q_off;                  // copy of the request
+    int32_t part_slot;                       // partial slot to write, or -1: write `out` directly
+    int32_t pad[5];
 };
+static_assert(sizeof(AttnItem) == 64, "AttnItem is 64 bytes");
 
 struct AttnArgs {
     const void *q_rot;  // [tot_q][Hq][d], store dtype, rotated
@@ -66,6 +72,9 @@ struct AttnArgs {
     void *out;        // [tot_q][Hq][d]
     int32_t n_items, n_groups, layer, n_q_heads, n_kv, d, bm, g;
     float scale_log2e;  // log2(e) / sqrt(d)
+#ifdef KVP_TIMING
+    unsigned long long *dbg;  // per-item timestamps (bench builds only)
+#endif
 };
 
 struct AppendArgs {
@@ -85,5 +94,10 @@ int launch_attention(int dtype, const AttnArgs &a, int kernel_kind, void *stream
 int launch_combine(int dtype, const AttnArgs &a, void *stream);
 
 enum { ATTN_GENERIC = 0, ATTN_MFMA = 1 };
+
+// MFMA kernel, paged layout: an item's block ids live in LDS, so one item may span at most
+// this many blocks, and blocks must hold at least MFMA_MIN_BLOCK_SIZE rows.
+constexpr int MFMA_MAX_ITEM_BLOCKS = 2048;
+constexpr int MFMA_MIN_BLOCK_SIZE = 16;
 
 }  // namespace kvp

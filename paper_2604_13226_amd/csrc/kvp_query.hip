@@ -152,39 +152,73 @@ __global__ __launch_bounds__(256) void attention_generic_kernel(AttnArgs a)
 //   m = max m_i;  l = sum l_i 2^(m_i - m);  O = sum O~_i 2^(m_i - m) / l.
 // A split that saw no visible row has m_i = -inf, l_i = 0 and contributes nothing.
 // ---------------------------------------------------------------------------------
+// One wavefront per packed row.  Lane i first holds the log-sum-exp weight of split i (at
+// most 64 splits); then lane half hf = i / 32 sweeps the splits of its parity, columns
+// 4 (i % 32) .. +3 (+128 j) with 16-byte loads, several splits in flight at once, and the
+// two halves are added with one exchange.
+constexpr int COMBINE_ROWS = 4;  // rows per 256-thread workgroup
+
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a)
 {
     const AttnGroup gp = a.groups[blockIdx.x];
     if (gp.n_splits <= 1) return;
+    const int lane = threadIdx.x & 63, li = lane & 31, hf = lane >> 5;
+    const int rr = (int)blockIdx.y * COMBINE_ROWS + (threadIdx.x >> 6);
+    if (rr >= gp.n_rows) return;
     const ReqMeta rq = a.reqs[gp.req];
-    const int d = a.d;
+    const int d = a.d, ns = gp.n_splits;
     const int64_t slot = (int64_t)a.bm * (d + 2);
     const float *base = a.partials + (int64_t)gp.part0 * slot;
-    for (int idx = threadIdx.x; idx < gp.n_rows * d; idx += blockDim.x) {
-        int rr = idx / d, e = idx % d;
-        float mx = -INFINITY;
-        for (int s = 0; s < gp.n_splits; ++s) mx = fmaxf(mx, base[s * slot + (int64_t)a.bm * d + rr]);
-        float l = 0.f, acc = 0.f;
-        for (int s = 0; s < gp.n_splits; ++s) {
-            float mi = base[s * slot + (int64_t)a.bm * d + rr];
-            float li = base[s * slot + (int64_t)a.bm * d + a.bm + rr];
-            float w = (mi == -INFINITY) ? 0.f : exp2f(mi - mx);
-            l += li * w;
-            acc += base[s * slot + (int64_t)rr * d + e] * w;
+    const float *ml = base + (int64_t)a.bm * d + rr;
+    float mi = -INFINITY, lv = 0.f;
+    if (lane < ns) { mi = ml[lane * slot]; lv = ml[lane * slot + a.bm]; }
+    float mx = mi;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    const float w = (mi == -INFINITY) ? 0.f : exp2f(mi - mx);
+    const float inv = 1.f / wave_sum(lv * w);
+    const int m = gp.m0 + rr;
+    const int t = m / a.g, hq = gp.kv_head * a.g + m % a.g;
+    T *op = (T *)a.out + ((int64_t)(rq.q_off + t) * a.n_q_heads + hq) * d;
+    const float *row = base + (int64_t)rr * d;
+    if ((d & 3) == 0) {
+        for (int e = 4 * li; e < d; e += 128) {
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 8
+            for (int s2 = 0; s2 < ns; s2 += 2) {  // same trip count in both halves
+                const int sq = s2 + hf, sp = sq < ns ? sq : ns - 1;
+                float ws = __shfl(w, sp, 64);  // executed by all 64 lanes
+                if (sq >= ns) ws = 0.f;
+                const float4 v = *(const float4 *)(row + sp * slot + e);
+                acc.x += v.x * ws; acc.y += v.y * ws; acc.z += v.z * ws; acc.w += v.w * ws;
+            }
+            acc.x += __shfl_xor(acc.x, 32, 64);
+            acc.y += __shfl_xor(acc.y, 32, 64);
+            acc.z += __shfl_xor(acc.z, 32, 64);
+            acc.w += __shfl_xor(acc.w, 32, 64);
+            if (hf == 0) {
+                st_elem(op + e, acc.x * inv);
+                st_elem(op + e + 1, acc.y * inv);
+                st_elem(op + e + 2, acc.z * inv);
+                st_elem(op + e + 3, acc.w * inv);
+            }
         }
-        int m = gp.m0 + rr;
-        int t = m / a.g, hq = gp.kv_head * a.g + m % a.g;
-        T *op = (T *)a.out + ((int64_t)(rq.q_off + t) * a.n_q_heads + hq) * d;
-        st_elem(op + e, acc / l);
+    } else {
+        for (int e = lane; e < d; e += 64) {
+            float acc = 0.f;
+            for (int sp = 0; sp < ns; ++sp) acc += row[sp * slot + e] * __shfl(w, sp, 64);
+            st_elem(op + e, acc * inv);
+        }
     }
 }
 
 int launch_combine(int dtype, const AttnArgs &a, void *stream)
 {
     if (a.n_groups == 0) return 0;
-    if (dtype == 1) hipLaunchKernelGGL((combine_kernel<bf16_t>), dim3(a.n_groups), dim3(256), 0, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL((combine_kernel<float>), dim3(a.n_groups), dim3(256), 0, (hipStream_t)stream, a);
+    dim3 grid((unsigned)a.n_groups, (unsigned)((a.bm + COMBINE_ROWS - 1) / COMBINE_ROWS));
+    if (dtype == 1) hipLaunchKernelGGL((combine_kernel<bf16_t>), grid, dim3(256), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL((combine_kernel<float>), grid, dim3(256), 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 

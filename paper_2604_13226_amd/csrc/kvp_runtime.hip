@@ -106,7 +106,25 @@ struct kvp_store {
     std::unordered_map<int64_t, PacketRec> dir;
     uint64_t used_bytes = 0;
     float2 *cs_dev = nullptr;
-    PlanRing ring;
+    PlanRing ring;          // plans of kvp_assemble
+    PlanRing ring_prefill;  // plans of kvp_query_prefill
+    // The prefill plan depends only on the request geometry (context lengths, query
+    // offsets, block table), which is the same for every layer of a forward pass: the
+    // uploaded plan is kept and reused while that geometry does not change.
+    struct PrefillCached {
+        bool valid = false;
+        std::vector<int32_t> sig;
+        PlanRing::Slot *slot = nullptr;
+        void *stream = nullptr;
+        const ReqMeta *reqs_dev = nullptr;
+        const int32_t *row_req_dev = nullptr, *bt_dev = nullptr;
+        const AttnGroup *groups_dev = nullptr;
+        const AttnItem *items_dev = nullptr;
+        int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0;
+        bool any_split = false;
+        uint64_t need = 0;
+    } pf;
+    std::vector<int32_t> sig_scratch;
     std::string err;
     std::vector<int64_t> dbg_asm, dbg_attn;
     bool dry = false;
@@ -269,7 +287,7 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
         return fail(nullptr, KVP_E_INVAL, "head_dim must be even and in [2, 256]");
     if (cfg->dtype != KVP_F32 && cfg->dtype != KVP_BF16) return fail(nullptr, KVP_E_INVAL, "unknown dtype %d", cfg->dtype);
     if (cfg->n_header < 0 || cfg->n_trailer < 0) return fail(nullptr, KVP_E_INVAL, "negative adapter length");
-    if (cfg->max_positions < 1 || cfg->max_positions > (1 << 22)) return fail(nullptr, KVP_E_INVAL, "max_positions must be in [1, 2^22]");
+    if (cfg->max_positions < 1 || cfg->max_positions > (1 << 21)) return fail(nullptr, KVP_E_INVAL, "max_positions must be in [1, 2^21]");
     if (!cfg->inv_freq && !(cfg->rope_base > 0.0)) return fail(nullptr, KVP_E_INVAL, "rope_base must be positive");
     const bool dry = cfg->device == KVP_DEVICE_NONE;
     if (!dry) {
@@ -281,6 +299,7 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
     s->cfg = *cfg;
     s->dry = dry;
     s->ring.dry = dry;
+    s->ring_prefill.dry = dry;
     s->esize = cfg->dtype == KVP_BF16 ? 2 : 4;
     const int half = cfg->head_dim / 2;
     s->inv_freq.resize(half);
@@ -320,9 +339,11 @@ int kvp_store_destroy(kvp_store_t *s)
     if (!s->dry) {
         (void)hipSetDevice(s->cfg.device);
         s->ring.release();
+        s->ring_prefill.release();
         if (s->cs_dev) (void)hipFree(s->cs_dev);
     } else {
         s->ring.release();
+        s->ring_prefill.release();
     }
     delete s;
     return KVP_OK;
@@ -483,11 +504,23 @@ int target_items(const kvp_store *s) { return s->target_items > 0 ? s->target_it
 // Groups of packed rows and their split-KV items.  Every group of a request gets the same
 // split length (a multiple of bn rows), chosen so the launch has about target_items work
 // items; a group's kv range stops at the last row any of its query rows may see.
-void plan_prefill(const kvp_store *s, int n_req, const int32_t *ctx_len, const int32_t *q_off, PrefillPlan &p)
+bool use_mfma(const kvp_store *s, const kvp_cache_t *c)
+{
+    const kvp_config_t &g = s->cfg;
+    if (g.dtype != KVP_BF16 || g.head_dim != 128 || s->force_generic) return false;
+    return !(c && c->layout == KVP_PAGED && c->block_size < MFMA_MIN_BLOCK_SIZE);
+}
+
+void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const int32_t *ctx_len, const int32_t *q_off,
+                  PrefillPlan &p)
 {
     const kvp_config_t &g = s->cfg;
     const int gq = g.n_q_heads / g.n_kv_heads;
-    const bool mfma = g.dtype == KVP_BF16 && g.head_dim == 128 && !s->force_generic;
+    const bool mfma = use_mfma(s, cache);
+    // paged + MFMA: an item's blocks must fit the kernel's LDS id table
+    const int max_split = (mfma && cache->layout == KVP_PAGED)
+                              ? (MFMA_MAX_ITEM_BLOCKS - 1) * cache->block_size / 64 * 64
+                              : INT32_MAX;
     p.kind = mfma ? ATTN_MFMA : ATTN_GENERIC;
     p.bm = mfma ? MFMA_BM : GENERIC_BM;
     const int min_split = mfma ? 256 : 64;
@@ -509,6 +542,7 @@ void plan_prefill(const kvp_store *s, int n_req, const int32_t *ctx_len, const i
         int split_len = (total + want - 1) / want;
         split_len = std::max(split_len, min_split);
         split_len = (split_len + p.bn - 1) / p.bn * p.bn;
+        split_len = std::min(split_len, max_split);
         const int M = rq.n_q * gq;
         for (int h = 0; h < g.n_kv_heads; ++h)
             for (int m0 = 0; m0 < M; m0 += p.bm) {
@@ -526,8 +560,21 @@ void plan_prefill(const kvp_store *s, int n_req, const int32_t *ctx_len, const i
                     p.n_slots += gp.n_splits;
                     p.any_split = true;
                 }
-                for (int sp = 0; sp < gp.n_splits; ++sp)
-                    p.items.push_back(AttnItem{(int)p.groups.size(), sp, sp * split_len, std::min(vis, (sp + 1) * split_len)});
+                for (int sp = 0; sp < gp.n_splits; ++sp) {
+                    AttnItem it{};
+                    it.group = (int)p.groups.size();
+                    it.split = sp;
+                    it.kv_begin = sp * split_len;
+                    it.kv_end = std::min(vis, (sp + 1) * split_len);
+                    it.req = r;
+                    it.kv_head = h;
+                    it.m0 = m0;
+                    it.n_rows = gp.n_rows;
+                    it.ctx_len = rq.ctx_len;
+                    it.q_off = rq.q_off;
+                    it.part_slot = gp.n_splits > 1 ? gp.part0 + sp : -1;
+                    p.items.push_back(it);
+                }
                 p.groups.push_back(gp);
             }
     }
@@ -545,13 +592,14 @@ uint64_t kvp_prefill_workspace_bytes(const kvp_store_t *s, int32_t n_req, int32_
     if (!s || n_req < 0 || max_tot_q < 0 || max_ctx < 0) return 0;
     const kvp_config_t &g = s->cfg;
     const int gq = g.n_q_heads / g.n_kv_heads;
-    const bool mfma = g.dtype == KVP_BF16 && g.head_dim == 128 && !s->force_generic;
-    const int bm = mfma ? MFMA_BM : GENERIC_BM;
+    const bool mfma = use_mfma(s, nullptr);
+    const int bm = mfma ? MFMA_BM : GENERIC_BM;  // the generic kernel's smaller bm needs less
     // groups <= Hkv * (rows / bm + one ragged block per request); every group has at most
     // ceil(target / groups) <= target / groups + 1 splits (and never more than MAX_SPLITS)
     const uint64_t groups = (uint64_t)g.n_kv_heads * ((uint64_t)max_tot_q * gq / bm + (uint64_t)n_req);
-    const uint64_t slots = std::min<uint64_t>((uint64_t)target_items(s) + 2 * groups, groups * MAX_SPLITS);
-    (void)max_ctx;
+    // (a paged cache may force extra splits: at most max_ctx / 32704 more per group)
+    const uint64_t extra = (uint64_t)max_ctx / ((MFMA_MAX_ITEM_BLOCKS - 1) * MFMA_MIN_BLOCK_SIZE / 64 * 64);
+    const uint64_t slots = (uint64_t)target_items(s) + (2 + extra) * groups;
     return q_rot_bytes(s, max_tot_q) + slots * bm * (g.head_dim + 2) * sizeof(float) + ALIGN;
 }
 
@@ -586,46 +634,54 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
             return fail(s, KVP_E_INVAL, "q, k_new, v_new, out must be 16-byte aligned");
     }
 
-    PrefillPlan p;
-    plan_prefill(s, n_req, cache->ctx_len, q_offsets, p);
-    const uint64_t qrb = q_rot_bytes(s, tot_q);
-    const uint64_t need = qrb + (uint64_t)p.n_slots * p.bm * (g.head_dim + 2) * sizeof(float);
-    if (tot_q > 0) {
-        if (!s->dry && !workspace) return fail(s, KVP_E_INVAL, "workspace is null");
-        if ((uintptr_t)workspace & (ALIGN - 1)) return fail(s, KVP_E_INVAL, "workspace must be 256-byte aligned");
-        if (workspace_bytes < need)
-            return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)need);
-    }
     int bt_stride = 0;
     for (int r = 0; r < n_req; ++r) bt_stride = std::max(bt_stride, n_blk[r]);
 
-    const uint64_t bytes = p.reqs.size() * sizeof(ReqMeta) + p.row_req.size() * 4 + p.groups.size() * sizeof(AttnGroup) +
-                           p.items.size() * sizeof(AttnItem) + (uint64_t)n_req * bt_stride * 4 + 6 * 64;
+    // geometry signature: everything the plan is a function of
+    std::vector<int32_t> &sig = s->sig_scratch;
+    sig.clear();
+    sig.push_back(cache->layout);
+    sig.push_back(n_req);
+    sig.push_back(cache->layout == KVP_CONTIG ? cache->t_cap : cache->block_size);
+    sig.push_back(cache->layout == KVP_CONTIG ? 0 : cache->n_blocks);
+    for (int r = 0; r < n_req; ++r) sig.push_back(cache->ctx_len[r]);
+    for (int r = 0; r <= n_req; ++r) sig.push_back(q_offsets[r]);
+    if (cache->layout == KVP_PAGED)
+        for (int r = 0; r < n_req; ++r) {
+            const int32_t *row = cache->block_table + (int64_t)r * cache->max_blocks_per_req;
+            sig.insert(sig.end(), row, row + n_blk[r]);
+        }
+    kvp_store::PrefillCached &pf = s->pf;
+    const bool hit = pf.valid && pf.stream == hip_stream && pf.sig == sig;
+    const uint64_t qrb = q_rot_bytes(s, tot_q);
     if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
-    PlanRing::Slot *slot = nullptr;
-    int hrc = s->ring.acquire(bytes, &slot);
-    if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
-    PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
-    const ReqMeta *reqs_dev = nullptr;
-    const int32_t *row_req_dev = nullptr, *bt_dev = nullptr;
-    const AttnGroup *groups_dev = nullptr;
-    const AttnItem *items_dev = nullptr;
-    ReqMeta *rh = w.put<ReqMeta>(p.reqs.size(), &reqs_dev);
-    if (!p.reqs.empty()) memcpy(rh, p.reqs.data(), p.reqs.size() * sizeof(ReqMeta));
-    int32_t *rr = w.put<int32_t>(p.row_req.size(), &row_req_dev);
-    if (!p.row_req.empty()) memcpy(rr, p.row_req.data(), p.row_req.size() * 4);
-    AttnGroup *gh = w.put<AttnGroup>(p.groups.size(), &groups_dev);
-    if (!p.groups.empty()) memcpy(gh, p.groups.data(), p.groups.size() * sizeof(AttnGroup));
-    AttnItem *ih = w.put<AttnItem>(p.items.size(), &items_dev);
-    if (!p.items.empty()) memcpy(ih, p.items.data(), p.items.size() * sizeof(AttnItem));
-    if (cache->layout == KVP_PAGED && bt_stride > 0) {
-        int32_t *bh = w.put<int32_t>((uint64_t)n_req * bt_stride, &bt_dev);
-        rc = compact_block_table(s, cache, n_req, first_blk, n_blk, bt_stride, bh);
-        if (rc) return rc;
-    }
 
-    s->dbg_attn.clear();
-    {
+    if (!hit) {
+        PrefillPlan p;
+        plan_prefill(s, cache, n_req, cache->ctx_len, q_offsets, p);
+        const uint64_t need = qrb + (uint64_t)p.n_slots * p.bm * (g.head_dim + 2) * sizeof(float);
+        const uint64_t bytes = p.reqs.size() * sizeof(ReqMeta) + p.row_req.size() * 4 + p.groups.size() * sizeof(AttnGroup) +
+                               p.items.size() * sizeof(AttnItem) + (uint64_t)n_req * bt_stride * 4 + 6 * 64;
+        PlanRing::Slot *slot = nullptr;
+        int hrc = s->ring_prefill.acquire(bytes, &slot);
+        if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
+        pf.valid = false;  // the slot may be the cached one; it is rewritten below either way
+        PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
+        ReqMeta *rh = w.put<ReqMeta>(p.reqs.size(), &pf.reqs_dev);
+        if (!p.reqs.empty()) memcpy(rh, p.reqs.data(), p.reqs.size() * sizeof(ReqMeta));
+        int32_t *rr = w.put<int32_t>(p.row_req.size(), &pf.row_req_dev);
+        if (!p.row_req.empty()) memcpy(rr, p.row_req.data(), p.row_req.size() * 4);
+        AttnGroup *gh = w.put<AttnGroup>(p.groups.size(), &pf.groups_dev);
+        if (!p.groups.empty()) memcpy(gh, p.groups.data(), p.groups.size() * sizeof(AttnGroup));
+        AttnItem *ih = w.put<AttnItem>(p.items.size(), &pf.items_dev);
+        if (!p.items.empty()) memcpy(ih, p.items.data(), p.items.size() * sizeof(AttnItem));
+        pf.bt_dev = nullptr;
+        if (cache->layout == KVP_PAGED && bt_stride > 0) {
+            int32_t *bh = w.put<int32_t>((uint64_t)n_req * bt_stride, &pf.bt_dev);
+            rc = compact_block_table(s, cache, n_req, first_blk, n_blk, bt_stride, bh);
+            if (rc) return rc;
+        }
+        s->dbg_attn.clear();
         int64_t head[6] = {p.kind, p.bm, (int64_t)p.groups.size(), (int64_t)p.items.size(), p.n_slots, (int64_t)need};
         s->dbg_attn.insert(s->dbg_attn.end(), head, head + 6);
         for (const AttnGroup &x : p.groups) {
@@ -636,13 +692,37 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
             int64_t row[4] = {x.group, x.split, x.kv_begin, x.kv_end};
             s->dbg_attn.insert(s->dbg_attn.end(), row, row + 4);
         }
+        pf.slot = slot;
+        pf.kind = p.kind;
+        pf.bm = p.bm;
+        pf.n_items = (int)p.items.size();
+        pf.n_groups = (int)p.groups.size();
+        pf.bt_stride = bt_stride;
+        pf.tot_q = tot_q;
+        pf.any_split = p.any_split;
+        pf.need = need;
+        pf.sig = sig;
+        pf.stream = hip_stream;
+        // validated below before the upload makes the entry usable
+        if (tot_q > 0) {
+            if (!s->dry && !workspace) return fail(s, KVP_E_INVAL, "workspace is null");
+            if ((uintptr_t)workspace & (ALIGN - 1)) return fail(s, KVP_E_INVAL, "workspace must be 256-byte aligned");
+            if (workspace_bytes < need)
+                return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)need);
+        }
+        if (s->dry || tot_q == 0) return KVP_OK;
+        HIP_TRY(s, hipMemcpyAsync(slot->dev, slot->host, w.off, hipMemcpyHostToDevice, (hipStream_t)hip_stream));
+        pf.valid = true;
+    } else if (tot_q > 0) {
+        if (!s->dry && !workspace) return fail(s, KVP_E_INVAL, "workspace is null");
+        if ((uintptr_t)workspace & (ALIGN - 1)) return fail(s, KVP_E_INVAL, "workspace must be 256-byte aligned");
+        if (workspace_bytes < pf.need)
+            return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)pf.need);
     }
-
     if (s->dry || tot_q == 0) return KVP_OK;
 
     hipStream_t st = (hipStream_t)hip_stream;
-    HIP_TRY(s, hipMemcpyAsync(slot->dev, slot->host, w.off, hipMemcpyHostToDevice, st));
-    CacheView view = make_view(s, cache, cc.shift, bt_dev, bt_stride);
+    CacheView view = make_view(s, cache, cc.shift, pf.bt_dev, pf.bt_stride);
 
     AppendArgs ap;
     ap.q = q;
@@ -651,8 +731,8 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     ap.q_rot = workspace;
     ap.cs = s->cs_dev;
     ap.cache = view;
-    ap.reqs = reqs_dev;
-    ap.row_req = row_req_dev;
+    ap.reqs = pf.reqs_dev;
+    ap.row_req = pf.row_req_dev;
     ap.tot_q = tot_q;
     ap.layer = layer;
     ap.n_q_heads = g.n_q_heads;
@@ -665,28 +745,28 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     AttnArgs at;
     at.q_rot = workspace;
     at.cache = view;
-    at.reqs = reqs_dev;
-    at.groups = groups_dev;
-    at.items = items_dev;
+    at.reqs = pf.reqs_dev;
+    at.groups = pf.groups_dev;
+    at.items = pf.items_dev;
     at.partials = (float *)((char *)workspace + qrb);
     at.out = out;
-    at.n_items = (int)p.items.size();
-    at.n_groups = (int)p.groups.size();
+    at.n_items = pf.n_items;
+    at.n_groups = pf.n_groups;
     at.layer = layer;
     at.n_q_heads = g.n_q_heads;
     at.n_kv = g.n_kv_heads;
     at.d = g.head_dim;
-    at.bm = p.bm;
+    at.bm = pf.bm;
     at.g = g.n_q_heads / g.n_kv_heads;
     at.scale_log2e = (float)(1.4426950408889634 / sqrt((double)g.head_dim));
-    e = launch_attention(g.dtype, at, p.kind, hip_stream);
+    e = launch_attention(g.dtype, at, pf.kind, hip_stream);
     if (e) return hip_fail(s, (hipError_t)e, "attention launch");
-    if (p.any_split) {
+    if (pf.any_split) {
         e = launch_combine(g.dtype, at, hip_stream);
         if (e) return hip_fail(s, (hipError_t)e, "combine launch");
     }
-    HIP_TRY(s, hipEventRecord(slot->ev, st));
-    slot->pending = true;
+    HIP_TRY(s, hipEventRecord(pf.slot->ev, st));
+    pf.slot->pending = true;
     return KVP_OK;
 }
 
