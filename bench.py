@@ -20,6 +20,19 @@ HBM_PEAK_GBS = 8000.0
 BF16_PEAK_TFLOPS = 2500.0
 
 
+def measured_traffic(workload):
+    """HBM bytes per assemble launch from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", "assemble_%s_pmc.txt" % workload)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def make_workload(name):
     import kvp_workloads as W
     return {
@@ -70,6 +83,9 @@ def main():
     ap.add_argument("--workload", default="llama_8k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=16)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (a known-size kernel to scale "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -115,6 +131,13 @@ def main():
         if ev:
             ev[2].record()
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -158,7 +181,7 @@ def main():
                    "layout": "paged" if w.paged else "contiguous"},
         "roofline": {"bound": "hbm", "kernel": "assemble_vec_kernel (all layers, one launch)",
                      "achieved": asm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": asm_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "frac": asm_gbs / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "bytes_per_launch": asm_bytes, "us_per_launch": asm_ms * 1e3},
         "prefill": {"us_per_layer": pre_us_layer, "bytes_per_layer": pre_bytes,
                     "flops_per_layer": pre_flops, "achieved_GBs": pre_gbs,

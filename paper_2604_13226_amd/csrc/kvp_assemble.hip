@@ -44,6 +44,26 @@ __device__ __forceinline__ uint4 pack(const float (&x)[8])
 
 constexpr int ASM_THREADS = 256;
 
+// Tile descriptor of this workgroup: from the device tile list, or derived from the packet
+// list carried in the kernel arguments (wave-uniform scalar scan).
+__device__ __forceinline__ AsmTile fetch_tile(const AsmArgs &a)
+{
+    if (a.tiles) return a.tiles[blockIdx.x];
+    const int b = (int)blockIdx.x;
+    int j = 0;
+    while (j + 1 < a.n_inline && a.inline_pk[j + 1].tile0 <= b) ++j;
+    const AsmPacket p = a.inline_pk[j];
+    AsmTile t;
+    t.src_base = p.src_base;
+    t.n_pkt = p.n_pkt;
+    t.tok0 = (b - p.tile0) * ASM_TILE_ROWS;
+    t.n_tok = p.n_pkt - t.tok0 < ASM_TILE_ROWS ? p.n_pkt - t.tok0 : ASM_TILE_ROWS;
+    t.dst_row = p.pos + t.tok0;
+    t.pos = p.pos;
+    t.req = p.req;
+    return t;
+}
+
 // Vector path: D (head_dim) is a compile-time power of two with D/2 a multiple of the
 // 16-byte vector width, so a thread's column chunk is the same in every pass.
 template <typename T, int D>
@@ -59,7 +79,7 @@ __global__ __launch_bounds__(ASM_THREADS) void assemble_vec_kernel(AsmArgs a)
     constexpr int VPASS = ASM_TILE_ROWS / VROWS;
     static_assert(CPR >= 1 && ASM_THREADS % CPR == 0 && KPASS >= 1 && VPASS >= 1, "shape");
 
-    const AsmTile tile = a.tiles[blockIdx.x];
+    const AsmTile tile = fetch_tile(a);
     const int layer = a.layer_begin + (int)blockIdx.y / a.n_kv;
     const int head = (int)blockIdx.y % a.n_kv;
     const int tid = threadIdx.x;
@@ -129,7 +149,7 @@ __global__ __launch_bounds__(ASM_THREADS) void assemble_vec_kernel(AsmArgs a)
 template <typename T>
 __global__ __launch_bounds__(ASM_THREADS) void assemble_scalar_kernel(AsmArgs a)
 {
-    const AsmTile tile = a.tiles[blockIdx.x];
+    const AsmTile tile = fetch_tile(a);
     const int layer = a.layer_begin + (int)blockIdx.y / a.n_kv;
     const int head = (int)blockIdx.y % a.n_kv;
     const int d = a.d, half = d / 2;

@@ -64,6 +64,11 @@ __device__ __forceinline__ void load_to_lds_16(const void *gptr, uint32_t lds_ad
 {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
+// same, global address = wave-uniform base + per-lane 32-bit byte offset
+__device__ __forceinline__ void load_to_lds_16(const void *sbase, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
+}
 
 // If the running reference maximum lags the true row maximum by at most this many
 // powers of two, the accumulators are not rescaled (probabilities then reach at most 2^8,
@@ -71,7 +76,12 @@ __device__ __forceinline__ void load_to_lds_16(const void *gptr, uint32_t lds_ad
 // because all three are relative to the same reference.
 constexpr float RESCALE_SLACK = 8.f;
 
-template <int STAGES>
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+// q_rot holds the rotated query already multiplied by log2(e)/sqrt(d), so S = K Q^T is in
+// log2 units.  The S accumulators start at -m_ref: after the MFMAs they hold s - m_ref and
+// the probabilities are exp2 of them with no further arithmetic.
+template <int STAGES, bool PAGED>
 __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -92,16 +102,18 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     // paged layout: this item's block ids go to LDS once, so the tile loop issues no
     // ordinary global loads (its in-flight count is what the waits below rely on)
     int *blk_ids = (int *)(lds + STAGES * STAGE_BYTES);
-    const bool paged = a.cache.layout != 0;
-    const int blk0 = paged ? (it.kv_begin >> a.cache.block_shift) : 0;
-    if (paged) {
+    const int blk0 = PAGED ? (it.kv_begin >> a.cache.block_shift) : 0;
+    if (PAGED) {
         const int nb = (kv_last >> a.cache.block_shift) - blk0 + 1;
         for (int i = tid; i < nb; i += 256)
             blk_ids[i] = a.cache.block_table[(int64_t)it.req * a.cache.max_blocks + blk0 + i];
         __syncthreads();
     }
-    const int64_t contig_base = (int64_t)it.req * a.cache.req_stride + (int64_t)a.layer * a.cache.layer_stride +
-                                (int64_t)it.kv_head * a.cache.t_cap * D;
+    // contiguous layout: wave-uniform byte address of the item's first K / V row
+    const int64_t contig_off = (int64_t)it.req * a.cache.req_stride + (int64_t)a.layer * a.cache.layer_stride +
+                               ((int64_t)it.kv_head * a.cache.t_cap + it.kv_begin) * D;
+    const char *k_item = (const char *)(kc + contig_off);
+    const char *v_item = (const char *)(vc + contig_off);
     const int64_t paged_base = (int64_t)a.layer * a.cache.layer_stride;
 
     // direct HBM -> LDS load of tile tj: wave w, instruction i fills tile rows
@@ -110,25 +122,29 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     const int slot_row = lane >> 4, slot_chunk = lane & 15;
     const int k_chunk = slot_chunk ^ ((4 * wave + slot_row) & 15);  // logical chunk fetched
     const int v_chunk = slot_chunk ^ (4 * slot_row);
+    const int last_tile_rows = it.kv_end - it.kv_begin - (n_tiles - 1) * BN;  // 1..64
     auto issue = [&](int tj) {
         const uint32_t st = lds_base + (uint32_t)((tj % STAGES) * STAGE_BYTES);
-        const int kv0 = it.kv_begin + tj * BN;
+        // rows past the range (last tile only) repeat the last row; they are masked later
+        const int max_r = tj == n_tiles - 1 ? last_tile_rows - 1 : BN - 1;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int r = 16 * i + 4 * wave + slot_row;
-            int kv = kv0 + r;
-            kv = kv < kv_last ? kv : kv_last;  // rows past the range repeat the last row (masked)
-            int64_t off;
-            if (!paged) {
-                off = contig_base + (int64_t)kv * D;
-            } else {
-                int b = blk_ids[(kv >> a.cache.block_shift) - blk0];
-                int slot = kv & ((1 << a.cache.block_shift) - 1);
-                off = paged_base + ((((int64_t)b * a.n_kv + it.kv_head) << a.cache.block_shift) + slot) * D;
-            }
+            int r = 16 * i + 4 * wave + slot_row;
+            r = r < max_r ? r : max_r;
             const uint32_t dst = st + (uint32_t)((16 * i + 4 * wave) * ROW_BYTES);
-            load_to_lds_16(kc + off + 8 * k_chunk, dst);
-            load_to_lds_16(vc + off + 8 * v_chunk, dst + TILE_BYTES);
+            if (!PAGED) {
+                const char *kt = k_item + (int64_t)tj * TILE_BYTES;
+                const char *vt = v_item + (int64_t)tj * TILE_BYTES;
+                load_to_lds_16(kt, (uint32_t)(r * ROW_BYTES + 16 * k_chunk), dst);
+                load_to_lds_16(vt, (uint32_t)(r * ROW_BYTES + 16 * v_chunk), dst + TILE_BYTES);
+            } else {
+                const int kv = it.kv_begin + tj * BN + r;
+                const int b = blk_ids[(kv >> a.cache.block_shift) - blk0];
+                const int slot = kv & ((1 << a.cache.block_shift) - 1);
+                const int64_t off = paged_base + ((((int64_t)b * a.n_kv + it.kv_head) << a.cache.block_shift) + slot) * D;
+                load_to_lds_16(kc + off + 8 * k_chunk, dst);
+                load_to_lds_16(vc + off + 8 * v_chunk, dst + TILE_BYTES);
+            }
         }
     };
     // the first tiles start their trip before anything else is fetched
@@ -166,7 +182,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     for (int eb = 0; eb < 4; ++eb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[eb][r] = 0.f;
-    float m_ref = -INFINITY, l_i = 0.f;  // reference max (scaled log2 units) and running sum
+    float m_ref = -INFINITY, l_i = 0.f;  // reference max (log2 units) and running sum
 
 #ifdef KVP_TIMING
     if (threadIdx.x == 0) a.dbg[blockIdx.x * 8 + 1] = wall_clock64();
@@ -174,8 +190,14 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     const int tr_row = (lane & 15) >> 2;
     const int tr_x = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);  // 16-byte chunk inside the 64-byte column group
     const int tr_half = 8 * (lane & 1);
-    const float c = a.scale_log2e;
 
+#ifdef KVP_TIMING
+    long long ph[6] = {0, 0, 0, 0, 0, 0};
+    long long tc = clock64();
+#define PHASE(i) do { long long t_ = clock64(); ph[i] += t_ - tc; tc = t_; } while (0)
+#else
+#define PHASE(i) do {} while (0)
+#endif
     for (int ti = 0; ti < n_tiles; ++ti) {
         // tile ti has landed once at most the loads of the tiles issued after it remain
         const int ahead = n_tiles - 1 - ti < STAGES - 2 ? n_tiles - 1 - ti : STAGES - 2;
@@ -183,19 +205,23 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
         else if (ahead == 2) wait_vmcnt<16>();
         else if (ahead == 1) wait_vmcnt<8>();
         else wait_vmcnt<0>();
+        PHASE(0);
         wg_barrier();  // every wave's part of tile ti is in LDS; everyone is done with tile ti-1
+        PHASE(1);
         if (ti + STAGES - 1 < n_tiles) issue(ti + STAGES - 1);  // refills the stage tile ti-1 used
+        PHASE(2);
 
         const int kv0 = it.kv_begin + ti * BN;
         const char *kl = lds + (ti % STAGES) * STAGE_BYTES;
         const char *vl = kl + TILE_BYTES;
 
-        // ---- S^T = K Q^T : 2 blocks of 32 kv rows x 32 query rows
+        // ---- S^T - m_ref = K Q^T - m_ref : 2 blocks of 32 kv rows x 32 query rows
+        const float init = m_ref == -INFINITY ? 0.f : -m_ref;
         floatx16 sacc[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kb][r] = 0.f;
+            for (int r = 0; r < 16; ++r) sacc[kb][r] = init;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             const int coff = 16 * ((2 * ks + h) ^ (n & 15));
@@ -215,33 +241,51 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
                     if (kv >= limit || kv >= it.kv_end) sacc[kb][r] = -INFINITY;
                 }
         }
-        float mx = fmaxf(sacc[0][0], sacc[1][0]);
+        float mx = max3(sacc[0][0], sacc[1][0], sacc[0][1]);
+        mx = max3(mx, sacc[1][1], sacc[0][2]);
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(sacc[0][r], sacc[1][r]));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;
-        if (__any(mx > m_ref + RESCALE_SLACK)) {  // wave-uniform; rare once the maxima settle
-            const float m_new = fmaxf(m_ref, mx);
-            const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_ref - m_new);
-            m_ref = m_new;
+        for (int r = 2; r < 15; ++r) mx = max3(mx, sacc[1][r], sacc[0][r + 1]);
+        mx = fmaxf(mx, sacc[1][15]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // row max relative to m_ref
+#ifdef KVP_TIMING
+        asm volatile("" : "+v"(mx));
+        PHASE(3);
+#endif
+        // The reference moves when a row sees its first visible entry (it becomes that
+        // tile's maximum) and afterwards only when the maximum outgrows the slack.
+        const bool first = m_ref == -INFINITY;
+        const bool move = first ? mx > -INFINITY : mx > RESCALE_SLACK;
+        if (__any(move)) {  // wave-uniform; rare once the maxima settle
+            const float delta = move ? mx : 0.f;
+            const float alpha = first ? 1.f : __builtin_amdgcn_exp2f(-delta);  // first: O = l = 0
+            m_ref = first ? (move ? mx : -INFINITY) : m_ref + delta;
             l_i *= alpha;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sacc[kb][r] -= delta;
 #pragma unroll
             for (int eb = 0; eb < 4; ++eb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[eb][r] *= alpha;
         }
-        const float m_sub = m_ref == -INFINITY ? 0.f : m_ref;  // nothing visible yet: p = 0
-        float rs = 0.f;
+        float rs0 = 0.f, rs1 = 0.f;
         uint32_t pk[2][8];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
-                float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][r], c, -m_sub));
-                float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][r + 1], c, -m_sub));
-                rs += p0 + p1;
+                float p0 = __builtin_amdgcn_exp2f(sacc[kb][r]);
+                float p1 = __builtin_amdgcn_exp2f(sacc[kb][r + 1]);
+                rs0 += p0;
+                rs1 += p1;
                 pk[kb][r >> 1] = pack_bf16_hw(p0, p1);
             }
-        l_i += rs;  // this lane's half of the row; the halves are added once, at the end
+        l_i += rs0 + rs1;  // this lane's half of the row; the halves are added once, at the end
+#ifdef KVP_TIMING
+        asm volatile("" : "+v"(l_i));
+        PHASE(4);
+#endif
 
         // ---- O^T += V^T P^T.  k-step j of block kb covers kv rows 32 kb + 16 j + [0, 16);
         // P^T slots 0..7 of lane-half h are rows 4h+{0..3} and 8+4h+{0..3} of that step, so
@@ -257,18 +301,33 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
                 for (int eb = 0; eb < 4; ++eb) {
                     typedef __attribute__((address_space(3))) short4v *lds_s4;
                     const int coff = 16 * (4 * (eb ^ tr_row) + tr_x);
+#ifdef KVP_EXP_PLAIN_READ
+                    short4v lo = *(const short4v *)(vp + coff);
+                    short4v hi = *(const short4v *)(vp + 8 * ROW_BYTES + coff);
+#else
                     short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(vp + coff));
                     short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(vp + 8 * ROW_BYTES + coff));
+#endif
                     union { short4v s[2]; bf16x8 v; } vf;
                     vf.s[0] = lo;
                     vf.s[1] = hi;
                     oacc[eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf, oacc[eb], 0, 0, 0);
                 }
             }
+#ifdef KVP_TIMING
+        asm volatile("" : "+v"(oacc[0]), "+v"(oacc[1]), "+v"(oacc[2]), "+v"(oacc[3]));
+        PHASE(5);
+#endif
     }
     l_i += __shfl_xor(l_i, 32, 64);
 
 #ifdef KVP_TIMING
+    if (threadIdx.x == 0) {
+        a.dbg[blockIdx.x * 8 + 4] = ph[0] + ph[1];
+        a.dbg[blockIdx.x * 8 + 5] = ph[2];
+        a.dbg[blockIdx.x * 8 + 6] = ph[3];
+        a.dbg[blockIdx.x * 8 + 7] = ph[4] | (ph[5] << 32);
+    }
     if (threadIdx.x == 0) a.dbg[blockIdx.x * 8 + 2] = wall_clock64();
 #endif
     // ---- epilogue: lane holds O[m][32 eb + 8 (r/4) + 4 h + r%4]
@@ -307,19 +366,26 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
 
 constexpr int ATTN_STAGES = 2;  // 64 KiB of tiles + block ids: two workgroups share a CU
 
-int launch_attention_mfma(const AttnArgs &a, void *stream)
+template <bool PAGED> static int launch_variant(const AttnArgs &a, void *stream)
 {
-    if (a.d != D || a.bm != BM) return (int)hipErrorInvalidValue;
-    constexpr int lds_bytes = ATTN_STAGES * STAGE_BYTES + MAX_BLOCK_IDS * 4;
+    constexpr int lds_bytes = ATTN_STAGES * STAGE_BYTES + (PAGED ? MAX_BLOCK_IDS * 4 : 0);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<ATTN_STAGES>,
+        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<ATTN_STAGES, PAGED>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(attention_mfma_kernel<ATTN_STAGES>, dim3(a.n_items), dim3(256), lds_bytes, (hipStream_t)stream, a);
+    hipLaunchKernelGGL((attention_mfma_kernel<ATTN_STAGES, PAGED>), dim3(a.n_items), dim3(256), lds_bytes,
+                       (hipStream_t)stream, a);
     return (int)hipGetLastError();
+}
+
+// The query in a.q_rot must already be multiplied by mfma_q_scale(): see the kernel.
+int launch_attention_mfma(const AttnArgs &a, void *stream)
+{
+    if (a.d != D || a.bm != BM) return (int)hipErrorInvalidValue;
+    return a.cache.layout != 0 ? launch_variant<true>(a, stream) : launch_variant<false>(a, stream);
 }
 
 }  // namespace kvp

@@ -28,12 +28,25 @@ struct CacheView {
     int32_t layout, t_cap, n_blocks, block_shift, max_blocks;
 };
 
+// Small requests carry their packet list inside the kernel arguments (no plan upload):
+// the kernel finds its tile's packet by a scan over the cumulative tile counts.
+struct AsmPacket {
+    int64_t src_base;  // element offset of the packet's K blob in the arena
+    int32_t n_pkt;     // rows of the packet
+    int32_t pos;       // Delta_j = cache row of the packet's first row
+    int32_t req;
+    int32_t tile0;     // index of the packet's first tile
+};
+constexpr int ASM_INLINE_PACKETS = 96;
+
 struct AsmArgs {
     const void *arena;
-    const float2 *cs;  // [max_positions][d/2] (cos, sin)
-    const AsmTile *tiles;
+    const float2 *cs;      // [max_positions][d/2] (cos, sin)
+    const AsmTile *tiles;  // device tile list, or nullptr: use `inline_pk`
     CacheView cache;
     int32_t n_tiles, layer_begin, n_layers_total, n_kv, d;
+    int32_t n_inline;
+    AsmPacket inline_pk[ASM_INLINE_PACKETS];
 };
 
 // ---- query prefill -------------------------------------------------------------
@@ -85,6 +98,7 @@ struct AppendArgs {
     const ReqMeta *reqs;
     const int32_t *row_req;  // [tot_q] -> request
     int32_t tot_q, layer, n_q_heads, n_kv, d, prerotated;
+    float q_scale;  // the rotated query is multiplied by this before it is stored
 };
 
 // launchers (defined next to their kernels)

@@ -37,8 +37,8 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a)
             T *dst = (T *)a.q_rot + o;
             float x = ld_elem(src + i), y = ld_elem(src + half + i);
             float xc = x * c, ys = y * s, yc = y * c, xs = x * s;
-            st_elem(dst + i, xc - ys);
-            st_elem(dst + half + i, yc + xs);
+            st_elem(dst + i, (xc - ys) * a.q_scale);
+            st_elem(dst + half + i, (yc + xs) * a.q_scale);
         } else {
             int h = hh - a.n_q_heads;
             int64_t o = ((int64_t)row * a.n_kv + h) * a.d;

@@ -130,7 +130,7 @@ struct kvp_store {
     bool dry = false;
     int n_cu = 256;
     int force_generic = 0;
-    int target_items = 0;  // 0: twice the CU count
+    int target_items = 0;  // 0: the CU count
     size_t esize = 2;
 };
 
@@ -401,6 +401,7 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
 
     // offsets Delta_j (Sec. 4.2.1 step 4: realign, then concatenate) and gather tiles
     std::vector<AsmTile> tiles;
+    std::vector<AsmPacket> packets;
     std::vector<int> ctx(n_req), first_blk(n_req, 0), n_blk(n_req, 0);
     for (int r = 0; r < n_req; ++r) {
         const kvp_request_t &q = reqs[r];
@@ -413,6 +414,7 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
             const PacketRec &p = it->second;
             if (pos + p.n_tokens > g.max_positions)
                 return fail(s, KVP_E_CAPACITY, "request %d: context exceeds max_positions %d", r, g.max_positions);
+            packets.push_back(AsmPacket{p.elem_off, p.n_tokens, (int32_t)pos, r, (int32_t)tiles.size()});
             for (int t0 = 0; t0 < p.n_tokens; t0 += ASM_TILE_ROWS) {
                 AsmTile t;
                 t.src_base = p.elem_off;
@@ -437,20 +439,27 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
     for (int r = 0; r < n_req; ++r) bt_stride = std::max(bt_stride, n_blk[r]);
 
     const int n_layers_launch = layer_end - layer_begin;
-    const uint64_t bytes = align_up(tiles.size() * sizeof(AsmTile), 64) + (uint64_t)n_req * bt_stride * 4 + 256;
-    PlanRing::Slot *slot = nullptr;
-    if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
-    int hrc = s->ring.acquire(bytes, &slot);
-    if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
-    PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
+    // Few packets and no block table: the packet list rides in the kernel arguments and
+    // nothing is uploaded.  Otherwise the tile list (and block table) go through a plan slot.
+    const bool inline_plan = (int)packets.size() <= ASM_INLINE_PACKETS && cache->layout == KVP_CONTIG;
     const AsmTile *tiles_dev = nullptr;
     const int32_t *bt_dev = nullptr;
-    AsmTile *th = w.put<AsmTile>(tiles.size(), &tiles_dev);
-    if (!tiles.empty()) memcpy(th, tiles.data(), tiles.size() * sizeof(AsmTile));
-    if (cache->layout == KVP_PAGED && bt_stride > 0) {
-        int32_t *bh = w.put<int32_t>((uint64_t)n_req * bt_stride, &bt_dev);
-        rc = compact_block_table(s, cache, n_req, first_blk, n_blk, bt_stride, bh);
-        if (rc) return rc;
+    PlanRing::Slot *slot = nullptr;
+    uint64_t upload = 0;
+    if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
+    if (!inline_plan) {
+        const uint64_t bytes = align_up(tiles.size() * sizeof(AsmTile), 64) + (uint64_t)n_req * bt_stride * 4 + 256;
+        int hrc = s->ring.acquire(bytes, &slot);
+        if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
+        PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
+        AsmTile *th = w.put<AsmTile>(tiles.size(), &tiles_dev);
+        if (!tiles.empty()) memcpy(th, tiles.data(), tiles.size() * sizeof(AsmTile));
+        if (cache->layout == KVP_PAGED && bt_stride > 0) {
+            int32_t *bh = w.put<int32_t>((uint64_t)n_req * bt_stride, &bt_dev);
+            rc = compact_block_table(s, cache, n_req, first_blk, n_blk, bt_stride, bh);
+            if (rc) return rc;
+        }
+        upload = w.off;
     }
 
     s->dbg_asm.clear();
@@ -462,11 +471,18 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
 
     if (!s->dry && !tiles.empty() && n_layers_launch > 0) {
         hipStream_t st = (hipStream_t)hip_stream;
-        HIP_TRY(s, hipMemcpyAsync(slot->dev, slot->host, w.off, hipMemcpyHostToDevice, st));
         AsmArgs a;
         a.arena = g.arena;
         a.cs = s->cs_dev;
-        a.tiles = tiles_dev;
+        a.tiles = nullptr;
+        a.n_inline = 0;
+        if (inline_plan) {
+            a.n_inline = (int)packets.size();
+            for (size_t i = 0; i < packets.size(); ++i) a.inline_pk[i] = packets[i];
+        } else {
+            HIP_TRY(s, hipMemcpyAsync(slot->dev, slot->host, upload, hipMemcpyHostToDevice, st));
+            a.tiles = tiles_dev;
+        }
         a.cache = make_view(s, cache, cc.shift, bt_dev, bt_stride);
         a.n_tiles = (int)tiles.size();
         a.layer_begin = layer_begin;
@@ -475,8 +491,10 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
         a.d = g.head_dim;
         int e = launch_assemble(g.dtype, a, n_layers_launch, hip_stream);
         if (e) return hip_fail(s, (hipError_t)e, "assemble launch");
-        HIP_TRY(s, hipEventRecord(slot->ev, st));
-        slot->pending = true;
+        if (slot) {
+            HIP_TRY(s, hipEventRecord(slot->ev, st));
+            slot->pending = true;
+        }
     }
     for (int r = 0; r < n_req; ++r) cache->ctx_len[r] = ctx[r];
     return KVP_OK;
@@ -499,7 +517,7 @@ constexpr int MFMA_BM = 128;
 constexpr int GENERIC_BM = 8;
 constexpr int MAX_SPLITS = 64;
 
-int target_items(const kvp_store *s) { return s->target_items > 0 ? s->target_items : 2 * s->n_cu; }
+int target_items(const kvp_store *s) { return s->target_items > 0 ? s->target_items : s->n_cu; }
 
 // Groups of packed rows and their split-KV items.  Every group of a request gets the same
 // split length (a multiple of bn rows), chosen so the launch has about target_items work
@@ -739,6 +757,8 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     ap.n_kv = g.n_kv_heads;
     ap.d = g.head_dim;
     ap.prerotated = (flags & KVP_PREROTATED) ? 1 : 0;
+    // the MFMA kernel takes the query pre-multiplied by log2(e)/sqrt(d); the generic one scales itself
+    ap.q_scale = pf.kind == ATTN_MFMA ? (float)(1.4426950408889634 / sqrt((double)g.head_dim)) : 1.f;
     int e = launch_append(g.dtype, ap, hip_stream);
     if (e) return hip_fail(s, (hipError_t)e, "append launch");
 
