@@ -179,6 +179,13 @@ def kvp_packet_bytes(store, n_tokens):
     return int(load().kvp_packet_bytes(ctypes.byref(store.cfg), int(n_tokens)))
 
 
+def packet_bytes(n_layers, n_kv_heads, head_dim, dtype, n_tokens):
+    """kvp_packet_bytes for a configuration not yet turned into a store (to size an arena)."""
+    cfg = kvp_config_t()
+    cfg.n_layers, cfg.n_kv_heads, cfg.head_dim, cfg.dtype = n_layers, n_kv_heads, head_dim, _dtype_code(dtype)
+    return int(load().kvp_packet_bytes(ctypes.byref(cfg), int(n_tokens)))
+
+
 class Cache:
     """kvp_cache_t plus the tensors/arrays it points to.
 

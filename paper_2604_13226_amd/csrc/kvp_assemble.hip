@@ -48,16 +48,16 @@ constexpr int ASM_THREADS = 256;
 // list carried in the kernel arguments (wave-uniform scalar scan).
 __device__ __forceinline__ AsmTile fetch_tile(const AsmArgs &a)
 {
-    if (a.tiles) return a.tiles[blockIdx.x];
     const int b = (int)blockIdx.x;
+    if (a.tiles) return a.tiles[b];
     int j = 0;
     while (j + 1 < a.n_inline && a.inline_pk[j + 1].tile0 <= b) ++j;
     const AsmPacket p = a.inline_pk[j];
     AsmTile t;
     t.src_base = p.src_base;
-    t.n_pkt = p.n_pkt;
-    t.tok0 = (b - p.tile0) * ASM_TILE_ROWS;
-    t.n_tok = p.n_pkt - t.tok0 < ASM_TILE_ROWS ? p.n_pkt - t.tok0 : ASM_TILE_ROWS;
+    t.stride = p.stride;
+    t.tok0 = (b - p.tile0) * a.tile_rows;
+    t.n_tok = p.n_pkt - t.tok0 < a.tile_rows ? p.n_pkt - t.tok0 : a.tile_rows;
     t.dst_row = p.pos + t.tok0;
     t.pos = p.pos;
     t.req = p.req;
@@ -66,27 +66,47 @@ __device__ __forceinline__ AsmTile fetch_tile(const AsmArgs &a)
 
 // Vector path: D (head_dim) is a compile-time power of two with D/2 a multiple of the
 // 16-byte vector width, so a thread's column chunk is the same in every pass.
-template <typename T, int D>
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+template <bool NT> __device__ __forceinline__ uint4 ld16(const void *p)
+{
+    if (NT) {
+        u32x4 v = __builtin_nontemporal_load((const u32x4 *)p);
+        return make_uint4(v.x, v.y, v.z, v.w);
+    }
+    return *(const uint4 *)p;
+}
+template <bool NT> __device__ __forceinline__ void st16(void *p, const uint4 &u)
+{
+    if (NT) {
+        u32x4 v = {u.x, u.y, u.z, u.w};
+        __builtin_nontemporal_store(v, (u32x4 *)p);
+    } else {
+        *(uint4 *)p = u;
+    }
+}
+
+template <typename T, int D, int ROWS, bool NT>
 __global__ __launch_bounds__(ASM_THREADS) void assemble_vec_kernel(AsmArgs a)
 {
     constexpr int N = Vec16<T>::N;
     constexpr int HALF = D / 2;
     constexpr int CPR = HALF / N;                  // K: (lo, hi) chunk pairs per row
     constexpr int KROWS = ASM_THREADS / CPR;       // rows per pass
-    constexpr int KPASS = ASM_TILE_ROWS / KROWS;
+    constexpr int KPASS = (ROWS + KROWS - 1) / KROWS;
     constexpr int VCPR = D / N;                    // V: chunks per row
     constexpr int VROWS = ASM_THREADS / VCPR;
-    constexpr int VPASS = ASM_TILE_ROWS / VROWS;
+    constexpr int VPASS = (ROWS + VROWS - 1) / VROWS;
     static_assert(CPR >= 1 && ASM_THREADS % CPR == 0 && KPASS >= 1 && VPASS >= 1, "shape");
 
     const AsmTile tile = fetch_tile(a);
-    const int layer = a.layer_begin + (int)blockIdx.y / a.n_kv;
-    const int head = (int)blockIdx.y % a.n_kv;
+    const int lh = (int)blockIdx.y;
+    const int layer = a.layer_begin + lh / a.n_kv;
+    const int head = lh % a.n_kv;
     const int tid = threadIdx.x;
 
     const T *arena = (const T *)a.arena;
-    const int64_t blob = (int64_t)a.n_layers_total * a.n_kv * tile.n_pkt * D;
-    const T *ksrc = arena + tile.src_base + (((int64_t)layer * a.n_kv + head) * tile.n_pkt + tile.tok0) * D;
+    const int64_t blob = (int64_t)a.n_layers_total * a.n_kv * tile.stride * D;
+    const T *ksrc = arena + tile.src_base + (((int64_t)layer * a.n_kv + head) * tile.stride + tile.tok0) * D;
     const T *vsrc = ksrc + blob;
     T *kdst = (T *)a.cache.k;
     T *vdst = (T *)a.cache.v;
@@ -98,8 +118,8 @@ __global__ __launch_bounds__(ASM_THREADS) void assemble_vec_kernel(AsmArgs a)
     for (int p = 0; p < KPASS; ++p) {
         int r = kr0 + p * KROWS;
         if (r < tile.n_tok) {
-            klo[p] = *(const uint4 *)(ksrc + (int64_t)r * D + kc * N);
-            khi[p] = *(const uint4 *)(ksrc + (int64_t)r * D + HALF + kc * N);
+            klo[p] = ld16<NT>(ksrc + (int64_t)r * D + kc * N);
+            khi[p] = ld16<NT>(ksrc + (int64_t)r * D + HALF + kc * N);
         }
     }
     const int vc = tid % VCPR, vr0 = tid / VCPR;
@@ -107,7 +127,7 @@ __global__ __launch_bounds__(ASM_THREADS) void assemble_vec_kernel(AsmArgs a)
 #pragma unroll
     for (int p = 0; p < VPASS; ++p) {
         int r = vr0 + p * VROWS;
-        if (r < tile.n_tok) vv[p] = *(const uint4 *)(vsrc + (int64_t)r * D + vc * N);
+        if (r < tile.n_tok) vv[p] = ld16<NT>(vsrc + (int64_t)r * D + vc * N);
     }
     float c[N], s[N];
     {
@@ -121,7 +141,7 @@ __global__ __launch_bounds__(ASM_THREADS) void assemble_vec_kernel(AsmArgs a)
         int r = vr0 + p * VROWS;
         if (r < tile.n_tok) {
             int64_t o = cache_row_off(a.cache, tile.req, layer, head, tile.dst_row + r, a.n_kv, D);
-            *(uint4 *)(vdst + o + vc * N) = vv[p];
+            st16<NT>(vdst + o + vc * N, vv[p]);
         }
     }
 #pragma unroll
@@ -139,8 +159,8 @@ __global__ __launch_bounds__(ASM_THREADS) void assemble_vec_kernel(AsmArgs a)
                 hi[i] = yc + xs;
             }
             int64_t o = cache_row_off(a.cache, tile.req, layer, head, tile.dst_row + r, a.n_kv, D);
-            *(uint4 *)(kdst + o + kc * N) = pack(lo);
-            *(uint4 *)(kdst + o + HALF + kc * N) = pack(hi);
+            st16<NT>(kdst + o + kc * N, pack(lo));
+            st16<NT>(kdst + o + HALF + kc * N, pack(hi));
         }
     }
 }
@@ -150,12 +170,13 @@ template <typename T>
 __global__ __launch_bounds__(ASM_THREADS) void assemble_scalar_kernel(AsmArgs a)
 {
     const AsmTile tile = fetch_tile(a);
-    const int layer = a.layer_begin + (int)blockIdx.y / a.n_kv;
-    const int head = (int)blockIdx.y % a.n_kv;
+    const int lh = (int)blockIdx.y;
+    const int layer = a.layer_begin + lh / a.n_kv;
+    const int head = lh % a.n_kv;
     const int d = a.d, half = d / 2;
     const T *arena = (const T *)a.arena;
-    const int64_t blob = (int64_t)a.n_layers_total * a.n_kv * tile.n_pkt * d;
-    const T *ksrc = arena + tile.src_base + (((int64_t)layer * a.n_kv + head) * tile.n_pkt + tile.tok0) * d;
+    const int64_t blob = (int64_t)a.n_layers_total * a.n_kv * tile.stride * d;
+    const T *ksrc = arena + tile.src_base + (((int64_t)layer * a.n_kv + head) * tile.stride + tile.tok0) * d;
     const T *vsrc = ksrc + blob;
     T *kdst = (T *)a.cache.k;
     T *vdst = (T *)a.cache.v;
@@ -173,21 +194,35 @@ __global__ __launch_bounds__(ASM_THREADS) void assemble_scalar_kernel(AsmArgs a)
     }
 }
 
+template <typename T, int D> static void launch_vec(const AsmArgs &a, dim3 grid, hipStream_t st, bool nt)
+{
+    dim3 block(ASM_THREADS);
+#define KVP_ASM_CASE(R)                                                                                   \
+    if (nt) hipLaunchKernelGGL((assemble_vec_kernel<T, D, R, true>), grid, block, 0, st, a);              \
+    else hipLaunchKernelGGL((assemble_vec_kernel<T, D, R, false>), grid, block, 0, st, a)
+    if (a.tile_rows == 16) { KVP_ASM_CASE(16); }
+    else if (a.tile_rows == 32) { KVP_ASM_CASE(32); }
+    else { KVP_ASM_CASE(64); }
+#undef KVP_ASM_CASE
+}
+
 int launch_assemble(int dtype, const AsmArgs &a, int n_layers_launch, void *stream)
 {
     if (a.n_tiles == 0 || n_layers_launch == 0) return 0;
+    if (a.tile_rows != 16 && a.tile_rows != 32 && a.tile_rows != 64) return (int)hipErrorInvalidValue;
     dim3 grid((unsigned)a.n_tiles, (unsigned)(n_layers_launch * a.n_kv));
     dim3 block(ASM_THREADS);
     hipStream_t st = (hipStream_t)stream;
+    const bool nt = a.nontemporal != 0;
     if (dtype == 1) {
-        if (a.d == 128) hipLaunchKernelGGL((assemble_vec_kernel<bf16_t, 128>), grid, block, 0, st, a);
-        else if (a.d == 64) hipLaunchKernelGGL((assemble_vec_kernel<bf16_t, 64>), grid, block, 0, st, a);
-        else if (a.d == 256) hipLaunchKernelGGL((assemble_vec_kernel<bf16_t, 256>), grid, block, 0, st, a);
+        if (a.d == 128) launch_vec<bf16_t, 128>(a, grid, st, nt);
+        else if (a.d == 64) launch_vec<bf16_t, 64>(a, grid, st, nt);
+        else if (a.d == 256) launch_vec<bf16_t, 256>(a, grid, st, nt);
         else hipLaunchKernelGGL((assemble_scalar_kernel<bf16_t>), grid, block, 0, st, a);
     } else {
-        if (a.d == 128) hipLaunchKernelGGL((assemble_vec_kernel<float, 128>), grid, block, 0, st, a);
-        else if (a.d == 64) hipLaunchKernelGGL((assemble_vec_kernel<float, 64>), grid, block, 0, st, a);
-        else if (a.d == 256) hipLaunchKernelGGL((assemble_vec_kernel<float, 256>), grid, block, 0, st, a);
+        if (a.d == 128) launch_vec<float, 128>(a, grid, st, nt);
+        else if (a.d == 64) launch_vec<float, 64>(a, grid, st, nt);
+        else if (a.d == 256) launch_vec<float, 256>(a, grid, st, nt);
         else hipLaunchKernelGGL((assemble_scalar_kernel<float>), grid, block, 0, st, a);
     }
     return (int)hipGetLastError();

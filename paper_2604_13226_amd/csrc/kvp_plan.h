@@ -9,7 +9,7 @@ namespace kvp {
 // The same tile list serves every (layer, kv head): blockIdx.y selects those.
 struct AsmTile {
     int64_t src_base;  // element offset of the packet's K blob in the arena
-    int32_t n_pkt;     // rows of the packet (stride between heads in the blob)
+    int32_t stride;    // rows between consecutive (layer, head) slices of the blob
     int32_t tok0;      // first packet row of this tile
     int32_t n_tok;     // rows in this tile
     int32_t dst_row;   // cache row (absolute position) of tok0
@@ -18,7 +18,7 @@ struct AsmTile {
 };
 static_assert(sizeof(AsmTile) == 32, "AsmTile is 32 bytes");
 
-constexpr int ASM_TILE_ROWS = 64;
+constexpr int ASM_TILE_ROWS_MAX = 64;  // tiles hold 16, 32 or 64 rows
 
 struct CacheView {
     void *k, *v;
@@ -33,9 +33,11 @@ struct CacheView {
 struct AsmPacket {
     int64_t src_base;  // element offset of the packet's K blob in the arena
     int32_t n_pkt;     // rows of the packet
+    int32_t stride;    // rows between consecutive (layer, head) slices of the blob
     int32_t pos;       // Delta_j = cache row of the packet's first row
     int32_t req;
     int32_t tile0;     // index of the packet's first tile
+    int32_t pad;
 };
 constexpr int ASM_INLINE_PACKETS = 96;
 
@@ -45,6 +47,7 @@ struct AsmArgs {
     const AsmTile *tiles;  // device tile list, or nullptr: use `inline_pk`
     CacheView cache;
     int32_t n_tiles, layer_begin, n_layers_total, n_kv, d;
+    int32_t tile_rows, nontemporal;
     int32_t n_inline;
     AsmPacket inline_pk[ASM_INLINE_PACKETS];
 };

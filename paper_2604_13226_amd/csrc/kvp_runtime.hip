@@ -27,6 +27,7 @@ inline uint64_t align_up(uint64_t x, uint64_t a = ALIGN) { return (x + a - 1) / 
 struct PacketRec {
     int64_t elem_off;  // element offset of the blob in the arena
     int32_t n_tokens;
+    int32_t stride;    // rows between (layer, head) slices: n_tokens + slice padding
 };
 
 // Ring of pinned-host / device twin buffers that carry one call's plan each.  A slot is
@@ -131,6 +132,7 @@ struct kvp_store {
     int n_cu = 256;
     int force_generic = 0;
     int target_items = 0;  // 0: the CU count
+    int asm_tile_rows = 32, asm_nontemporal = 0;
     size_t esize = 2;
 };
 
@@ -182,6 +184,11 @@ void build_cos_sin(const std::vector<float> &inv_freq, int max_pos, std::vector<
     for (int t = 0; t < nt; ++t) th.emplace_back(work, t);
     for (auto &t : th) t.join();
 }
+
+// Rows between consecutive (layer, head) slices of a packet blob.  No padding: skewing
+// equal-length packets by a few rows per slice / per blob was measured and changed nothing.
+int slice_pad_rows(int) { return 0; }
+int blob_pad_rows(int) { return 0; }
 
 struct CacheCheck {
     int shift = 0;
@@ -274,7 +281,8 @@ uint64_t kvp_packet_bytes(const kvp_config_t *cfg, int32_t n_tokens)
 {
     if (!cfg || n_tokens < 0) return 0;
     uint64_t es = cfg->dtype == KVP_BF16 ? 2 : 4;
-    return align_up(2ull * cfg->n_layers * cfg->n_kv_heads * (uint64_t)n_tokens * cfg->head_dim * es);
+    const uint64_t stride = (uint64_t)n_tokens + slice_pad_rows(n_tokens);
+    return align_up((2ull * cfg->n_layers * cfg->n_kv_heads * stride + blob_pad_rows(n_tokens)) * cfg->head_dim * es);
 }
 
 int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
@@ -309,6 +317,10 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
     s->cfg.inv_freq = nullptr;
     const char *fg = getenv("KVP_FORCE_GENERIC_ATTENTION");
     s->force_generic = fg && fg[0] == '1';
+    const char *tr = getenv("KVP_ASM_TILE_ROWS");  // tuning knobs of the gather kernel
+    if (tr && (atoi(tr) == 16 || atoi(tr) == 32 || atoi(tr) == 64)) s->asm_tile_rows = atoi(tr);
+    const char *nt = getenv("KVP_ASM_NONTEMPORAL");
+    if (nt) s->asm_nontemporal = nt[0] == '1';
     const char *ti = getenv("KVP_ATTN_TARGET_ITEMS");  // test knob: how finely split-KV cuts
     if (ti && atoi(ti) > 0) s->target_items = std::min(atoi(ti), 1 << 16);
     if (!dry) {
@@ -358,8 +370,11 @@ int kvp_store_put(kvp_store_t *s, int64_t packet_id, int32_t n_tokens, const voi
     if (!s->dry && (!k || !v)) return fail(s, KVP_E_INVAL, "k or v is null");
     if (s->dir.count(packet_id)) return fail(s, KVP_E_EXISTS, "packet %lld already stored", (long long)packet_id);
     const kvp_config_t &g = s->cfg;
-    const uint64_t half_bytes = (uint64_t)g.n_layers * g.n_kv_heads * (uint64_t)n_tokens * g.head_dim * s->esize;
-    const uint64_t need = align_up(2 * half_bytes);
+    const uint64_t row_bytes = (uint64_t)g.head_dim * s->esize;
+    const int stride = n_tokens + slice_pad_rows(n_tokens);
+    const uint64_t n_slices = (uint64_t)g.n_layers * g.n_kv_heads;
+    const uint64_t half_bytes = n_slices * stride * row_bytes;
+    const uint64_t need = align_up(2 * half_bytes + blob_pad_rows(n_tokens) * row_bytes);
     if (s->used_bytes + need > g.arena_bytes)
         return fail(s, KVP_E_NOSPACE, "arena full: %llu used + %llu needed > %llu", (unsigned long long)s->used_bytes,
                     (unsigned long long)need, (unsigned long long)g.arena_bytes);
@@ -368,11 +383,12 @@ int kvp_store_put(kvp_store_t *s, int64_t packet_id, int32_t n_tokens, const voi
         char *dst = (char *)g.arena + s->used_bytes;
         hipMemcpyKind kind = src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
         hipStream_t st = (hipStream_t)hip_stream;
-        HIP_TRY(s, hipMemcpyAsync(dst, k, half_bytes, kind, st));
-        HIP_TRY(s, hipMemcpyAsync(dst + half_bytes, v, half_bytes, kind, st));
+        const uint64_t slice_bytes = (uint64_t)n_tokens * row_bytes;
+        HIP_TRY(s, hipMemcpy2DAsync(dst, stride * row_bytes, k, slice_bytes, slice_bytes, n_slices, kind, st));
+        HIP_TRY(s, hipMemcpy2DAsync(dst + half_bytes, stride * row_bytes, v, slice_bytes, slice_bytes, n_slices, kind, st));
         if (!src_on_device) HIP_TRY(s, hipStreamSynchronize(st));  // host buffers may be reused on return
     }
-    s->dir[packet_id] = PacketRec{(int64_t)(s->used_bytes / s->esize), n_tokens};
+    s->dir[packet_id] = PacketRec{(int64_t)(s->used_bytes / s->esize), n_tokens, stride};
     s->used_bytes += need;
     return KVP_OK;
 }
@@ -414,13 +430,13 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
             const PacketRec &p = it->second;
             if (pos + p.n_tokens > g.max_positions)
                 return fail(s, KVP_E_CAPACITY, "request %d: context exceeds max_positions %d", r, g.max_positions);
-            packets.push_back(AsmPacket{p.elem_off, p.n_tokens, (int32_t)pos, r, (int32_t)tiles.size()});
-            for (int t0 = 0; t0 < p.n_tokens; t0 += ASM_TILE_ROWS) {
+            packets.push_back(AsmPacket{p.elem_off, p.n_tokens, p.stride, (int32_t)pos, r, (int32_t)tiles.size(), 0});
+            for (int t0 = 0; t0 < p.n_tokens; t0 += s->asm_tile_rows) {
                 AsmTile t;
                 t.src_base = p.elem_off;
-                t.n_pkt = p.n_tokens;
+                t.stride = p.stride;
                 t.tok0 = t0;
-                t.n_tok = std::min(ASM_TILE_ROWS, p.n_tokens - t0);
+                t.n_tok = std::min(s->asm_tile_rows, p.n_tokens - t0);
                 t.dst_row = (int32_t)pos + t0;
                 t.pos = (int32_t)pos;
                 t.req = r;
@@ -465,7 +481,7 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
     s->dbg_asm.clear();
     s->dbg_asm.push_back((int64_t)tiles.size());
     for (const AsmTile &t : tiles) {
-        int64_t row[8] = {t.src_base, t.n_pkt, t.tok0, t.n_tok, t.dst_row, t.pos, t.req, 0};
+        int64_t row[8] = {t.src_base, t.stride, t.tok0, t.n_tok, t.dst_row, t.pos, t.req, 0};
         s->dbg_asm.insert(s->dbg_asm.end(), row, row + 8);
     }
 
@@ -485,6 +501,8 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
         }
         a.cache = make_view(s, cache, cc.shift, bt_dev, bt_stride);
         a.n_tiles = (int)tiles.size();
+        a.tile_rows = s->asm_tile_rows;
+        a.nontemporal = s->asm_nontemporal;
         a.layer_begin = layer_begin;
         a.n_layers_total = g.n_layers;
         a.n_kv = g.n_kv_heads;

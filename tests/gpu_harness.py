@@ -21,9 +21,8 @@ def needed_packets(w):
 
 def build_store(w, kvp, device="cuda:0", packets=None, max_positions=None, extra_bytes=0):
     packets = needed_packets(w) if packets is None else packets
-    es = w.elem_bytes
-    per_tok = 2 * w.n_layers * w.n_kv_heads * w.head_dim * es
-    arena = sum((int(w.packet_lens[p]) * per_tok + 255) // 256 * 256 for p in packets) + extra_bytes
+    arena = sum(kvp.packet_bytes(w.n_layers, w.n_kv_heads, w.head_dim, w.dtype, int(w.packet_lens[p]))
+                for p in packets) + extra_bytes
     if max_positions is None:
         max_positions = max([w.ctx_len(r) + w.requests[r].n_q for r in range(len(w.requests))] + [1]) + 64
     store = kvp.kvp_store_create(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype,

@@ -57,10 +57,14 @@ def test_create_rejects_bad_config(bad):
 
 
 def test_directory_and_arena_accounting():
-    s = dry_store(arena_bytes=3 * 2 * 2 * 2 * 100 * 128 * 2)
-    per100 = 2 * 2 * 2 * 100 * 128 * 2
+    per100 = kvp.packet_bytes(2, 2, 128, "bf16", 100)
+    raw100 = 2 * 2 * 2 * 100 * 128 * 2
+    assert raw100 <= per100 <= raw100 * 1.05 and per100 % 256 == 0
+    per200 = kvp.packet_bytes(2, 2, 128, "bf16", 200)
+    s = dry_store(arena_bytes=per100 + per200)
     assert kvp.kvp_packet_bytes(s, 100) == per100
     assert kvp.kvp_packet_bytes(s, 1) == 2 * 2 * 2 * 128 * 2
+    assert kvp.kvp_packet_bytes(s, 200) <= 2 * per100
     kvp.kvp_store_put(s, 7, None, None, n_tokens=100)
     assert kvp.kvp_store_packet_len(s, 7) == 100
     assert kvp.kvp_store_packet_len(s, 8) == kvp.KVP_E_NOTFOUND
@@ -78,7 +82,7 @@ def test_directory_and_arena_accounting():
     with pytest.raises(kvp.KvpError) as e:
         kvp.kvp_store_put(s, 10, None, None, n_tokens=1)
     assert e.value.code == kvp.KVP_E_NOSPACE
-    assert kvp.kvp_store_bytes_used(s) == 3 * per100          # failed puts changed nothing
+    assert kvp.kvp_store_bytes_used(s) == per100 + per200     # failed puts changed nothing
     assert kvp.kvp_store_packet_len(s, 10) == kvp.KVP_E_NOTFOUND
 
 
@@ -103,8 +107,8 @@ def test_assemble_plan_offsets_and_tiles():
         rows = t[t[:, 6] == r]
         assert sorted(set(rows[:, 5])) == want_pos[r]
         covered = np.zeros(int(cache.ctx_len[r]), int)
-        for src, n_pkt, tok0, n_tok, dst, pos, _, _ in rows:
-            assert 1 <= n_tok <= 64 and tok0 + n_tok <= n_pkt
+        for src, stride, tok0, n_tok, dst, pos, _, _ in rows:
+            assert 1 <= n_tok <= 64 and tok0 + n_tok <= stride
             assert dst == pos + tok0
             covered[dst:dst + n_tok] += 1
         base = 0 if r == 0 else 10
