@@ -20,6 +20,13 @@
 // conflicts are avoided by choosing WHICH 16-byte chunk of a row each lane fetches:
 // K row r keeps logical chunk c at physical chunk c ^ (r & 15), V row r at c ^ 4 (r & 3).
 //
+// The kernel also does the query side of the layer (Sec. 4.2.1 step 4): every workgroup
+// rotates its own 128 query rows to positions ctx_len + t in registers (the RoPE partner of
+// element e is e + 64, which the MFMA operand layout keeps in the same lane), and the
+// workgroups whose kv range reaches into the query rows first rotate K_new, write it and
+// V_new to the cache rows ctx_len + t, and only then start loading tiles.  Several
+// workgroups may write the same rows: they write the same bytes.
+//
 // HBM traffic: every K/V row of the range is read once per group of 128 packed rows.
 #include "kvp_device.h"
 
@@ -78,8 +85,7 @@ constexpr float RESCALE_SLACK = 8.f;
 
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
-// q_rot holds the rotated query already multiplied by log2(e)/sqrt(d), so S = K Q^T is in
-// log2 units.  The S accumulators start at -m_ref: after the MFMAs they hold s - m_ref and
+// The query is held rotated and multiplied by log2(e)/sqrt(d), so S = K Q^T is in log2 units.  The S accumulators start at -m_ref: after the MFMAs they hold s - m_ref and
 // the probabilities are exp2 of them with no further arithmetic.
 template <int STAGES, bool PAGED>
 __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
@@ -147,10 +153,70 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
             }
         }
     };
-    // the first tiles start their trip before anything else is fetched
+    // a first tile that lies wholly inside the packet prefix can start its trip right away
+    const bool early0 = n_tiles > 0 && it.kv_begin + BN <= it.ctx_len;
+    if (early0) issue(0);
+
+    // ---- query rows inside this item's range: rotate K_new to its row's position and
+    // append K_new / V_new before any tile load can touch those rows
+    {
+#pragma clang fp contract(off)  // same separately-rounded arithmetic as the gather kernel
+        const int tail_lo = it.kv_begin > it.ctx_len ? it.kv_begin : it.ctx_len;
+        const int n_tail = it.kv_end - tail_lo;  // > 0 only for items that reach the query rows
+        if (n_tail > 0) {
+            bf16_t *kcw = (bf16_t *)a.cache.k;
+            bf16_t *vcw = (bf16_t *)a.cache.v;
+            for (int idx = tid; idx < n_tail * 24; idx += 256) {
+                const int row = tail_lo + idx / 24, cidx = idx % 24;  // 8 K chunk pairs + 16 V chunks
+                const int64_t src = ((int64_t)(it.q_off + row - it.ctx_len) * a.n_kv + it.kv_head) * D;
+                int64_t dst;
+                if (!PAGED) {
+                    dst = contig_off + (int64_t)(row - it.kv_begin) * D;
+                } else {
+                    const int b = blk_ids[(row >> a.cache.block_shift) - blk0];
+                    const int slot = row & ((1 << a.cache.block_shift) - 1);
+                    dst = paged_base + ((((int64_t)b * a.n_kv + it.kv_head) << a.cache.block_shift) + slot) * D;
+                }
+                if (cidx >= 8) {
+                    const int e = 8 * (cidx - 8);
+                    *(uint4 *)(vcw + dst + e) = *(const uint4 *)((const bf16_t *)a.v_new + src + e);
+                } else {
+                    const int e = 8 * cidx;
+                    const uint4 ulo = *(const uint4 *)((const bf16_t *)a.k_new + src + e);
+                    const uint4 uhi = *(const uint4 *)((const bf16_t *)a.k_new + src + 64 + e);
+                    const uint32_t wl[4] = {ulo.x, ulo.y, ulo.z, ulo.w}, wh[4] = {uhi.x, uhi.y, uhi.z, uhi.w};
+                    uint32_t ol[4], oh[4];
+                    const float4 *csr = (const float4 *)(a.cs + (int64_t)row * 64 + e);
+                    float4 cs4[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) cs4[j] = a.prerotated ? make_float4(1.f, 0.f, 1.f, 0.f) : csr[j];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        float lo2[2], hi2[2];
+#pragma unroll
+                        for (int u = 0; u < 2; ++u) {
+                            const float x = __uint_as_float(u ? (wl[j] & 0xFFFF0000u) : (wl[j] << 16));
+                            const float y = __uint_as_float(u ? (wh[j] & 0xFFFF0000u) : (wh[j] << 16));
+                            const float c = u ? cs4[j].z : cs4[j].x, sn = u ? cs4[j].w : cs4[j].y;
+                            const float xc = x * c, ys = y * sn, yc = y * c, xs = x * sn;
+                            lo2[u] = xc - ys;
+                            hi2[u] = yc + xs;
+                        }
+                        ol[j] = (uint32_t)f32_to_bf16(lo2[0]) | ((uint32_t)f32_to_bf16(lo2[1]) << 16);
+                        oh[j] = (uint32_t)f32_to_bf16(hi2[0]) | ((uint32_t)f32_to_bf16(hi2[1]) << 16);
+                    }
+                    *(uint4 *)(kcw + dst + e) = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+                    *(uint4 *)(kcw + dst + 64 + e) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+                }
+            }
+            wait_vmcnt<0>();   // this wave's stores have reached the L2
+            __syncthreads();   // ... and so have every other wave's
+        }
+    }
+
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
-        if (s < n_tiles) issue(s);
+        if (s < n_tiles && !(s == 0 && early0)) issue(s);
 
     // this lane's query row
     const int rr = 32 * wave + n;
@@ -161,14 +227,44 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     // smallest limit among the wave's rows (rows are ordered by query token)
     const int wave_limit = it.ctx_len + (it.m0 + 32 * wave) / g + 1;
 
-    // B operand of S^T = K Q^T: lane holds Q[m][16 ks + 8 h .. +7] for ks = 0..7
+    // B operand of S^T = K Q^T: lane holds Q[m][16 ks + 8 h .. +7] for ks = 0..7, rotated to
+    // position ctx_len + t and multiplied by log2(e)/sqrt(d).  Element 16 ks + 8 h + j (ks < 4)
+    // pairs with the same slot of ks + 4.
     bf16x8 qf[8];
     {
-        const bf16_t *qp = (const bf16_t *)a.q_rot + ((int64_t)(it.q_off + t) * a.n_q_heads + hq) * D + 8 * h;
+        const bf16_t *qp = (const bf16_t *)a.q + ((int64_t)(it.q_off + t) * a.n_q_heads + hq) * D + 8 * h;
+        uint4 qraw[8];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            uint4 u = row_ok ? *(const uint4 *)(qp + 16 * ks) : make_uint4(0, 0, 0, 0);
-            qf[ks] = __builtin_bit_cast(bf16x8, u);
+        for (int ks = 0; ks < 8; ++ks) qraw[ks] = row_ok ? *(const uint4 *)(qp + 16 * ks) : make_uint4(0, 0, 0, 0);
+        const float4 *csr = (const float4 *)(a.cs + (int64_t)(it.ctx_len + t) * 64 + 8 * h);
+        const bool rot = !a.prerotated && row_ok;
+        float4 cs4[4][4];  // (cos, sin) pairs of elements 16 ks + 8 h + 2 j, + 1
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) cs4[ks][j] = rot ? csr[8 * ks + j] : make_float4(1.f, 0.f, 1.f, 0.f);
+        const float qs = a.scale_log2e;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const uint32_t wl[4] = {qraw[ks].x, qraw[ks].y, qraw[ks].z, qraw[ks].w};
+            const uint32_t wh[4] = {qraw[ks + 4].x, qraw[ks + 4].y, qraw[ks + 4].z, qraw[ks + 4].w};
+            uint32_t ol[4], oh[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float lo2[2], hi2[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const float x = __uint_as_float(u ? (wl[j] & 0xFFFF0000u) : (wl[j] << 16));
+                    const float y = __uint_as_float(u ? (wh[j] & 0xFFFF0000u) : (wh[j] << 16));
+                    const float c = u ? cs4[ks][j].z : cs4[ks][j].x, sn = u ? cs4[ks][j].w : cs4[ks][j].y;
+                    lo2[u] = (x * c - y * sn) * qs;
+                    hi2[u] = (y * c + x * sn) * qs;
+                }
+                ol[j] = pack_bf16_hw(lo2[0], lo2[1]);
+                oh[j] = pack_bf16_hw(hi2[0], hi2[1]);
+            }
+            qf[ks] = __builtin_bit_cast(bf16x8, make_uint4(ol[0], ol[1], ol[2], ol[3]));
+            qf[ks + 4] = __builtin_bit_cast(bf16x8, make_uint4(oh[0], oh[1], oh[2], oh[3]));
         }
     }
     // Pin Q in registers here: the compiler then places its wait for the Q loads before the
@@ -208,8 +304,6 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
         PHASE(0);
         wg_barrier();  // every wave's part of tile ti is in LDS; everyone is done with tile ti-1
         PHASE(1);
-        if (ti + STAGES - 1 < n_tiles) issue(ti + STAGES - 1);  // refills the stage tile ti-1 used
-        PHASE(2);
 
         const int kv0 = it.kv_begin + ti * BN;
         const char *kl = lds + (ti % STAGES) * STAGE_BYTES;
@@ -235,6 +329,10 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
             sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], sacc[0], 0, 0, 0);
             sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], sacc[1], 0, 0, 0);
         }
+        // The next tile's loads are issued while the matrix cores work on S: they refill the
+        // stage tile ti-1 used, which every wave left before the barrier above.
+        if (ti + STAGES - 1 < n_tiles) issue(ti + STAGES - 1);
+        PHASE(2);
 
         // ---- online softmax; accumulator r of block kb is kv row kv0 + 32 kb + 8 (r/4) + 4 h + r%4
         if (kv0 + BN > wave_limit || kv0 + BN > it.kv_end) {  // wave-uniform: tail tiles only
@@ -274,10 +372,15 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[eb][r] *= alpha;
         }
+        // ---- P = exp2(S - m_ref) and O^T += V^T P^T, one 32-row block at a time so that the
+        // exponentials of block 1 run while the matrix cores accumulate block 0.
+        // k-step j of block kb covers kv rows 32 kb + 16 j + [0, 16); P^T slots 0..7 of lane-half
+        // h are rows 4h+{0..3} and 8+4h+{0..3} of that step, so the two transposing reads fetch
+        // exactly those rows of V for column 32 eb + n.
         float rs0 = 0.f, rs1 = 0.f;
-        uint32_t pk[2][8];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb) {
+            uint32_t pk[8];
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
 #ifdef KVP_EXP_NO_EXP
@@ -288,22 +391,11 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
 #endif
                 rs0 += p0;
                 rs1 += p1;
-                pk[kb][r >> 1] = pack_bf16_hw(p0, p1);
+                pk[r >> 1] = pack_bf16_hw(p0, p1);
             }
-        l_i += rs0 + rs1;  // this lane's half of the row; the halves are added once, at the end
-#ifdef KVP_TIMING
-        asm volatile("" : "+v"(l_i));
-        PHASE(4);
-#endif
-
-        // ---- O^T += V^T P^T.  k-step j of block kb covers kv rows 32 kb + 16 j + [0, 16);
-        // P^T slots 0..7 of lane-half h are rows 4h+{0..3} and 8+4h+{0..3} of that step, so
-        // the two transposing reads fetch exactly those rows of V for column 32 eb + n.
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                uint4 pu = make_uint4(pk[kb][4 * j], pk[kb][4 * j + 1], pk[kb][4 * j + 2], pk[kb][4 * j + 3]);
+                uint4 pu = make_uint4(pk[4 * j], pk[4 * j + 1], pk[4 * j + 2], pk[4 * j + 3]);
                 bf16x8 pf = __builtin_bit_cast(bf16x8, pu);
                 const char *vp = vl + (32 * kb + 16 * j + 4 * h + tr_row) * ROW_BYTES + tr_half;
 #pragma unroll
@@ -312,9 +404,6 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
                     const int coff = 16 * (4 * (eb ^ tr_row) + tr_x);
 #if defined(KVP_EXP_NO_VREAD)
                     short4v lo = {(short)coff, 1, 2, 3}, hi = {4, 5, 6, (short)eb};
-#elif defined(KVP_EXP_PLAIN_READ)
-                    short4v lo = *(const short4v *)(vp + coff);
-                    short4v hi = *(const short4v *)(vp + 8 * ROW_BYTES + coff);
 #else
                     short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(vp + coff));
                     short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(vp + 8 * ROW_BYTES + coff));
@@ -325,6 +414,8 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
                     oacc[eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf, oacc[eb], 0, 0, 0);
                 }
             }
+        }
+        l_i += rs0 + rs1;  // this lane's half of the row; the halves are added once, at the end
 #ifdef KVP_TIMING
         asm volatile("" : "+v"(oacc[0]), "+v"(oacc[1]), "+v"(oacc[2]), "+v"(oacc[3]));
         PHASE(5);
@@ -392,7 +483,6 @@ template <bool PAGED> static int launch_variant(const AttnArgs &a, void *stream)
     return (int)hipGetLastError();
 }
 
-// The query in a.q_rot must already be multiplied by mfma_q_scale(): see the kernel.
 int launch_attention_mfma(const AttnArgs &a, void *stream)
 {
     if (a.d != D || a.bm != BM) return (int)hipErrorInvalidValue;

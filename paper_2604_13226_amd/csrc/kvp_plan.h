@@ -79,7 +79,11 @@ struct AttnItem {
 static_assert(sizeof(AttnItem) == 64, "AttnItem is 64 bytes");
 
 struct AttnArgs {
-    const void *q_rot;  // [tot_q][Hq][d], store dtype, rotated
+    const void *q_rot;  // [tot_q][Hq][d], store dtype, rotated (generic kernel)
+    // the MFMA kernel rotates the query and appends K_new / V_new itself:
+    const void *q, *k_new, *v_new;  // un-rotated inputs of kvp_query_prefill
+    const float2 *cs;               // [max_positions][d/2] (cos, sin)
+    int32_t prerotated;
     CacheView cache;
     const ReqMeta *reqs;
     const AttnGroup *groups;

@@ -760,28 +760,35 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     hipStream_t st = (hipStream_t)hip_stream;
     CacheView view = make_view(s, cache, cc.shift, pf.bt_dev, pf.bt_stride);
 
-    AppendArgs ap;
-    ap.q = q;
-    ap.k_new = k_new;
-    ap.v_new = v_new;
-    ap.q_rot = workspace;
-    ap.cs = s->cs_dev;
-    ap.cache = view;
-    ap.reqs = pf.reqs_dev;
-    ap.row_req = pf.row_req_dev;
-    ap.tot_q = tot_q;
-    ap.layer = layer;
-    ap.n_q_heads = g.n_q_heads;
-    ap.n_kv = g.n_kv_heads;
-    ap.d = g.head_dim;
-    ap.prerotated = (flags & KVP_PREROTATED) ? 1 : 0;
-    // the MFMA kernel takes the query pre-multiplied by log2(e)/sqrt(d); the generic one scales itself
-    ap.q_scale = pf.kind == ATTN_MFMA ? (float)(1.4426950408889634 / sqrt((double)g.head_dim)) : 1.f;
-    int e = launch_append(g.dtype, ap, hip_stream);
-    if (e) return hip_fail(s, (hipError_t)e, "append launch");
+    if (pf.kind != ATTN_MFMA) {  // the MFMA kernel does the query side itself
+        AppendArgs ap;
+        ap.q = q;
+        ap.k_new = k_new;
+        ap.v_new = v_new;
+        ap.q_rot = workspace;
+        ap.cs = s->cs_dev;
+        ap.cache = view;
+        ap.reqs = pf.reqs_dev;
+        ap.row_req = pf.row_req_dev;
+        ap.tot_q = tot_q;
+        ap.layer = layer;
+        ap.n_q_heads = g.n_q_heads;
+        ap.n_kv = g.n_kv_heads;
+        ap.d = g.head_dim;
+        ap.prerotated = (flags & KVP_PREROTATED) ? 1 : 0;
+        ap.q_scale = 1.f;
+        int e = launch_append(g.dtype, ap, hip_stream);
+        if (e) return hip_fail(s, (hipError_t)e, "append launch");
+    }
 
+    int e = 0;
     AttnArgs at;
     at.q_rot = workspace;
+    at.q = q;
+    at.k_new = k_new;
+    at.v_new = v_new;
+    at.cs = s->cs_dev;
+    at.prerotated = (flags & KVP_PREROTATED) ? 1 : 0;
     at.cache = view;
     at.reqs = pf.reqs_dev;
     at.groups = pf.groups_dev;
