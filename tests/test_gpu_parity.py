@@ -244,3 +244,45 @@ def test_full_size_llama_k5_sampled(gpu_device):
     for layer in layers:
         err = float(np.max(np.abs(got["out"][r][layer] - ref["out"][r][layer])))
         assert err <= 2e-2, (layer, err)
+
+
+@pytest.mark.parametrize("mk", [lambda: W.tiny_fp32(), lambda: W.llama_k5(n_layers=1, n_packets=8)])
+def test_decode_steps_after_prefill(gpu_device, mk):
+    """After the query prefill the caller advances ctx_len by n_q; every later token is one
+    more kvp_query_prefill with a single query row (auto-regressive decoding over the composed
+    cache, Sec. 3.1).  Appended rows stay bit-exact, outputs stay within tolerance."""
+    import oracle
+    import paper_2604_13226_amd as kvp
+    w = mk()
+    w.requests[0].packet_ids = w.requests[0].packet_ids[:2]
+    steps = 3
+    rq = w.requests[0]
+    store = build_store(w, kvp, max_positions=w.ctx_len(0) + rq.n_q + steps + 8)
+    cache = kvp.Cache.contiguous(store, 1, w.ctx_len(0) + rq.n_q + steps)
+    kvp.kvp_assemble(store, [(rq.packet_ids, 0)], cache)
+    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, 1, rq.n_q, w.ctx_len(0) + rq.n_q + steps))
+    f = oracle.inv_freq(w.rope_base, w.head_dim)
+    pk = [W.to_numpy(w.packet_kv(p)[0]) for p in rq.packet_ids]
+    pv = [W.to_numpy(w.packet_kv(p)[1]) for p in rq.packet_ids]
+    rows = w.ctx_len(0) + rq.n_q + steps
+    npdt = np.float32 if w.dtype == "f32" else np.uint16
+    ko = np.zeros((w.n_layers, w.n_kv_heads, rows, w.head_dim), npdt)
+    vo = np.zeros_like(ko)
+    ko, vo, ctx = oracle.assemble(w.dtype, pk, pv, f, 0, rows, ko, vo)
+    n_q = rq.n_q
+    for step in range(steps + 1):
+        q, kn, vn = (W.normal_tensor((n_q, h, w.head_dim), w.seed, 40 + i, step, 1.0 if i == 0 else w.kv_scale,
+                                     w.torch_dtype, "cuda")
+                     for i, h in enumerate((w.n_q_heads, w.n_kv_heads, w.n_kv_heads)))
+        out = torch.empty_like(q)
+        assert int(cache.ctx_len[0]) == ctx
+        kvp.kvp_query_prefill(store, cache, 0, q, kn, vn, [0, n_q], ws, out)
+        torch.cuda.synchronize()
+        ref = oracle.query_prefill(w.dtype, W.to_numpy(q), W.to_numpy(kn), W.to_numpy(vn), f, ctx, ko[0], vo[0])
+        err = float(np.max(np.abs(out.float().cpu().numpy().astype(np.float64) - ref)))
+        assert err <= TOL[w.dtype], (step, err)
+        ctx += n_q
+        cache.ctx_len[0] = ctx            # the caller advances the context after the layer(s)
+        k, v = cache.logical(0, 0, ctx)
+        assert np.array_equal(W.to_numpy(k), ko[0][:, :ctx]) and np.array_equal(W.to_numpy(v), vo[0][:, :ctx])
+        n_q = 1
