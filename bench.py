@@ -83,6 +83,9 @@ def main():
     ap.add_argument("--workload", default="llama_8k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=16)
+    ap.add_argument("--path", default="cache", choices=["cache", "packets"],
+                    help="cache: kvp_assemble + kvp_query_prefill (the metric's path); packets: "
+                         "kvp_prefill_packets, attention read in place from the store, no assembly")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (a known-size kernel to scale "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
@@ -119,15 +122,22 @@ def main():
     out = torch.empty_like(qkv[0][0])
     torch.cuda.synchronize()
 
+    k_tail = torch.empty_like(qkv[0][1])
+    reqs0 = [(rq.packet_ids, 0) for rq in w.requests]
+
     def step(ev=None):
         if ev:
             ev[0].record()
-        kvp.kvp_assemble(store, reqs, cache)
+        if args.path == "cache":
+            kvp.kvp_assemble(store, reqs, cache)
         if ev:
             ev[1].record()
         for layer in range(w.n_layers):
             q, kn, vn = qkv[layer]
-            kvp.kvp_query_prefill(store, cache, layer, q, kn, vn, q_off, ws, out)
+            if args.path == "cache":
+                kvp.kvp_query_prefill(store, cache, layer, q, kn, vn, q_off, ws, out)
+            else:
+                kvp.kvp_prefill_packets(store, reqs0, layer, q, kn, vn, q_off, k_tail, ws, out)
         if ev:
             ev[2].record()
 
@@ -159,7 +169,7 @@ def main():
     pre_flops = sum(4.0 * rq.n_q * c * w.n_q_heads * w.head_dim
                     + 2.0 * rq.n_q * rq.n_q * w.n_q_heads * w.head_dim
                     for c, rq in zip(ctx, w.requests))                                 # per layer
-    asm_gbs = asm_bytes / (asm_ms * 1e-3) / 1e9
+    asm_gbs = asm_bytes / (max(asm_ms, 1e-6) * 1e-3) / 1e9
     pre_us_layer = pre_ms * 1e3 / w.n_layers
     pre_gbs = pre_bytes / (pre_us_layer * 1e-6) / 1e9
     pre_tflops = pre_flops / (pre_us_layer * 1e-6) / 1e12
@@ -178,7 +188,7 @@ def main():
         "config": {"workload": "%s: %d layers, Hq %d / Hkv %d, d %d, %d request(s), ctx %s, n_q %s"
                    % (w.name, w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, n_req,
                       ctx[:4], [rq.n_q for rq in w.requests[:4]]),
-                   "layout": "paged" if w.paged else "contiguous"},
+                   "layout": "paged" if w.paged else "contiguous", "path": args.path},
         "roofline": {"bound": "hbm", "kernel": "assemble_vec_kernel (all layers, one launch)",
                      "achieved": asm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": asm_gbs / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),

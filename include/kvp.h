@@ -171,6 +171,24 @@ int kvp_query_prefill(kvp_store_t *store, kvp_cache_t *cache, int32_t layer, con
                       int32_t n_req, uint32_t flags, void *workspace,
                       uint64_t workspace_bytes, void *out, void *hip_stream);
 
+/*
+ * The same attention without materialising a cache (Sec. 3.1: the score of two tokens
+ * depends only on their position difference, so instead of rotating every cached key by
+ * Delta_j (Eq. 1) the query is rotated by (ctx_len + t) - Delta_j for packet j's rows).
+ * K and V are read in place from the store; nothing is gathered or written except
+ *   k_tail : DEVICE [tot_q][n_kv_heads][head_dim], out: K_new rotated to ctx_len[r] + t and
+ *            rounded exactly as kvp_query_prefill would have appended it (V_new needs no
+ *            copy); the caller keeps it if decoding continues.
+ * `out` equals what kvp_assemble + kvp_query_prefill give, within the attention tolerance
+ * (operands are rounded to bf16 at different points).  reqs[r].base_pos must be 0.  bf16
+ * stores with head_dim 128 only.  workspace as for kvp_query_prefill.
+ * Errors: KVP_E_INVAL, KVP_E_NOTFOUND, KVP_E_CAPACITY.
+ */
+int kvp_prefill_packets(kvp_store_t *store, const kvp_request_t *reqs, int32_t n_req, int32_t layer,
+                        const void *q, const void *k_new, const void *v_new, const int32_t *q_offsets,
+                        uint32_t flags, void *k_tail, void *workspace, uint64_t workspace_bytes,
+                        void *out, void *hip_stream);
+
 /* Upper bound of the workspace kvp_query_prefill needs for n_req requests with at most
  * max_tot_q query rows in total and contexts (ctx_len + n_q) of at most max_ctx rows. */
 uint64_t kvp_prefill_workspace_bytes(const kvp_store_t *store, int32_t n_req,

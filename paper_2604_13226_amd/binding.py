@@ -51,6 +51,8 @@ EXPORTS = {
                             ctypes.POINTER(kvp_cache_t), _vp]),
     "kvp_query_prefill": (_i32, [_vp, ctypes.POINTER(kvp_cache_t), _i32, _vp, _vp, _vp, _vp, _i32,
                                  _u32, _vp, _u64, _vp, _vp]),
+    "kvp_prefill_packets": (_i32, [_vp, ctypes.POINTER(kvp_request_t), _i32, _i32, _vp, _vp, _vp, _vp, _u32,
+                                   _vp, _vp, _u64, _vp, _vp]),
     "kvp_prefill_workspace_bytes": (_u64, [_vp, _i32, _i32, _i32]),
     "kvp_last_error": (ctypes.c_char_p, [_vp]),
     "kvp_debug_last_plan": (_i64, [_vp, _i32, _vp, _i64]),
@@ -256,8 +258,7 @@ class Cache:
         return gather(self.k), gather(self.v)
 
 
-def kvp_assemble(store, requests, cache, layer_begin=0, layer_end=None, stream=None):
-    """requests: list of (packet_ids, base_pos).  Fills cache.ctx_len."""
+def _requests(requests):
     n_req = len(requests)
     arr = (kvp_request_t * max(n_req, 1))()
     keep = []
@@ -267,6 +268,13 @@ def kvp_assemble(store, requests, cache, layer_begin=0, layer_end=None, stream=N
         arr[i].packet_ids = a.ctypes.data if len(a) else None
         arr[i].k = len(a)
         arr[i].base_pos = int(base_pos)
+    return arr, keep
+
+
+def kvp_assemble(store, requests, cache, layer_begin=0, layer_end=None, stream=None):
+    """requests: list of (packet_ids, base_pos).  Fills cache.ctx_len."""
+    n_req = len(requests)
+    arr, keep = _requests(requests)
     if layer_end is None:
         layer_end = store.cfg.n_layers
     rc = load().kvp_assemble(store.handle, arr, n_req, int(layer_begin), int(layer_end),
@@ -298,6 +306,26 @@ def kvp_query_prefill(store, cache, layer, q, k_new, v_new, q_offsets, workspace
                                   k_new.data_ptr(), v_new.data_ptr(), qo.ctypes.data, n_req, int(flags),
                                   workspace.data_ptr(), int(workspace.numel()), out.data_ptr(),
                                   _stream(stream))
+    _check(store.handle, rc)
+
+
+def kvp_prefill_packets(store, requests, layer, q, k_new, v_new, q_offsets, k_tail, workspace, out,
+                        flags=0, stream=None):
+    """Attention of the query rows over the requests' packets read in place from the store.
+    requests: list of (packet_ids, 0); k_tail [tot_q][Hkv][d] receives the rotated K_new."""
+    qo = np.ascontiguousarray(q_offsets, np.int32)
+    n_req = len(qo) - 1
+    arr, keep = _requests(requests)
+    if store.dry:
+        rc = load().kvp_prefill_packets(store.handle, arr, n_req, int(layer), None, None, None, qo.ctypes.data,
+                                        int(flags), None, None, 1 << 60, None, None)
+        return _check(store.handle, rc)
+    for t in (q, k_new, v_new, out, k_tail):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == store.torch_dtype
+    assert k_tail.shape == k_new.shape and out.shape == q.shape
+    rc = load().kvp_prefill_packets(store.handle, arr, n_req, int(layer), q.data_ptr(), k_new.data_ptr(),
+                                    v_new.data_ptr(), qo.ctypes.data, int(flags), k_tail.data_ptr(),
+                                    workspace.data_ptr(), int(workspace.numel()), out.data_ptr(), _stream(stream))
     _check(store.handle, rc)
 
 

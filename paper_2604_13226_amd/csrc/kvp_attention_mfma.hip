@@ -62,19 +62,27 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 }
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
-// HBM -> LDS without staging registers: each lane names its own 16 global bytes; the
-// wavefront's 64 x 16 B land contiguously at the wave-uniform LDS byte address lds_addr.
-// Written as inline assembly so that the compiler's wait-count insertion does not treat
-// every later LDS read as dependent on every outstanding load: the waits are explicit
-// (wait_vmcnt + wg_barrier) in the tile loop.
-__device__ __forceinline__ void load_to_lds_16(const void *gptr, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
-}
-// same, global address = wave-uniform base + per-lane 32-bit byte offset
+// HBM -> LDS without staging registers: each lane names its own 16 global bytes (a
+// wave-uniform base plus a per-lane 32-bit byte offset); the wavefront's 64 x 16 B land
+// contiguously at the wave-uniform LDS byte address lds_addr.  Written as inline assembly so
+// that the compiler's wait-count insertion does not treat every later LDS read as dependent
+// on every outstanding load: the waits are explicit (wait_vmcnt + wg_barrier) in the loop.
 __device__ __forceinline__ void load_to_lds_16(const void *sbase, uint32_t voff, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+// a pointer the program knows to be wave-uniform, made so for the compiler too
+__device__ __forceinline__ const char *uniform_ptr(const void *p)
+{
+    const uint64_t v = (uint64_t)(uintptr_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const char *)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
+// same with a full per-lane address
+__device__ __forceinline__ void load_to_lds_16(const void *gptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
 
 // If the running reference maximum lags the true row maximum by at most this many
@@ -85,15 +93,56 @@ constexpr float RESCALE_SLACK = 8.f;
 
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
-// The query is held rotated and multiplied by log2(e)/sqrt(d), so S = K Q^T is in log2 units.  The S accumulators start at -m_ref: after the MFMAs they hold s - m_ref and
-// the probabilities are exp2 of them with no further arithmetic.
-template <int STAGES, bool PAGED>
+// One 16-byte chunk pair of a head vector rotated by the (cos, sin) pairs in cs4 (Eq. 1):
+// element i of the low chunk pairs with element i of the high chunk.
+template <bool EXACT>
+__device__ __forceinline__ void rotate_chunk_pair(const uint4 &ulo, const uint4 &uhi, const float4 (&cs4)[4], float sign,
+                                                  float scale, uint4 &olo, uint4 &ohi)
+{
+#pragma clang fp contract(off)  // EXACT: separately rounded products and sums, as the gather kernel
+    const uint32_t wl[4] = {ulo.x, ulo.y, ulo.z, ulo.w}, wh[4] = {uhi.x, uhi.y, uhi.z, uhi.w};
+    uint32_t ol[4], oh[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float lo2[2], hi2[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const float x = __uint_as_float(u ? (wl[j] & 0xFFFF0000u) : (wl[j] << 16));
+            const float y = __uint_as_float(u ? (wh[j] & 0xFFFF0000u) : (wh[j] << 16));
+            const float c = u ? cs4[j].z : cs4[j].x, sn = (u ? cs4[j].w : cs4[j].y) * sign;
+            const float xc = x * c, ys = y * sn, yc = y * c, xs = x * sn;
+            lo2[u] = xc - ys;
+            hi2[u] = yc + xs;
+            if (!EXACT) { lo2[u] *= scale; hi2[u] *= scale; }
+        }
+        if (EXACT) {
+            ol[j] = (uint32_t)f32_to_bf16(lo2[0]) | ((uint32_t)f32_to_bf16(lo2[1]) << 16);
+            oh[j] = (uint32_t)f32_to_bf16(hi2[0]) | ((uint32_t)f32_to_bf16(hi2[1]) << 16);
+        } else {
+            ol[j] = pack_bf16_hw(lo2[0], lo2[1]);
+            oh[j] = pack_bf16_hw(hi2[0], hi2[1]);
+        }
+    }
+    olo = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+    ohi = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+}
+
+enum { SRC_CONTIG = 0, SRC_PAGED = 1, SRC_PACKETS = 2 };
+
+// The query is held rotated and multiplied by log2(e)/sqrt(d), so S = K Q^T is in log2
+// units.  The S accumulators start at -m_ref: after the MFMAs they hold s - m_ref and the
+// probabilities are exp2 of them with no further arithmetic.
+//
+// SRC_CONTIG / SRC_PAGED: an item's [kv_begin, kv_end) are cache rows.
+// SRC_PACKETS: no cache exists; [kv_begin, kv_end) index a.tiles, each tile up to 64 rows of
+// one stored packet (read in place from the arena) or of the query rows (rotated K_new in
+// a.k_tail, V_new as given).  The keys of a stored packet stay at their local positions;
+// instead the query is rotated by (ctx_len + t) - Delta_j for that packet's tiles, which
+// gives the same scores (Eq. 1: scores depend on the position difference only).
+template <int STAGES, int SRC>
 __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-#ifdef KVP_TIMING
-    if (threadIdx.x == 0) a.dbg[blockIdx.x * 8 + 0] = wall_clock64();
-#endif
     const AttnItem it = a.items[blockIdx.x];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -103,24 +152,28 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     const bf16_t *kc = (const bf16_t *)a.cache.k;
     const bf16_t *vc = (const bf16_t *)a.cache.v;
     const int kv_last = it.kv_end - 1;
-    const int n_tiles = (it.kv_end - it.kv_begin + BN - 1) / BN;
+    const int n_tiles = SRC == SRC_PACKETS ? it.kv_end - it.kv_begin : (it.kv_end - it.kv_begin + BN - 1) / BN;
 
     // paged layout: this item's block ids go to LDS once, so the tile loop issues no
     // ordinary global loads (its in-flight count is what the waits below rely on)
     int *blk_ids = (int *)(lds + STAGES * STAGE_BYTES);
-    const int blk0 = PAGED ? (it.kv_begin >> a.cache.block_shift) : 0;
-    if (PAGED) {
+    const int blk0 = SRC == SRC_PAGED ? (it.kv_begin >> a.cache.block_shift) : 0;
+    if (SRC == SRC_PAGED) {
         const int nb = (kv_last >> a.cache.block_shift) - blk0 + 1;
         for (int i = tid; i < nb; i += 256)
             blk_ids[i] = a.cache.block_table[(int64_t)it.req * a.cache.max_blocks + blk0 + i];
         __syncthreads();
     }
     // contiguous layout: wave-uniform byte address of the item's first K / V row
-    const int64_t contig_off = (int64_t)it.req * a.cache.req_stride + (int64_t)a.layer * a.cache.layer_stride +
-                               ((int64_t)it.kv_head * a.cache.t_cap + it.kv_begin) * D;
+    const int64_t contig_off = SRC == SRC_CONTIG
+                                   ? (int64_t)it.req * a.cache.req_stride + (int64_t)a.layer * a.cache.layer_stride +
+                                         ((int64_t)it.kv_head * a.cache.t_cap + it.kv_begin) * D
+                                   : 0;
     const char *k_item = (const char *)(kc + contig_off);
     const char *v_item = (const char *)(vc + contig_off);
     const int64_t paged_base = (int64_t)a.layer * a.cache.layer_stride;
+    // packets: rows of the query's own K (rotated, in a.k_tail) and V (a.v_new) for this head
+    const int64_t tail_off = ((int64_t)it.q_off * a.n_kv + it.kv_head) * D;
 
     // direct HBM -> LDS load of tile tj: wave w, instruction i fills tile rows
     // 16 i + 4 w .. +3 (1 KiB contiguous in LDS); lane l owns slot (row + l / 16, chunk l % 16)
@@ -128,9 +181,35 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     const int slot_row = lane >> 4, slot_chunk = lane & 15;
     const int k_chunk = slot_chunk ^ ((4 * wave + slot_row) & 15);  // logical chunk fetched
     const int v_chunk = slot_chunk ^ (4 * slot_row);
-    const int last_tile_rows = it.kv_end - it.kv_begin - (n_tiles - 1) * BN;  // 1..64
+    const int last_tile_rows = it.kv_end - it.kv_begin - (n_tiles - 1) * BN;  // 1..64 (cache modes)
     auto issue = [&](int tj) {
         const uint32_t st = lds_base + (uint32_t)((tj % STAGES) * STAGE_BYTES);
+        if (SRC == SRC_PACKETS) {
+            const AttnTile td = a.tiles[it.kv_begin + tj];
+            const char *kt, *vt;
+            uint32_t row_bytes;
+            if (td.kind == 0) {
+                const int64_t slice = ((int64_t)a.layer * a.n_kv + it.kv_head) * td.stride + td.row0;
+                kt = (const char *)((const bf16_t *)a.arena + td.src_base + slice * D);
+                vt = kt + (int64_t)a.n_layers_total * a.n_kv * td.stride * ROW_BYTES;
+                row_bytes = ROW_BYTES;
+            } else {
+                kt = (const char *)((const bf16_t *)a.k_tail + tail_off + (int64_t)td.row0 * a.n_kv * D);
+                vt = (const char *)((const bf16_t *)a.v_new + tail_off + (int64_t)td.row0 * a.n_kv * D);
+                row_bytes = (uint32_t)(a.n_kv * ROW_BYTES);
+            }
+            kt = uniform_ptr(kt);
+            vt = uniform_ptr(vt);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int r = 16 * i + 4 * wave + slot_row;
+                r = r < td.n_rows - 1 ? r : td.n_rows - 1;  // rows past the tile repeat its last row (masked)
+                const uint32_t dst = st + (uint32_t)((16 * i + 4 * wave) * ROW_BYTES);
+                load_to_lds_16(kt, (uint32_t)r * row_bytes + 16 * k_chunk, dst);
+                load_to_lds_16(vt, (uint32_t)r * row_bytes + 16 * v_chunk, dst + TILE_BYTES);
+            }
+            return;
+        }
         // rows past the range (last tile only) repeat the last row; they are masked later
         const int max_r = tj == n_tiles - 1 ? last_tile_rows - 1 : BN - 1;
 #pragma unroll
@@ -138,7 +217,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
             int r = 16 * i + 4 * wave + slot_row;
             r = r < max_r ? r : max_r;
             const uint32_t dst = st + (uint32_t)((16 * i + 4 * wave) * ROW_BYTES);
-            if (!PAGED) {
+            if (SRC == SRC_CONTIG) {
                 const char *kt = k_item + (int64_t)tj * TILE_BYTES;
                 const char *vt = v_item + (int64_t)tj * TILE_BYTES;
                 load_to_lds_16(kt, (uint32_t)(r * ROW_BYTES + 16 * k_chunk), dst);
@@ -153,24 +232,35 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
             }
         }
     };
-    // a first tile that lies wholly inside the packet prefix can start its trip right away
-    const bool early0 = n_tiles > 0 && it.kv_begin + BN <= it.ctx_len;
+    // a first tile that cannot contain query rows can start its trip right away
+    const bool early0 = n_tiles > 0 && (SRC == SRC_PACKETS ? a.tiles[it.kv_begin].kind == 0 : it.kv_begin + BN <= it.ctx_len);
     if (early0) issue(0);
 
     // ---- query rows inside this item's range: rotate K_new to its row's position and
     // append K_new / V_new before any tile load can touch those rows
     {
-#pragma clang fp contract(off)  // same separately-rounded arithmetic as the gather kernel
-        const int tail_lo = it.kv_begin > it.ctx_len ? it.kv_begin : it.ctx_len;
-        const int n_tail = it.kv_end - tail_lo;  // > 0 only for items that reach the query rows
+        int tail_lo, n_tail;  // query rows [tail_lo, tail_lo + n_tail) relative to ctx_len
+        if (SRC == SRC_PACKETS) {
+            // an item that reaches the query tiles writes all of this head's rotated K_new rows
+            const bool has_tail = n_tiles > 0 && a.tiles[it.kv_end - 1].kind != 0;
+            tail_lo = 0;
+            n_tail = has_tail ? it.n_q : 0;
+        } else {
+            tail_lo = (it.kv_begin > it.ctx_len ? it.kv_begin : it.ctx_len) - it.ctx_len;
+            n_tail = it.kv_end - it.ctx_len - tail_lo;  // > 0 only for items that reach the query rows
+        }
         if (n_tail > 0) {
-            bf16_t *kcw = (bf16_t *)a.cache.k;
+            bf16_t *kcw = SRC == SRC_PACKETS ? (bf16_t *)a.k_tail : (bf16_t *)a.cache.k;
             bf16_t *vcw = (bf16_t *)a.cache.v;
-            for (int idx = tid; idx < n_tail * 24; idx += 256) {
-                const int row = tail_lo + idx / 24, cidx = idx % 24;  // 8 K chunk pairs + 16 V chunks
-                const int64_t src = ((int64_t)(it.q_off + row - it.ctx_len) * a.n_kv + it.kv_head) * D;
+            const int n_chunks = SRC == SRC_PACKETS ? 8 : 24;  // 8 K chunk pairs (+ 16 V chunks)
+            for (int idx = tid; idx < n_tail * n_chunks; idx += 256) {
+                const int qr = tail_lo + idx / n_chunks, cidx = idx % n_chunks;
+                const int row = it.ctx_len + qr;  // position of the row
+                const int64_t src = ((int64_t)(it.q_off + qr) * a.n_kv + it.kv_head) * D;
                 int64_t dst;
-                if (!PAGED) {
+                if (SRC == SRC_PACKETS) {
+                    dst = src;
+                } else if (SRC == SRC_CONTIG) {
                     dst = contig_off + (int64_t)(row - it.kv_begin) * D;
                 } else {
                     const int b = blk_ids[(row >> a.cache.block_shift) - blk0];
@@ -184,29 +274,14 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
                     const int e = 8 * cidx;
                     const uint4 ulo = *(const uint4 *)((const bf16_t *)a.k_new + src + e);
                     const uint4 uhi = *(const uint4 *)((const bf16_t *)a.k_new + src + 64 + e);
-                    const uint32_t wl[4] = {ulo.x, ulo.y, ulo.z, ulo.w}, wh[4] = {uhi.x, uhi.y, uhi.z, uhi.w};
-                    uint32_t ol[4], oh[4];
                     const float4 *csr = (const float4 *)(a.cs + (int64_t)row * 64 + e);
                     float4 cs4[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) cs4[j] = a.prerotated ? make_float4(1.f, 0.f, 1.f, 0.f) : csr[j];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        float lo2[2], hi2[2];
-#pragma unroll
-                        for (int u = 0; u < 2; ++u) {
-                            const float x = __uint_as_float(u ? (wl[j] & 0xFFFF0000u) : (wl[j] << 16));
-                            const float y = __uint_as_float(u ? (wh[j] & 0xFFFF0000u) : (wh[j] << 16));
-                            const float c = u ? cs4[j].z : cs4[j].x, sn = u ? cs4[j].w : cs4[j].y;
-                            const float xc = x * c, ys = y * sn, yc = y * c, xs = x * sn;
-                            lo2[u] = xc - ys;
-                            hi2[u] = yc + xs;
-                        }
-                        ol[j] = (uint32_t)f32_to_bf16(lo2[0]) | ((uint32_t)f32_to_bf16(lo2[1]) << 16);
-                        oh[j] = (uint32_t)f32_to_bf16(hi2[0]) | ((uint32_t)f32_to_bf16(hi2[1]) << 16);
-                    }
-                    *(uint4 *)(kcw + dst + e) = make_uint4(ol[0], ol[1], ol[2], ol[3]);
-                    *(uint4 *)(kcw + dst + 64 + e) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+                    uint4 olo, ohi;
+                    rotate_chunk_pair<true>(ulo, uhi, cs4, 1.f, 1.f, olo, ohi);
+                    *(uint4 *)(kcw + dst + e) = olo;
+                    *(uint4 *)(kcw + dst + 64 + e) = ohi;
                 }
             }
             wait_vmcnt<0>();   // this wave's stores have reached the L2
@@ -223,55 +298,40 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     const bool row_ok = rr < it.n_rows;
     const int m = it.m0 + (row_ok ? rr : 0);
     const int t = m / g, hq = it.kv_head * g + m % g;
-    const int limit = row_ok ? it.ctx_len + t + 1 : 0;  // kv rows [0, limit) are visible
+    const int limit = row_ok ? it.ctx_len + t + 1 : 0;  // cache modes: kv rows [0, limit) are visible
     // smallest limit among the wave's rows (rows are ordered by query token)
     const int wave_limit = it.ctx_len + (it.m0 + 32 * wave) / g + 1;
 
-    // B operand of S^T = K Q^T: lane holds Q[m][16 ks + 8 h .. +7] for ks = 0..7, rotated to
-    // position ctx_len + t and multiplied by log2(e)/sqrt(d).  Element 16 ks + 8 h + j (ks < 4)
-    // pairs with the same slot of ks + 4.
+    // B operand of S^T = K Q^T: lane holds Q[m][16 ks + 8 h .. +7] for ks = 0..7, rotated by
+    // `rel` positions and multiplied by log2(e)/sqrt(d).  Element 16 ks + 8 h + j (ks < 4)
+    // pairs with the same slot of ks + 4, so the rotation stays inside the lane.
     bf16x8 qf[8];
-    {
-        const bf16_t *qp = (const bf16_t *)a.q + ((int64_t)(it.q_off + t) * a.n_q_heads + hq) * D + 8 * h;
+    const bf16_t *qp = (const bf16_t *)a.q + ((int64_t)(it.q_off + t) * a.n_q_heads + hq) * D + 8 * h;
+    const int q_pos = a.prerotated ? 0 : it.ctx_len + t;  // rotation the query still needs
+    auto load_q = [&](int delta) {
         uint4 qraw[8];
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qraw[ks] = row_ok ? *(const uint4 *)(qp + 16 * ks) : make_uint4(0, 0, 0, 0);
-        const float4 *csr = (const float4 *)(a.cs + (int64_t)(it.ctx_len + t) * 64 + 8 * h);
-        const bool rot = !a.prerotated && row_ok;
-        float4 cs4[4][4];  // (cos, sin) pairs of elements 16 ks + 8 h + 2 j, + 1
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) cs4[ks][j] = rot ? csr[8 * ks + j] : make_float4(1.f, 0.f, 1.f, 0.f);
-        const float qs = a.scale_log2e;
+        const int rel = row_ok ? q_pos - delta : 0;
+        const float sign = rel < 0 ? -1.f : 1.f;
+        const float4 *csr = (const float4 *)(a.cs + (int64_t)(rel < 0 ? -rel : rel) * 64 + 8 * h);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            const uint32_t wl[4] = {qraw[ks].x, qraw[ks].y, qraw[ks].z, qraw[ks].w};
-            const uint32_t wh[4] = {qraw[ks + 4].x, qraw[ks + 4].y, qraw[ks + 4].z, qraw[ks + 4].w};
-            uint32_t ol[4], oh[4];
+            float4 cs4[4];  // (cos, sin) pairs of elements 16 ks + 8 h + 2 j, + 1
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                float lo2[2], hi2[2];
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const float x = __uint_as_float(u ? (wl[j] & 0xFFFF0000u) : (wl[j] << 16));
-                    const float y = __uint_as_float(u ? (wh[j] & 0xFFFF0000u) : (wh[j] << 16));
-                    const float c = u ? cs4[ks][j].z : cs4[ks][j].x, sn = u ? cs4[ks][j].w : cs4[ks][j].y;
-                    lo2[u] = (x * c - y * sn) * qs;
-                    hi2[u] = (y * c + x * sn) * qs;
-                }
-                ol[j] = pack_bf16_hw(lo2[0], lo2[1]);
-                oh[j] = pack_bf16_hw(hi2[0], hi2[1]);
-            }
-            qf[ks] = __builtin_bit_cast(bf16x8, make_uint4(ol[0], ol[1], ol[2], ol[3]));
-            qf[ks + 4] = __builtin_bit_cast(bf16x8, make_uint4(oh[0], oh[1], oh[2], oh[3]));
+            for (int j = 0; j < 4; ++j) cs4[j] = csr[8 * ks + j];
+            uint4 olo, ohi;
+            rotate_chunk_pair<false>(qraw[ks], qraw[ks + 4], cs4, sign, a.scale_log2e, olo, ohi);
+            qf[ks] = __builtin_bit_cast(bf16x8, olo);
+            qf[ks + 4] = __builtin_bit_cast(bf16x8, ohi);
         }
-    }
-    // Pin Q in registers here: the compiler then places its wait for the Q loads before the
-    // tile loop instead of at their first use inside it (where it would also drain every
-    // tile load in flight).
+        // Pin Q in registers here: the compiler then places its wait for these loads right
+        // here instead of at their first use inside the tile loop's matrix code.
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));
+        for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));
+    };
+    int cur_delta = SRC == SRC_PACKETS && n_tiles > 0 ? a.tiles[it.kv_begin].pos : 0;
+    load_q(cur_delta);
 
     floatx16 oacc[4];
 #pragma unroll
@@ -280,20 +340,10 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
         for (int r = 0; r < 16; ++r) oacc[eb][r] = 0.f;
     float m_ref = -INFINITY, l_i = 0.f;  // reference max (log2 units) and running sum
 
-#ifdef KVP_TIMING
-    if (threadIdx.x == 0) a.dbg[blockIdx.x * 8 + 1] = wall_clock64();
-#endif
     const int tr_row = (lane & 15) >> 2;
     const int tr_x = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);  // 16-byte chunk inside the 64-byte column group
     const int tr_half = 8 * (lane & 1);
 
-#ifdef KVP_TIMING
-    long long ph[6] = {0, 0, 0, 0, 0, 0};
-    long long tc = clock64();
-#define PHASE(i) do { long long t_ = clock64(); ph[i] += t_ - tc; tc = t_; } while (0)
-#else
-#define PHASE(i) do {} while (0)
-#endif
     for (int ti = 0; ti < n_tiles; ++ti) {
         // tile ti has landed once at most the loads of the tiles issued after it remain
         const int ahead = n_tiles - 1 - ti < STAGES - 2 ? n_tiles - 1 - ti : STAGES - 2;
@@ -301,13 +351,19 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
         else if (ahead == 2) wait_vmcnt<16>();
         else if (ahead == 1) wait_vmcnt<8>();
         else wait_vmcnt<0>();
-        PHASE(0);
         wg_barrier();  // every wave's part of tile ti is in LDS; everyone is done with tile ti-1
-        PHASE(1);
 
         const int kv0 = it.kv_begin + ti * BN;
         const char *kl = lds + (ti % STAGES) * STAGE_BYTES;
         const char *vl = kl + TILE_BYTES;
+        AttnTile td;
+        if (SRC == SRC_PACKETS) {
+            td = a.tiles[it.kv_begin + ti];
+            if (td.pos != cur_delta) {  // the tile belongs to another packet: re-rotate the query
+                cur_delta = td.pos;
+                load_q(cur_delta);
+            }
+        }
 
         // ---- S^T - m_ref = K Q^T - m_ref : 2 blocks of 32 kv rows x 32 query rows
         const float init = m_ref == -INFINITY ? 0.f : -m_ref;
@@ -319,23 +375,27 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             const int coff = 16 * ((2 * ks + h) ^ (n & 15));
-#ifdef KVP_EXP_NO_KREAD
-            bf16x8 a0 = qf[ks], a1 = qf[7 - ks];
-            (void)coff;
-#else
             bf16x8 a0 = __builtin_bit_cast(bf16x8, *(const uint4 *)(kl + n * ROW_BYTES + coff));
             bf16x8 a1 = __builtin_bit_cast(bf16x8, *(const uint4 *)(kl + (32 + n) * ROW_BYTES + coff));
-#endif
             sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], sacc[0], 0, 0, 0);
             sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], sacc[1], 0, 0, 0);
         }
         // The next tile's loads are issued while the matrix cores work on S: they refill the
         // stage tile ti-1 used, which every wave left before the barrier above.
         if (ti + STAGES - 1 < n_tiles) issue(ti + STAGES - 1);
-        PHASE(2);
 
-        // ---- online softmax; accumulator r of block kb is kv row kv0 + 32 kb + 8 (r/4) + 4 h + r%4
-        if (kv0 + BN > wave_limit || kv0 + BN > it.kv_end) {  // wave-uniform: tail tiles only
+        // ---- online softmax; accumulator r of block kb is tile row 32 kb + 8 (r/4) + 4 h + r%4
+        if (SRC == SRC_PACKETS) {
+            if (td.kind != 0 || td.n_rows < BN) {  // wave-uniform: query tiles and ragged packet ends
+                const int vis = td.kind != 0 ? (row_ok ? t - td.row0 + 1 : 0) : BN;  // causal among query rows
+                const int lim = vis < td.n_rows ? vis : td.n_rows;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (32 * kb + 8 * (r >> 2) + 4 * h + (r & 3) >= lim) sacc[kb][r] = -INFINITY;
+            }
+        } else if (kv0 + BN > wave_limit || kv0 + BN > it.kv_end) {  // wave-uniform: tail tiles only
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -350,10 +410,6 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
         for (int r = 2; r < 15; ++r) mx = max3(mx, sacc[1][r], sacc[0][r + 1]);
         mx = fmaxf(mx, sacc[1][15]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // row max relative to m_ref
-#ifdef KVP_TIMING
-        asm volatile("" : "+v"(mx));
-        PHASE(3);
-#endif
         // The reference moves when a row sees its first visible entry (it becomes that
         // tile's maximum) and afterwards only when the maximum outgrows the slack.
         const bool first = m_ref == -INFINITY;
@@ -372,23 +428,20 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[eb][r] *= alpha;
         }
+
         // ---- P = exp2(S - m_ref) and O^T += V^T P^T, one 32-row block at a time so that the
         // exponentials of block 1 run while the matrix cores accumulate block 0.
-        // k-step j of block kb covers kv rows 32 kb + 16 j + [0, 16); P^T slots 0..7 of lane-half
-        // h are rows 4h+{0..3} and 8+4h+{0..3} of that step, so the two transposing reads fetch
-        // exactly those rows of V for column 32 eb + n.
+        // k-step j of block kb covers tile rows 32 kb + 16 j + [0, 16); P^T slots 0..7 of
+        // lane-half h are rows 4h+{0..3} and 8+4h+{0..3} of that step, so the two transposing
+        // reads fetch exactly those rows of V for column 32 eb + n.
         float rs0 = 0.f, rs1 = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             uint32_t pk[8];
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
-#ifdef KVP_EXP_NO_EXP
-                float p0 = sacc[kb][r] * 0.001f, p1 = sacc[kb][r + 1] * 0.001f;
-#else
                 float p0 = __builtin_amdgcn_exp2f(sacc[kb][r]);
                 float p1 = __builtin_amdgcn_exp2f(sacc[kb][r + 1]);
-#endif
                 rs0 += p0;
                 rs1 += p1;
                 pk[r >> 1] = pack_bf16_hw(p0, p1);
@@ -402,12 +455,8 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
                 for (int eb = 0; eb < 4; ++eb) {
                     typedef __attribute__((address_space(3))) short4v *lds_s4;
                     const int coff = 16 * (4 * (eb ^ tr_row) + tr_x);
-#if defined(KVP_EXP_NO_VREAD)
-                    short4v lo = {(short)coff, 1, 2, 3}, hi = {4, 5, 6, (short)eb};
-#else
                     short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(vp + coff));
                     short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(vp + 8 * ROW_BYTES + coff));
-#endif
                     union { short4v s[2]; bf16x8 v; } vf;
                     vf.s[0] = lo;
                     vf.s[1] = hi;
@@ -416,22 +465,9 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
             }
         }
         l_i += rs0 + rs1;  // this lane's half of the row; the halves are added once, at the end
-#ifdef KVP_TIMING
-        asm volatile("" : "+v"(oacc[0]), "+v"(oacc[1]), "+v"(oacc[2]), "+v"(oacc[3]));
-        PHASE(5);
-#endif
     }
     l_i += __shfl_xor(l_i, 32, 64);
 
-#ifdef KVP_TIMING
-    if (threadIdx.x == 0) {
-        a.dbg[blockIdx.x * 8 + 4] = ph[0] + ph[1];
-        a.dbg[blockIdx.x * 8 + 5] = ph[2];
-        a.dbg[blockIdx.x * 8 + 6] = ph[3];
-        a.dbg[blockIdx.x * 8 + 7] = ph[4] | (ph[5] << 32);
-    }
-    if (threadIdx.x == 0) a.dbg[blockIdx.x * 8 + 2] = wall_clock64();
-#endif
     // ---- epilogue: lane holds O[m][32 eb + 8 (r/4) + 4 h + r%4]
     if (row_ok) {
         if (it.part_slot < 0) {
@@ -461,24 +497,21 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
             }
         }
     }
-#ifdef KVP_TIMING
-    if (threadIdx.x == 0) a.dbg[blockIdx.x * 8 + 3] = wall_clock64();
-#endif
 }
 
 constexpr int ATTN_STAGES = 2;  // 64 KiB of tiles + block ids: two workgroups share a CU
 
-template <bool PAGED> static int launch_variant(const AttnArgs &a, void *stream)
+template <int SRC> static int launch_variant(const AttnArgs &a, void *stream)
 {
-    constexpr int lds_bytes = ATTN_STAGES * STAGE_BYTES + (PAGED ? MAX_BLOCK_IDS * 4 : 0);
+    constexpr int lds_bytes = ATTN_STAGES * STAGE_BYTES + (SRC == SRC_PAGED ? MAX_BLOCK_IDS * 4 : 0);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<ATTN_STAGES, PAGED>,
+        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<ATTN_STAGES, SRC>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((attention_mfma_kernel<ATTN_STAGES, PAGED>), dim3(a.n_items), dim3(256), lds_bytes,
+    hipLaunchKernelGGL((attention_mfma_kernel<ATTN_STAGES, SRC>), dim3(a.n_items), dim3(256), lds_bytes,
                        (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
@@ -486,7 +519,8 @@ template <bool PAGED> static int launch_variant(const AttnArgs &a, void *stream)
 int launch_attention_mfma(const AttnArgs &a, void *stream)
 {
     if (a.d != D || a.bm != BM) return (int)hipErrorInvalidValue;
-    return a.cache.layout != 0 ? launch_variant<true>(a, stream) : launch_variant<false>(a, stream);
+    if (a.tiles) return launch_variant<SRC_PACKETS>(a, stream);
+    return a.cache.layout != 0 ? launch_variant<SRC_PAGED>(a, stream) : launch_variant<SRC_CONTIG>(a, stream);
 }
 
 }  // namespace kvp

@@ -74,9 +74,23 @@ struct AttnItem {
     int32_t req, kv_head, m0, n_rows;        // copy of the group
     int32_t ctx_len, q_off;                  // copy of the request
     int32_t part_slot;                       // partial slot to write, or -1: write `out` directly
-    int32_t pad[5];
+    int32_t n_q;                             // query rows of the request
+    int32_t pad[4];
 };
 static_assert(sizeof(AttnItem) == 64, "AttnItem is 64 bytes");
+
+// Attention straight from the packet store: one tile = up to 64 rows of one stored packet
+// (kind 0) or of the request's own query rows (kind 1).
+struct AttnTile {
+    int64_t src_base;  // kind 0: element offset of the packet's K blob in the arena
+    int32_t stride;    // kind 0: rows between (layer, head) slices of the blob
+    int32_t row0;      // first row: inside the packet (kind 0) / among the query rows (kind 1)
+    int32_t n_rows;    // 1..64
+    int32_t pos;       // Delta_j of the packet; 0 for query rows
+    int32_t kind;
+    int32_t pad;
+};
+static_assert(sizeof(AttnTile) == 32, "AttnTile is 32 bytes");
 
 struct AttnArgs {
     const void *q_rot;  // [tot_q][Hq][d], store dtype, rotated (generic kernel)
@@ -84,6 +98,11 @@ struct AttnArgs {
     const void *q, *k_new, *v_new;  // un-rotated inputs of kvp_query_prefill
     const float2 *cs;               // [max_positions][d/2] (cos, sin)
     int32_t prerotated;
+    // attention from the store without a cache (nullptr otherwise):
+    const AttnTile *tiles;
+    const void *arena;
+    void *k_tail;  // [tot_q][n_kv][d]: rotated K_new, written by the kernel
+    int32_t n_layers_total;
     CacheView cache;
     const ReqMeta *reqs;
     const AttnGroup *groups;

@@ -121,10 +121,11 @@ struct kvp_store {
         const int32_t *row_req_dev = nullptr, *bt_dev = nullptr;
         const AttnGroup *groups_dev = nullptr;
         const AttnItem *items_dev = nullptr;
+        const AttnTile *tiles_dev = nullptr;
         int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0;
         bool any_split = false;
         uint64_t need = 0;
-    } pf;
+    } pf, pk;  // pf: kvp_query_prefill, pk: kvp_prefill_packets
     std::vector<int32_t> sig_scratch;
     std::string err;
     std::vector<int64_t> dbg_asm, dbg_attn;
@@ -609,6 +610,7 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
                     it.ctx_len = rq.ctx_len;
                     it.q_off = rq.q_off;
                     it.part_slot = gp.n_splits > 1 ? gp.part0 + sp : -1;
+                    it.n_q = rq.n_q;
                     p.items.push_back(it);
                 }
                 p.groups.push_back(gp);
@@ -702,6 +704,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         int hrc = s->ring_prefill.acquire(bytes, &slot);
         if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
         pf.valid = false;  // the slot may be the cached one; it is rewritten below either way
+        if (s->pk.slot == slot) s->pk.valid = false;  // the two caches share one ring
         PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
         ReqMeta *rh = w.put<ReqMeta>(p.reqs.size(), &pf.reqs_dev);
         if (!p.reqs.empty()) memcpy(rh, p.reqs.data(), p.reqs.size() * sizeof(ReqMeta));
@@ -789,6 +792,10 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     at.v_new = v_new;
     at.cs = s->cs_dev;
     at.prerotated = (flags & KVP_PREROTATED) ? 1 : 0;
+    at.tiles = nullptr;
+    at.arena = nullptr;
+    at.k_tail = nullptr;
+    at.n_layers_total = g.n_layers;
     at.cache = view;
     at.reqs = pf.reqs_dev;
     at.groups = pf.groups_dev;
@@ -812,6 +819,212 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     }
     HIP_TRY(s, hipEventRecord(pf.slot->ev, st));
     pf.slot->pending = true;
+    return KVP_OK;
+}
+
+// -------------------------------------------------------------------------------------
+// Attention over the retrieved packets in place (no cache): the plan is a list of tiles of
+// at most 64 rows, each inside one stored packet or inside the query rows.
+int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32_t layer, const void *q,
+                        const void *k_new, const void *v_new, const int32_t *q_offsets, uint32_t flags, void *k_tail,
+                        void *workspace, uint64_t workspace_bytes, void *out, void *hip_stream)
+{
+    if (!s) return KVP_E_INVAL;
+    const kvp_config_t &g = s->cfg;
+    if (g.dtype != KVP_BF16 || g.head_dim != 128)
+        return fail(s, KVP_E_INVAL, "kvp_prefill_packets needs a bf16 store with head_dim 128");
+    if (n_req < 0 || !q_offsets || (n_req > 0 && !reqs)) return fail(s, KVP_E_INVAL, "bad request list or q_offsets is null");
+    if (layer < 0 || layer >= g.n_layers) return fail(s, KVP_E_INVAL, "layer %d outside [0, %d)", layer, g.n_layers);
+    if (flags & ~KVP_PREROTATED) return fail(s, KVP_E_INVAL, "unknown flags 0x%x", flags);
+    if (q_offsets[0] != 0) return fail(s, KVP_E_INVAL, "q_offsets[0] must be 0");
+
+    std::vector<int32_t> &sig = s->sig_scratch;
+    sig.clear();
+    sig.push_back(n_req);
+    for (int r = 0; r < n_req; ++r) {
+        const kvp_request_t &rq = reqs[r];
+        if (rq.k < 0 || (rq.k > 0 && !rq.packet_ids)) return fail(s, KVP_E_INVAL, "request %d: bad packet list", r);
+        if (rq.base_pos != 0) return fail(s, KVP_E_INVAL, "request %d: base_pos must be 0 without a cache", r);
+        if (q_offsets[r + 1] < q_offsets[r]) return fail(s, KVP_E_INVAL, "q_offsets is not non-decreasing at %d", r);
+        sig.push_back(rq.k);
+        sig.push_back(q_offsets[r + 1]);
+        for (int j = 0; j < rq.k; ++j) {
+            sig.push_back((int32_t)(rq.packet_ids[j] & 0xFFFFFFFF));
+            sig.push_back((int32_t)(rq.packet_ids[j] >> 32));
+        }
+    }
+    const int tot_q = q_offsets[n_req];
+    if (tot_q > 0 && !s->dry) {
+        if (!q || !k_new || !v_new || !out || !k_tail) return fail(s, KVP_E_INVAL, "q, k_new, v_new, k_tail or out is null");
+        if (((uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)out | (uintptr_t)k_tail) & 15)
+            return fail(s, KVP_E_INVAL, "q, k_new, v_new, k_tail, out must be 16-byte aligned");
+    }
+    kvp_store::PrefillCached &pk = s->pk;
+    const bool hit = pk.valid && pk.stream == hip_stream && pk.sig == sig;
+    if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
+
+    if (!hit) {
+        const int gq = g.n_q_heads / g.n_kv_heads;
+        std::vector<AttnTile> tiles;
+        std::vector<ReqMeta> metas(n_req);
+        std::vector<int> tile_begin(n_req), n_pkt_tiles(n_req);
+        int64_t n_groups_total = 0;
+        for (int r = 0; r < n_req; ++r) {
+            const kvp_request_t &rq = reqs[r];
+            const int n_q = q_offsets[r + 1] - q_offsets[r];
+            int64_t pos = 0;
+            tile_begin[r] = (int)tiles.size();
+            for (int j = 0; j < rq.k; ++j) {
+                auto itp = s->dir.find(rq.packet_ids[j]);
+                if (itp == s->dir.end()) return fail(s, KVP_E_NOTFOUND, "request %d: packet %lld not in the store", r, (long long)rq.packet_ids[j]);
+                const PacketRec &p = itp->second;
+                for (int r0 = 0; r0 < p.n_tokens; r0 += 64)
+                    tiles.push_back(AttnTile{p.elem_off, p.stride, r0, std::min(64, p.n_tokens - r0), (int32_t)pos, 0, 0});
+                pos += p.n_tokens;
+            }
+            if (pos + n_q > g.max_positions) return fail(s, KVP_E_CAPACITY, "request %d: %lld rows exceed max_positions %d", r, (long long)(pos + n_q), g.max_positions);
+            n_pkt_tiles[r] = (int)tiles.size() - tile_begin[r];
+            for (int r0 = 0; r0 < n_q; r0 += 64) tiles.push_back(AttnTile{0, 0, r0, std::min(64, n_q - r0), 0, 1, 0});
+            metas[r] = ReqMeta{(int32_t)pos, q_offsets[r], n_q, 0};
+            n_groups_total += (int64_t)g.n_kv_heads * (((int64_t)n_q * gq + MFMA_BM - 1) / MFMA_BM);
+        }
+        std::vector<AttnGroup> groups;
+        std::vector<AttnItem> items;
+        int n_slots = 0;
+        bool any_split = false;
+        int want = n_groups_total ? (int)std::min<int64_t>(MAX_SPLITS, (target_items(s) + n_groups_total - 1) / n_groups_total) : 1;
+        if (want < 1) want = 1;
+        for (int r = 0; r < n_req; ++r) {
+            const ReqMeta &rq = metas[r];
+            if (rq.n_q == 0) continue;
+            const int n_t = n_pkt_tiles[r] + (rq.n_q + 63) / 64;
+            const int per_item = std::max(4, (n_t + want - 1) / want);  // at least 256 rows per item
+            const int M = rq.n_q * gq;
+            for (int h = 0; h < g.n_kv_heads; ++h)
+                for (int m0 = 0; m0 < M; m0 += MFMA_BM) {
+                    AttnGroup gp;
+                    gp.req = r;
+                    gp.kv_head = h;
+                    gp.m0 = m0;
+                    gp.n_rows = std::min(MFMA_BM, M - m0);
+                    const int t_last = (m0 + gp.n_rows - 1) / gq;
+                    const int vis_tiles = n_pkt_tiles[r] + t_last / 64 + 1;  // causal: later query tiles are invisible
+                    gp.n_splits = (vis_tiles + per_item - 1) / per_item;
+                    gp.part0 = n_slots;
+                    gp.pad0 = gp.pad1 = 0;
+                    if (gp.n_splits > 1) {
+                        n_slots += gp.n_splits;
+                        any_split = true;
+                    }
+                    for (int sp = 0; sp < gp.n_splits; ++sp) {
+                        AttnItem it{};
+                        it.group = (int)groups.size();
+                        it.split = sp;
+                        it.kv_begin = tile_begin[r] + sp * per_item;
+                        it.kv_end = tile_begin[r] + std::min(vis_tiles, (sp + 1) * per_item);
+                        it.req = r;
+                        it.kv_head = h;
+                        it.m0 = m0;
+                        it.n_rows = gp.n_rows;
+                        it.ctx_len = rq.ctx_len;
+                        it.q_off = rq.q_off;
+                        it.part_slot = gp.n_splits > 1 ? gp.part0 + sp : -1;
+                        it.n_q = rq.n_q;
+                        items.push_back(it);
+                    }
+                    groups.push_back(gp);
+                }
+        }
+        const uint64_t need = (uint64_t)n_slots * MFMA_BM * (g.head_dim + 2) * sizeof(float);
+        const uint64_t bytes = metas.size() * sizeof(ReqMeta) + groups.size() * sizeof(AttnGroup) +
+                               items.size() * sizeof(AttnItem) + tiles.size() * sizeof(AttnTile) + 6 * 64;
+        PlanRing::Slot *slot = nullptr;
+        int hrc = s->ring_prefill.acquire(bytes, &slot);
+        if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
+        pk.valid = false;
+        if (s->pf.slot == slot) s->pf.valid = false;  // the two caches share one ring
+        PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
+        ReqMeta *rh = w.put<ReqMeta>(metas.size(), &pk.reqs_dev);
+        if (!metas.empty()) memcpy(rh, metas.data(), metas.size() * sizeof(ReqMeta));
+        AttnGroup *gh = w.put<AttnGroup>(groups.size(), &pk.groups_dev);
+        if (!groups.empty()) memcpy(gh, groups.data(), groups.size() * sizeof(AttnGroup));
+        AttnItem *ih = w.put<AttnItem>(items.size(), &pk.items_dev);
+        if (!items.empty()) memcpy(ih, items.data(), items.size() * sizeof(AttnItem));
+        AttnTile *th = w.put<AttnTile>(tiles.size(), &pk.tiles_dev);
+        if (!tiles.empty()) memcpy(th, tiles.data(), tiles.size() * sizeof(AttnTile));
+
+        s->dbg_attn.clear();
+        int64_t head[6] = {2, MFMA_BM, (int64_t)groups.size(), (int64_t)items.size(), n_slots, (int64_t)need};
+        s->dbg_attn.insert(s->dbg_attn.end(), head, head + 6);
+        for (const AttnGroup &x : groups) {
+            int64_t row[6] = {x.req, x.kv_head, x.m0, x.n_rows, x.part0, x.n_splits};
+            s->dbg_attn.insert(s->dbg_attn.end(), row, row + 6);
+        }
+        for (const AttnItem &x : items) {
+            int64_t row[4] = {x.group, x.split, x.kv_begin, x.kv_end};
+            s->dbg_attn.insert(s->dbg_attn.end(), row, row + 4);
+        }
+        s->dbg_attn.push_back((int64_t)tiles.size());
+        for (const AttnTile &x : tiles) {
+            int64_t row[6] = {x.src_base, x.stride, x.row0, x.n_rows, x.pos, x.kind};
+            s->dbg_attn.insert(s->dbg_attn.end(), row, row + 6);
+        }
+        pk.slot = slot;
+        pk.kind = ATTN_MFMA;
+        pk.bm = MFMA_BM;
+        pk.n_items = (int)items.size();
+        pk.n_groups = (int)groups.size();
+        pk.tot_q = tot_q;
+        pk.any_split = any_split;
+        pk.need = need;
+        pk.sig = sig;
+        pk.stream = hip_stream;
+        if (tot_q > 0 && workspace_bytes < need)
+            return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)need);
+        if (s->dry || tot_q == 0) return KVP_OK;
+        if (need > 0 && (!workspace || ((uintptr_t)workspace & (ALIGN - 1)))) return fail(s, KVP_E_INVAL, "workspace is null or not 256-byte aligned");
+        HIP_TRY(s, hipMemcpyAsync(slot->dev, slot->host, w.off, hipMemcpyHostToDevice, (hipStream_t)hip_stream));
+        pk.valid = true;
+    } else if (tot_q > 0) {
+        if (workspace_bytes < pk.need)
+            return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)pk.need);
+        if (pk.need > 0 && (!workspace || ((uintptr_t)workspace & (ALIGN - 1)))) return fail(s, KVP_E_INVAL, "workspace is null or not 256-byte aligned");
+    }
+    if (s->dry || tot_q == 0) return KVP_OK;
+
+    AttnArgs at;
+    memset(&at, 0, sizeof at);
+    at.q = q;
+    at.k_new = k_new;
+    at.v_new = v_new;
+    at.cs = s->cs_dev;
+    at.prerotated = (flags & KVP_PREROTATED) ? 1 : 0;
+    at.tiles = pk.tiles_dev;
+    at.arena = g.arena;
+    at.k_tail = k_tail;
+    at.n_layers_total = g.n_layers;
+    at.reqs = pk.reqs_dev;
+    at.groups = pk.groups_dev;
+    at.items = pk.items_dev;
+    at.partials = (float *)workspace;
+    at.out = out;
+    at.n_items = pk.n_items;
+    at.n_groups = pk.n_groups;
+    at.layer = layer;
+    at.n_q_heads = g.n_q_heads;
+    at.n_kv = g.n_kv_heads;
+    at.d = g.head_dim;
+    at.bm = pk.bm;
+    at.g = g.n_q_heads / g.n_kv_heads;
+    at.scale_log2e = (float)(1.4426950408889634 / sqrt((double)g.head_dim));
+    int e = launch_attention(g.dtype, at, ATTN_MFMA, hip_stream);
+    if (e) return hip_fail(s, (hipError_t)e, "attention launch");
+    if (pk.any_split) {
+        e = launch_combine(g.dtype, at, hip_stream);
+        if (e) return hip_fail(s, (hipError_t)e, "combine launch");
+    }
+    HIP_TRY(s, hipEventRecord(pk.slot->ev, (hipStream_t)hip_stream));
+    pk.slot->pending = true;
     return KVP_OK;
 }
 

@@ -229,3 +229,45 @@ def test_prefill_errors():
     assert e.value.code == kvp.KVP_E_INVAL
     kvp.kvp_query_prefill(s, cache, 0, None, None, None, np.array([0, 10], np.int32), None, None)
     assert cache.ctx_len[0] == 90                             # prefill never advances ctx_len
+
+
+def test_packets_plan_tiles_and_items():
+    s = dry_store(n_q_heads=32, n_kv_heads=8)
+    lens = {0: 70, 1: 1, 2: 64, 3: 129}
+    for pid, n in lens.items():
+        kvp.kvp_store_put(s, pid, None, None, n_tokens=n)
+    reqs = [([3, 1, 0], 0), ([], 0), ([2, 2], 0)]
+    n_q = [40, 70, 0]
+    q_off = np.concatenate([[0], np.cumsum(n_q)]).astype(np.int32)
+    kvp.kvp_prefill_packets(s, reqs, 0, None, None, None, q_off, None, None, None)
+    p = kvp.kvp_debug_last_plan(s, 1)
+    kind, bm, ng, ni, slots, need = (int(x) for x in p[:6])
+    assert kind == 2 and bm == 128
+    groups = p[6:6 + 6 * ng].reshape(ng, 6)
+    items = p[6 + 6 * ng:6 + 6 * ng + 4 * ni].reshape(ni, 4)
+    rest = p[6 + 6 * ng + 4 * ni:]
+    tiles = rest[1:].reshape(int(rest[0]), 6)
+    # request 0: packets 3, 1, 0 at Delta = 0, 129, 130, then one tile of query rows
+    t0 = [tuple(int(v) for v in t[2:]) for t in tiles[:7]]
+    assert t0 == [(0, 64, 0, 0), (64, 64, 0, 0), (128, 1, 0, 0), (0, 1, 129, 0), (0, 64, 130, 0), (64, 6, 130, 0),
+                  (0, 40, 0, 1)]
+    # request 1 has no packets: two tiles of query rows; request 2 has no query rows: no groups
+    assert [tuple(int(v) for v in t[2:]) for t in tiles[7:9]] == [(0, 64, 0, 1), (64, 6, 0, 1)]
+    assert set(int(x) for x in groups[:, 0]) == {0, 1}
+    for gi, (r, h, m0, n_rows, part0, n_splits) in enumerate(groups):
+        rng = sorted((int(b), int(e)) for g_, sp, b, e in items if g_ == gi)
+        assert len(rng) == n_splits and all(e0 == b1 for (_, e0), (b1, _) in zip(rng, rng[1:]))
+        first = 0 if r == 0 else 7
+        t_last = (m0 + n_rows - 1) // 4
+        n_pkt_tiles = 6 if r == 0 else 0
+        assert rng[0][0] == first and rng[-1][1] == first + n_pkt_tiles + t_last // 64 + 1
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_prefill_packets(s, [([9], 0)], 0, None, None, None, np.array([0, 4], np.int32), None, None, None)
+    assert e.value.code == kvp.KVP_E_NOTFOUND
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_prefill_packets(s, [([0], 3)], 0, None, None, None, np.array([0, 4], np.int32), None, None, None)
+    assert e.value.code == kvp.KVP_E_INVAL
+    f32 = dry_store(dtype="f32")
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_prefill_packets(f32, [([], 0)], 0, None, None, None, np.array([0, 4], np.int32), None, None, None)
+    assert e.value.code == kvp.KVP_E_INVAL

@@ -286,3 +286,89 @@ def test_decode_steps_after_prefill(gpu_device, mk):
         k, v = cache.logical(0, 0, ctx)
         assert np.array_equal(W.to_numpy(k), ko[0][:, :ctx]) and np.array_equal(W.to_numpy(v), vo[0][:, :ctx])
         n_q = 1
+
+
+def _run_packets(w, layers, flags=0, prerotate_with=None):
+    """kvp_prefill_packets over the workload: returns (out[r][layer], k_tail[r][layer])."""
+    import paper_2604_13226_amd as kvp
+    store = build_store(w, kvp)
+    n_req = len(w.requests)
+    q_off = np.zeros(n_req + 1, np.int32)
+    for r in range(n_req):
+        q_off[r + 1] = q_off[r] + w.requests[r].n_q
+    ctx = [w.ctx_len(r) for r in range(n_req)]
+    tot_q = int(q_off[-1])
+    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, n_req, tot_q, max(ctx) + 300))
+    reqs = [(rq.packet_ids, 0) for rq in w.requests]
+    outs, tails = [dict() for _ in range(n_req)], [dict() for _ in range(n_req)]
+    for layer in layers:
+        parts = []
+        for r in range(n_req):
+            q, kn, vn = w.query(r, layer, "cuda")
+            if prerotate_with is not None:
+                q, kn = prerotate_with(r, layer, q, kn, ctx[r])
+            parts.append((q, kn, vn))
+        q, kn, vn = (torch.cat([p[i] for p in parts]).contiguous() for i in range(3))
+        out = torch.full_like(q, float("nan"))
+        k_tail = torch.full_like(kn, float("nan"))
+        kvp.kvp_prefill_packets(store, reqs, layer, q, kn, vn, q_off, k_tail, ws, out, flags)
+        torch.cuda.synchronize()
+        for r in range(n_req):
+            outs[r][layer] = out[q_off[r]:q_off[r + 1]].float().cpu().numpy().astype(np.float64)
+            tails[r][layer] = W.to_numpy(k_tail[q_off[r]:q_off[r + 1]])
+    return outs, tails
+
+
+def _check_packets(w, layers, outs, tails, ref):
+    worst = 0.0
+    for r, rq in enumerate(w.requests):
+        if rq.n_q == 0:
+            continue
+        ctx = ref["ctx"][r]
+        for layer in layers:
+            o = outs[r][layer]
+            assert np.all(np.isfinite(o)), (w.name, r, layer)
+            err = float(np.max(np.abs(o - ref["out"][r][layer])))
+            worst = max(worst, err)
+            assert err <= TOL["bf16"], (w.name, r, layer, err)
+            # rotated K_new: the rows the cache path would have appended, bit for bit
+            want = ref["k"][r][layer][:, ctx:ctx + rq.n_q].transpose(1, 0, 2)     # [n_q][Hkv][d]
+            assert np.array_equal(tails[r][layer], want), (w.name, "k_tail", r, layer)
+    return worst
+
+
+@pytest.mark.parametrize("mk", [
+    lambda: W.llama_k5(n_layers=2, n_packets=16),
+    lambda: W.qwen_k20(n_layers=1, n_packets=40),
+    lambda: W.llama_8k(n_layers=1, n_packets=16),
+])
+def test_prefill_packets_matches_oracle(gpu_device, mk):
+    """Attention read in place from the store (no cache) gives the assembled path's result."""
+    w = mk()
+    layers = list(range(w.n_layers))
+    outs, tails = _run_packets(w, layers)
+    err = _check_packets(w, layers, outs, tails, oracle_workload(w))
+    print(w.name, "in-place max abs err", err)
+
+
+def test_prefill_packets_batch_ragged(gpu_device):
+    w = W.llama_long_b8(n_layers=1, n_packets=6, batch=4, k=4, n_q=150)
+    w.packet_lens[:] = [70, 1, 64, 129, 300, 63]
+    w.requests[1].packet_ids = [2, 2, 5, 2]
+    w.requests[2].n_q = 0
+    w.requests[3].packet_ids = []            # no documents: causal self-attention of the query
+    w.requests[3].n_q = 77
+    outs, tails = _run_packets(w, [0])
+    _check_packets(w, [0], outs, tails, oracle_workload(w))
+
+
+def test_prefill_packets_split_invariance(gpu_device):
+    w = W.llama_k5(n_layers=1, n_packets=8)
+    ref = oracle_workload(w)
+    for target in ("1", "64", "4000"):
+        os.environ["KVP_ATTN_TARGET_ITEMS"] = target
+        try:
+            outs, tails = _run_packets(w, [0])
+        finally:
+            del os.environ["KVP_ATTN_TARGET_ITEMS"]
+        _check_packets(w, [0], outs, tails, ref)
