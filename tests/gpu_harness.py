@@ -103,14 +103,18 @@ def run_workload(w, layers=None, device="cuda:0", flags=0, block_order="random",
     return res
 
 
-def oracle_workload(w, layers=None, prerotated=False, prerotate_with=None):
-    """Same computation with the CPU oracle (contiguous logical caches)."""
+def oracle_workload(w, layers=None, prerotated=False, prerotate_with=None, requests=None):
+    """Same computation with the CPU oracle (contiguous logical caches).  `requests` limits
+    the work to a sample of the requests (the other entries of the result are None)."""
     import oracle
     layers = list(range(w.n_layers)) if layers is None else list(layers)
     f = oracle.inv_freq(w.rope_base, w.head_dim)
     npdt = np.float32 if w.dtype == "f32" else np.uint16
     K, V, outs, ctxs = [], [], [], []
     for r, rq in enumerate(w.requests):
+        if requests is not None and r not in requests:
+            K.append(None), V.append(None), outs.append(None), ctxs.append(w.ctx_len(r))
+            continue
         pk, pv = [], []
         for p in rq.packet_ids:
             k, v = w.packet_kv(p)

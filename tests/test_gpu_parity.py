@@ -372,3 +372,49 @@ def test_prefill_packets_split_invariance(gpu_device):
         finally:
             del os.environ["KVP_ATTN_TARGET_ITEMS"]
         _check_packets(w, [0], outs, tails, ref)
+
+
+def _compare_sampled(w, got, ref, sample, layers):
+    for r in sample:
+        rows = ref["ctx"][r] + w.requests[r].n_q
+        for layer in layers:
+            assert np.array_equal(got["k"][r][layer][:, :rows], ref["k"][r][layer][:, :rows]), (w.name, "K", r, layer)
+            assert np.array_equal(got["v"][r][layer][:, :rows], ref["v"][r][layer][:, :rows]), (w.name, "V", r, layer)
+            err = float(np.max(np.abs(got["out"][r][layer] - ref["out"][r][layer])))
+            assert np.isfinite(err) and err <= 2e-2, (w.name, r, layer, err)
+
+
+def test_full_size_llama_8k_sampled(gpu_device):
+    """The benchmark's workload at full depth: assembly bit-exact on every layer (one launch
+    over 32 layers), attention checked on two layers."""
+    w = W.llama_8k()
+    layers = [5, 31]
+    got = run_workload(w, layers=layers)
+    ref = oracle_workload(w, layers=layers)
+    ctx = ref["ctx"][0]
+    for layer in range(w.n_layers):
+        rows = ctx + (w.requests[0].n_q if layer in layers else 0)
+        assert np.array_equal(got["k"][0][layer][:, :rows], ref["k"][0][layer][:, :rows]), layer
+        assert np.array_equal(got["v"][0][layer][:, :rows], ref["v"][0][layer][:, :rows]), layer
+    for layer in layers:
+        err = float(np.max(np.abs(got["out"][0][layer] - ref["out"][0][layer])))
+        assert err <= 2e-2, (layer, err)
+
+
+def test_full_size_long_context_batch_sampled(gpu_device):
+    """Config 4 (batch 8, 32 packets of 528 rows, 128 query rows) on one layer: the oracle
+    checks two of the eight requests."""
+    w = W.llama_long_b8(n_layers=1)
+    sample = [0, 5]
+    got = run_workload(w)
+    _compare_sampled(w, got, oracle_workload(w, requests=sample), sample, [0])
+
+
+def test_full_size_serving_mix_sampled(gpu_device):
+    """Config 5 (64 requests, paged cache, block 16, Zipf retrieval) on one layer: the oracle
+    checks four of the 64 requests, among them the longest and the shortest context."""
+    w = W.serving_mix(n_layers=1)
+    ctx = [w.ctx_len(r) for r in range(len(w.requests))]
+    sample = sorted({int(np.argmax(ctx)), int(np.argmin(ctx)), 7, 41})
+    got = run_workload(w)
+    _compare_sampled(w, got, oracle_workload(w, requests=sample), sample, [0])
