@@ -86,6 +86,8 @@ def main():
     ap.add_argument("--path", default="cache", choices=["cache", "packets"],
                     help="cache: kvp_assemble + kvp_query_prefill (the metric's path); packets: "
                          "kvp_prefill_packets, attention read in place from the store, no assembly")
+    ap.add_argument("--per-request", action="store_true",
+                    help="batched workloads: also time every request alone (p50 / p99 latency)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (a known-size kernel to scale "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
@@ -199,6 +201,35 @@ def main():
                     "mfma_frac": pre_tflops / BF16_PEAK_TFLOPS},
         "assemble_us_per_layer": asm_ms * 1e3 / w.n_layers,
     }
+    total_rows = sum(ctx) + tot_q
+    res["tokens_per_s"] = total_rows * w.n_layers / (ms_per_step * 1e-3) / w.n_layers  # context + query rows per second
+    if n_req > 1 and args.per_request:
+        # every request issued alone, back to back (closed loop): wall-clock latency of its
+        # kvp_assemble + kvp_query_prefill over the workload's layers
+        lat = []
+        for r in range(n_req):
+            rq = w.requests[r]
+            if rq.n_q == 0:
+                continue
+            wr = type(w)(**{**w.__dict__, "requests": [rq]})
+            c1 = make_cache(wr, kvp, store, dev, t_slack=0)
+            qo1 = np.array([0, rq.n_q], np.int32)
+            parts = [tuple(x[q_off[r]:q_off[r + 1]].contiguous() for x in qkv[layer]) for layer in range(w.n_layers)]
+            o1 = torch.empty_like(parts[0][0])
+            for rep in range(3):
+                torch.cuda.synchronize()
+                t_a = time.perf_counter()
+                kvp.kvp_assemble(store, [(rq.packet_ids, rq.base_pos)], c1)
+                for layer in range(w.n_layers):
+                    q1, k1, v1 = parts[layer]
+                    kvp.kvp_query_prefill(store, c1, layer, q1, k1, v1, qo1, ws, o1)
+                torch.cuda.synchronize()
+                t_b = time.perf_counter()
+            lat.append((t_b - t_a) * 1e6)
+        lat = np.array(lat)
+        res["per_request"] = {"n": int(len(lat)), "p50_us": float(np.percentile(lat, 50)),
+                              "p99_us": float(np.percentile(lat, 99)), "mean_us": float(lat.mean()),
+                              "what": "one request at a time, assemble + prefill over %d layer(s), wall clock" % w.n_layers}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, min(args.cpu_layers, w.n_layers))
     print(json.dumps(res))

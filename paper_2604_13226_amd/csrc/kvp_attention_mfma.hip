@@ -40,7 +40,6 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) void *lds_void_p;
 typedef __attribute__((address_space(1))) const void *glb_void_p;
 
-constexpr int BM = 128;  // packed rows per workgroup
 constexpr int BN = 64;   // kv rows per tile
 constexpr int D = 128;   // head_dim
 constexpr int ROW_BYTES = D * 2;
@@ -139,11 +138,20 @@ enum { SRC_CONTIG = 0, SRC_PAGED = 1, SRC_PACKETS = 2 };
 // a.k_tail, V_new as given).  The keys of a stored packet stay at their local positions;
 // instead the query is rotated by (ctx_len + t) - Delta_j for that packet's tiles, which
 // gives the same scores (Eq. 1: scores depend on the position difference only).
-template <int STAGES, int SRC>
-__global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
+//
+// NW wavefronts per workgroup, 32 packed rows each (BM = 32 NW rows share every K/V tile):
+// NW = 4 with two tile stages lets two workgroups share a CU (small row blocks, many
+// items); NW = 8 reads each K/V row once per 256 packed rows and, alone on its CU, can
+// afford four tile stages, i.e. three tiles in flight.
+template <int STAGES, int SRC, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
 {
+    constexpr int BM = 32 * NW;
+    constexpr int NT = 64 * NW;    // threads
+    constexpr int NI = 16 / NW;    // K (and V) load instructions per wave per tile
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const AttnItem it = a.items[blockIdx.x];
+    if (it.n_rows <= 0) return;  // padding item of the launch order
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
@@ -160,7 +168,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     const int blk0 = SRC == SRC_PAGED ? (it.kv_begin >> a.cache.block_shift) : 0;
     if (SRC == SRC_PAGED) {
         const int nb = (kv_last >> a.cache.block_shift) - blk0 + 1;
-        for (int i = tid; i < nb; i += 256)
+        for (int i = tid; i < nb; i += NT)
             blk_ids[i] = a.cache.block_table[(int64_t)it.req * a.cache.max_blocks + blk0 + i];
         __syncthreads();
     }
@@ -176,7 +184,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     const int64_t tail_off = ((int64_t)it.q_off * a.n_kv + it.kv_head) * D;
 
     // direct HBM -> LDS load of tile tj: wave w, instruction i fills tile rows
-    // 16 i + 4 w .. +3 (1 KiB contiguous in LDS); lane l owns slot (row + l / 16, chunk l % 16)
+    // 4 (NW i + w) .. +3 (1 KiB contiguous in LDS); lane l owns slot (row + l / 16, chunk l % 16)
     const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)lds);
     const int slot_row = lane >> 4, slot_chunk = lane & 15;
     const int k_chunk = slot_chunk ^ ((4 * wave + slot_row) & 15);  // logical chunk fetched
@@ -201,10 +209,10 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
             kt = uniform_ptr(kt);
             vt = uniform_ptr(vt);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                int r = 16 * i + 4 * wave + slot_row;
+            for (int i = 0; i < NI; ++i) {
+                int r = 4 * (NW * i + wave) + slot_row;
                 r = r < td.n_rows - 1 ? r : td.n_rows - 1;  // rows past the tile repeat its last row (masked)
-                const uint32_t dst = st + (uint32_t)((16 * i + 4 * wave) * ROW_BYTES);
+                const uint32_t dst = st + (uint32_t)(4 * (NW * i + wave) * ROW_BYTES);
                 load_to_lds_16(kt, (uint32_t)r * row_bytes + 16 * k_chunk, dst);
                 load_to_lds_16(vt, (uint32_t)r * row_bytes + 16 * v_chunk, dst + TILE_BYTES);
             }
@@ -213,10 +221,10 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
         // rows past the range (last tile only) repeat the last row; they are masked later
         const int max_r = tj == n_tiles - 1 ? last_tile_rows - 1 : BN - 1;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int r = 16 * i + 4 * wave + slot_row;
+        for (int i = 0; i < NI; ++i) {
+            int r = 4 * (NW * i + wave) + slot_row;
             r = r < max_r ? r : max_r;
-            const uint32_t dst = st + (uint32_t)((16 * i + 4 * wave) * ROW_BYTES);
+            const uint32_t dst = st + (uint32_t)(4 * (NW * i + wave) * ROW_BYTES);
             if (SRC == SRC_CONTIG) {
                 const char *kt = k_item + (int64_t)tj * TILE_BYTES;
                 const char *vt = v_item + (int64_t)tj * TILE_BYTES;
@@ -253,7 +261,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
             bf16_t *kcw = SRC == SRC_PACKETS ? (bf16_t *)a.k_tail : (bf16_t *)a.cache.k;
             bf16_t *vcw = (bf16_t *)a.cache.v;
             const int n_chunks = SRC == SRC_PACKETS ? 8 : 24;  // 8 K chunk pairs (+ 16 V chunks)
-            for (int idx = tid; idx < n_tail * n_chunks; idx += 256) {
+            for (int idx = tid; idx < n_tail * n_chunks; idx += NT) {
                 const int qr = tail_lo + idx / n_chunks, cidx = idx % n_chunks;
                 const int row = it.ctx_len + qr;  // position of the row
                 const int64_t src = ((int64_t)(it.q_off + qr) * a.n_kv + it.kv_head) * D;
@@ -296,6 +304,7 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     // this lane's query row
     const int rr = 32 * wave + n;
     const bool row_ok = rr < it.n_rows;
+    const bool wave_active = 32 * wave < it.n_rows;  // wave-uniform
     const int m = it.m0 + (row_ok ? rr : 0);
     const int t = m / g, hq = it.kv_head * g + m % g;
     const int limit = row_ok ? it.ctx_len + t + 1 : 0;  // cache modes: kv rows [0, limit) are visible
@@ -347,9 +356,8 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     for (int ti = 0; ti < n_tiles; ++ti) {
         // tile ti has landed once at most the loads of the tiles issued after it remain
         const int ahead = n_tiles - 1 - ti < STAGES - 2 ? n_tiles - 1 - ti : STAGES - 2;
-        if (ahead >= 3) wait_vmcnt<24>();
-        else if (ahead == 2) wait_vmcnt<16>();
-        else if (ahead == 1) wait_vmcnt<8>();
+        if (ahead >= 2) wait_vmcnt<2 * 2 * NI>();
+        else if (ahead == 1) wait_vmcnt<2 * NI>();
         else wait_vmcnt<0>();
         wg_barrier();  // every wave's part of tile ti is in LDS; everyone is done with tile ti-1
 
@@ -359,10 +367,15 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
         AttnTile td;
         if (SRC == SRC_PACKETS) {
             td = a.tiles[it.kv_begin + ti];
-            if (td.pos != cur_delta) {  // the tile belongs to another packet: re-rotate the query
+            if (td.pos != cur_delta && wave_active) {  // the tile belongs to another packet: re-rotate the query
                 cur_delta = td.pos;
                 load_q(cur_delta);
             }
+        }
+
+        if (!wave_active) {  // a wave without rows only helps to load the tiles
+            if (ti + STAGES - 1 < n_tiles) issue(ti + STAGES - 1);
+            continue;
         }
 
         // ---- S^T - m_ref = K Q^T - m_ref : 2 blocks of 32 kv rows x 32 query rows
@@ -372,13 +385,26 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[kb][r] = init;
+        // K fragments are requested in batches ahead of the MFMAs that use them, so the LDS
+        // latency is paid once per batch instead of once per fragment.
+        {
+            constexpr int KS_PER_BATCH = SRC == SRC_PACKETS ? 4 : 8;  // fewer live registers there
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const int coff = 16 * ((2 * ks + h) ^ (n & 15));
-            bf16x8 a0 = __builtin_bit_cast(bf16x8, *(const uint4 *)(kl + n * ROW_BYTES + coff));
-            bf16x8 a1 = __builtin_bit_cast(bf16x8, *(const uint4 *)(kl + (32 + n) * ROW_BYTES + coff));
-            sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], sacc[0], 0, 0, 0);
-            sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], sacc[1], 0, 0, 0);
+            for (int b = 0; b < 8 / KS_PER_BATCH; ++b) {
+                uint4 kf[2 * KS_PER_BATCH];
+#pragma unroll
+                for (int i = 0; i < KS_PER_BATCH; ++i) {
+                    const int coff = 16 * ((2 * (KS_PER_BATCH * b + i) + h) ^ (n & 15));
+                    kf[2 * i] = *(const uint4 *)(kl + n * ROW_BYTES + coff);
+                    kf[2 * i + 1] = *(const uint4 *)(kl + (32 + n) * ROW_BYTES + coff);
+                }
+                __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the matrix code
+#pragma unroll
+                for (int i = 0; i < KS_PER_BATCH; ++i) {
+                    sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[2 * i]), qf[KS_PER_BATCH * b + i], sacc[0], 0, 0, 0);
+                    sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[2 * i + 1]), qf[KS_PER_BATCH * b + i], sacc[1], 0, 0, 0);
+                }
+            }
         }
         // The next tile's loads are issued while the matrix cores work on S: they refill the
         // stage tile ti-1 used, which every wave left before the barrier above.
@@ -435,6 +461,18 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
         // lane-half h are rows 4h+{0..3} and 8+4h+{0..3} of that step, so the two transposing
         // reads fetch exactly those rows of V for column 32 eb + n.
         float rs0 = 0.f, rs1 = 0.f;
+        typedef __attribute__((address_space(3))) short4v *lds_s4;
+        short4v vfr[2][8];  // V fragments of one k-step: [buffer][2 eb + lo/hi]
+        auto read_v = [&](int step, int buf) {  // step = 2 kb + j
+            const char *vp = vl + (16 * step + 4 * h + tr_row) * ROW_BYTES + tr_half;
+#pragma unroll
+            for (int eb = 0; eb < 4; ++eb) {
+                const int coff = 16 * (4 * (eb ^ tr_row) + tr_x);
+                vfr[buf][2 * eb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(vp + coff));
+                vfr[buf][2 * eb + 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(vp + 8 * ROW_BYTES + coff));
+            }
+        };
+        read_v(0, 0);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             uint32_t pk[8];
@@ -448,18 +486,15 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
             }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
+                const int step = 2 * kb + j;
+                if (step + 1 < 4) read_v(step + 1, (step + 1) & 1);  // next k-step's V lands under these MFMAs
                 uint4 pu = make_uint4(pk[4 * j], pk[4 * j + 1], pk[4 * j + 2], pk[4 * j + 3]);
                 bf16x8 pf = __builtin_bit_cast(bf16x8, pu);
-                const char *vp = vl + (32 * kb + 16 * j + 4 * h + tr_row) * ROW_BYTES + tr_half;
 #pragma unroll
                 for (int eb = 0; eb < 4; ++eb) {
-                    typedef __attribute__((address_space(3))) short4v *lds_s4;
-                    const int coff = 16 * (4 * (eb ^ tr_row) + tr_x);
-                    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(vp + coff));
-                    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4)(vp + 8 * ROW_BYTES + coff));
                     union { short4v s[2]; bf16x8 v; } vf;
-                    vf.s[0] = lo;
-                    vf.s[1] = hi;
+                    vf.s[0] = vfr[step & 1][2 * eb];
+                    vf.s[1] = vfr[step & 1][2 * eb + 1];
                     oacc[eb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf, oacc[eb], 0, 0, 0);
                 }
             }
@@ -499,28 +534,33 @@ __global__ __launch_bounds__(256, 2) void attention_mfma_kernel(AttnArgs a)
     }
 }
 
-constexpr int ATTN_STAGES = 2;  // 64 KiB of tiles + block ids: two workgroups share a CU
-
-template <int SRC> static int launch_variant(const AttnArgs &a, void *stream)
+template <int SRC, int NW> static int launch_variant(const AttnArgs &a, void *stream)
 {
-    constexpr int lds_bytes = ATTN_STAGES * STAGE_BYTES + (SRC == SRC_PAGED ? MAX_BLOCK_IDS * 4 : 0);
+    constexpr int STAGES = NW == 8 ? 4 : 2;
+    constexpr int lds_bytes = STAGES * STAGE_BYTES + (SRC == SRC_PAGED ? MAX_BLOCK_IDS * 4 : 0);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<ATTN_STAGES, SRC>,
+        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<STAGES, SRC, NW>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((attention_mfma_kernel<ATTN_STAGES, SRC>), dim3(a.n_items), dim3(256), lds_bytes,
+    hipLaunchKernelGGL((attention_mfma_kernel<STAGES, SRC, NW>), dim3(a.n_items), dim3(64 * NW), lds_bytes,
                        (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 
+template <int NW> static int launch_nw(const AttnArgs &a, void *stream)
+{
+    if (a.tiles) return launch_variant<SRC_PACKETS, NW>(a, stream);
+    return a.cache.layout != 0 ? launch_variant<SRC_PAGED, NW>(a, stream) : launch_variant<SRC_CONTIG, NW>(a, stream);
+}
+
+// a.bm selects the workgroup shape: 128 packed rows (4 waves) or 256 (8 waves)
 int launch_attention_mfma(const AttnArgs &a, void *stream)
 {
-    if (a.d != D || a.bm != BM) return (int)hipErrorInvalidValue;
-    if (a.tiles) return launch_variant<SRC_PACKETS>(a, stream);
-    return a.cache.layout != 0 ? launch_variant<SRC_PAGED>(a, stream) : launch_variant<SRC_CONTIG>(a, stream);
+    if (a.d != D || (a.bm != 128 && a.bm != 256)) return (int)hipErrorInvalidValue;
+    return a.bm == 256 ? launch_nw<8>(a, stream) : launch_nw<4>(a, stream);
 }
 
 }  // namespace kvp

@@ -84,6 +84,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void attention_generic_kernel(AttnArgs a)
 {
     const AttnItem it = a.items[blockIdx.x];
+    if (it.n_rows <= 0) return;  // padding item of the launch order
     const AttnGroup gp = a.groups[it.group];
     const ReqMeta rq = a.reqs[gp.req];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;

@@ -134,6 +134,7 @@ struct kvp_store {
     int force_generic = 0;
     int target_items = 0;  // 0: the CU count
     int asm_tile_rows = 32, asm_nontemporal = 0;
+    int force_bm = 0;  // test knob: row-block size of the MFMA attention kernel
     size_t esize = 2;
 };
 
@@ -322,6 +323,7 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
     if (tr && (atoi(tr) == 16 || atoi(tr) == 32 || atoi(tr) == 64)) s->asm_tile_rows = atoi(tr);
     const char *nt = getenv("KVP_ASM_NONTEMPORAL");
     if (nt) s->asm_nontemporal = nt[0] == '1';
+    if (const char *fb = getenv("KVP_ATTN_BM")) s->force_bm = atoi(fb);
     const char *ti = getenv("KVP_ATTN_TARGET_ITEMS");  // test knob: how finely split-KV cuts
     if (ti && atoi(ti) > 0) s->target_items = std::min(atoi(ti), 1 << 16);
     if (!dry) {
@@ -522,6 +524,50 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
 // -------------------------------------------------------------------------------------
 namespace {
 
+// Workgroups are dealt to the 8 XCDs round-robin by index, and each XCD has its own L2.
+// Items that read the same K/V rows (same request, KV head and kv range, different row
+// blocks) are therefore placed 8 apart, next to each other in launch order: they run on
+// one XCD at about the same time and all but the first find the tiles in its L2.  Cohorts
+// of unequal size are padded with null items (n_rows = 0: the workgroup exits at once).
+void xcd_order(std::vector<AttnItem> &items)
+{
+    constexpr int XCDS = 8;
+    struct Cohort { int64_t key; std::vector<int> members; };
+    std::vector<Cohort> cohorts;
+    std::unordered_map<int64_t, int> index;
+    bool shared = false;
+    for (int i = 0; i < (int)items.size(); ++i) {
+        const AttnItem &it = items[i];
+        const int64_t key = ((int64_t)it.req << 40) ^ ((int64_t)it.kv_head << 28) ^ (int64_t)it.split;
+        auto f = index.find(key);
+        if (f == index.end()) {
+            index[key] = (int)cohorts.size();
+            cohorts.push_back(Cohort{key, {i}});
+        } else {
+            cohorts[f->second].members.push_back(i);
+            shared = true;
+        }
+    }
+    if (!shared) return;
+    std::vector<AttnItem> out;
+    out.reserve(items.size() + 64);
+    AttnItem null_item{};
+    null_item.group = -1;
+    for (size_t c0 = 0; c0 < cohorts.size(); c0 += XCDS) {
+        const size_t c1 = std::min(cohorts.size(), c0 + XCDS);
+        size_t depth = 0;
+        for (size_t c = c0; c < c1; ++c) depth = std::max(depth, cohorts[c].members.size());
+        const bool last_block = c1 == cohorts.size();
+        for (size_t j = 0; j < depth; ++j)
+            for (size_t c = c0; c < c0 + XCDS; ++c) {
+                if (c < c1 && j < cohorts[c].members.size()) out.push_back(items[cohorts[c].members[j]]);
+                else if (!(last_block && c >= c1 && j + 1 == depth)) out.push_back(null_item);
+            }
+    }
+    while (!out.empty() && out.back().group < 0) out.pop_back();
+    items.swap(out);
+}
+
 struct PrefillPlan {
     int kind = ATTN_GENERIC, bm = 8, bn = 64;
     std::vector<ReqMeta> reqs;
@@ -560,6 +606,11 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
                               : INT32_MAX;
     p.kind = mfma ? ATTN_MFMA : ATTN_GENERIC;
     p.bm = mfma ? MFMA_BM : GENERIC_BM;
+    if (mfma) {  // row blocks of 256 when some request has that many packed rows
+        for (int r = 0; r < n_req; ++r)
+            if ((int64_t)(q_off[r + 1] - q_off[r]) * gq >= 2 * MFMA_BM) p.bm = 2 * MFMA_BM;
+        if (s->force_bm == 128 || s->force_bm == 256) p.bm = s->force_bm;
+    }
     const int min_split = mfma ? 256 : 64;
     p.reqs.resize(n_req);
     int64_t n_groups = 0;
@@ -616,6 +667,7 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
                 p.groups.push_back(gp);
             }
     }
+    xcd_order(p.items);
 }
 
 uint64_t q_rot_bytes(const kvp_store *s, int64_t tot_q)
@@ -631,14 +683,15 @@ uint64_t kvp_prefill_workspace_bytes(const kvp_store_t *s, int32_t n_req, int32_
     const kvp_config_t &g = s->cfg;
     const int gq = g.n_q_heads / g.n_kv_heads;
     const bool mfma = use_mfma(s, nullptr);
-    const int bm = mfma ? MFMA_BM : GENERIC_BM;  // the generic kernel's smaller bm needs less
+    const int bm = mfma ? MFMA_BM : GENERIC_BM;  // smaller or larger row blocks need no more
     // groups <= Hkv * (rows / bm + one ragged block per request); every group has at most
     // ceil(target / groups) <= target / groups + 1 splits (and never more than MAX_SPLITS)
     const uint64_t groups = (uint64_t)g.n_kv_heads * ((uint64_t)max_tot_q * gq / bm + (uint64_t)n_req);
     // (a paged cache may force extra splits: at most max_ctx / 32704 more per group)
     const uint64_t extra = (uint64_t)max_ctx / ((MFMA_MAX_ITEM_BLOCKS - 1) * MFMA_MIN_BLOCK_SIZE / 64 * 64);
     const uint64_t slots = (uint64_t)target_items(s) + (2 + extra) * groups;
-    return q_rot_bytes(s, max_tot_q) + slots * bm * (g.head_dim + 2) * sizeof(float) + ALIGN;
+    // (the MFMA kernel may pick 256-row blocks: twice the rows per slot, no more slots)
+    return q_rot_bytes(s, max_tot_q) + slots * (mfma ? 2 * bm : bm) * (g.head_dim + 2) * sizeof(float) + ALIGN;
 }
 
 int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const void *q, const void *k_new,
@@ -935,6 +988,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
                     groups.push_back(gp);
                 }
         }
+        xcd_order(items);
         const uint64_t need = (uint64_t)n_slots * MFMA_BM * (g.head_dim + 2) * sizeof(float);
         const uint64_t bytes = metas.size() * sizeof(ReqMeta) + groups.size() * sizeof(AttnGroup) +
                                items.size() * sizeof(AttnItem) + tiles.size() * sizeof(AttnTile) + 6 * 64;

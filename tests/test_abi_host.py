@@ -271,3 +271,24 @@ def test_packets_plan_tiles_and_items():
     with pytest.raises(kvp.KvpError) as e:
         kvp.kvp_prefill_packets(f32, [([], 0)], 0, None, None, None, np.array([0, 4], np.int32), None, None, None)
     assert e.value.code == kvp.KVP_E_INVAL
+
+
+def test_items_that_share_kv_rows_land_on_one_xcd():
+    # config-4 geometry: 4 row blocks per (request, KV head); workgroup i runs on XCD i % 8
+    s = dry_store(n_q_heads=32, n_kv_heads=8)
+    n_req = 8
+    cache = kvp.Cache.dry(n_req, t_cap=16896 + 128)
+    cache.ctx_len[:n_req] = 16896
+    q_off = (np.arange(n_req + 1) * 128).astype(np.int32)
+    kvp.kvp_query_prefill(s, cache, 0, None, None, None, q_off, None, None)
+    kind, bm, groups, items, slots, need = _attn_plan(s)
+    where = {}
+    for i, (gi, sp, b, e) in enumerate(items):
+        if gi < 0:
+            continue
+        r, h = int(groups[gi][0]), int(groups[gi][1])
+        where.setdefault((r, h, int(sp)), []).append(i)
+    assert bm == 256 and len(where) * 2 == sum(len(v) for v in where.values())   # 512 packed rows / 256
+    for idx in where.values():
+        assert len({i % 8 for i in idx}) == 1            # one XCD
+        assert max(idx) - min(idx) <= 24                 # adjacent in launch order
