@@ -128,6 +128,14 @@ __device__ __forceinline__ void rotate_chunk_pair(const uint4 &ulo, const uint4 
 
 enum { SRC_CONTIG = 0, SRC_PAGED = 1, SRC_PACKETS = 2 };
 
+// Bench builds (-DKVP_TIMING) record per-workgroup time stamps; product builds compile
+// these to nothing.
+#ifdef KVP_TIMING
+#define KVP_STAMP(slot) do { if (threadIdx.x == 0 && (slot) < 32) a.dbg[blockIdx.x * 32 + (slot)] = wall_clock64(); } while (0)
+#else
+#define KVP_STAMP(slot) do {} while (0)
+#endif
+
 // The query is held rotated and multiplied by log2(e)/sqrt(d), so S = K Q^T is in log2
 // units.  The S accumulators start at -m_ref: after the MFMAs they hold s - m_ref and the
 // probabilities are exp2 of them with no further arithmetic.
@@ -150,6 +158,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
     constexpr int NT = 64 * NW;    // threads
     constexpr int NI = 16 / NW;    // K (and V) load instructions per wave per tile
     extern __shared__ __attribute__((aligned(1024))) char lds[];
+    KVP_STAMP(0);
     const AttnItem it = a.items[blockIdx.x];
     if (it.n_rows <= 0) return;  // padding item of the launch order
     const int tid = threadIdx.x, lane = tid & 63;
@@ -226,8 +235,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
             r = r < max_r ? r : max_r;
             const uint32_t dst = st + (uint32_t)(4 * (NW * i + wave) * ROW_BYTES);
             if (SRC == SRC_CONTIG) {
-                const char *kt = k_item + (int64_t)tj * TILE_BYTES;
-                const char *vt = v_item + (int64_t)tj * TILE_BYTES;
+                const char *kt = uniform_ptr(k_item + (int64_t)tj * TILE_BYTES);
+                const char *vt = uniform_ptr(v_item + (int64_t)tj * TILE_BYTES);
                 load_to_lds_16(kt, (uint32_t)(r * ROW_BYTES + 16 * k_chunk), dst);
                 load_to_lds_16(vt, (uint32_t)(r * ROW_BYTES + 16 * v_chunk), dst + TILE_BYTES);
             } else {
@@ -324,13 +333,16 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
         const int rel = row_ok ? q_pos - delta : 0;
         const float sign = rel < 0 ? -1.f : 1.f;
         const float4 *csr = (const float4 *)(a.cs + (int64_t)(rel < 0 ? -rel : rel) * 64 + 8 * h);
+        float4 cs4[4][4];  // (cos, sin) pairs of elements 16 ks + 8 h + 2 j, + 1
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) cs4[ks][j] = csr[8 * ks + j];
+        __builtin_amdgcn_sched_barrier(0);  // all 24 loads are in flight before the first use
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            float4 cs4[4];  // (cos, sin) pairs of elements 16 ks + 8 h + 2 j, + 1
-#pragma unroll
-            for (int j = 0; j < 4; ++j) cs4[j] = csr[8 * ks + j];
             uint4 olo, ohi;
-            rotate_chunk_pair<false>(qraw[ks], qraw[ks + 4], cs4, sign, a.scale_log2e, olo, ohi);
+            rotate_chunk_pair<false>(qraw[ks], qraw[ks + 4], cs4[ks], sign, a.scale_log2e, olo, ohi);
             qf[ks] = __builtin_bit_cast(bf16x8, olo);
             qf[ks + 4] = __builtin_bit_cast(bf16x8, ohi);
         }
@@ -340,7 +352,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
         for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));
     };
     int cur_delta = SRC == SRC_PACKETS && n_tiles > 0 ? a.tiles[it.kv_begin].pos : 0;
+    KVP_STAMP(1);
     load_q(cur_delta);
+    KVP_STAMP(2);
 
     floatx16 oacc[4];
 #pragma unroll
@@ -359,7 +373,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
         if (ahead >= 2) wait_vmcnt<2 * 2 * NI>();
         else if (ahead == 1) wait_vmcnt<2 * NI>();
         else wait_vmcnt<0>();
+        KVP_STAMP(4 + 2 * ti);
         wg_barrier();  // every wave's part of tile ti is in LDS; everyone is done with tile ti-1
+        KVP_STAMP(5 + 2 * ti);
 
         const int kv0 = it.kv_begin + ti * BN;
         const char *kl = lds + (ti % STAGES) * STAGE_BYTES;
@@ -502,6 +518,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
         l_i += rs0 + rs1;  // this lane's half of the row; the halves are added once, at the end
     }
     l_i += __shfl_xor(l_i, 32, 64);
+    KVP_STAMP(30);
 
     // ---- epilogue: lane holds O[m][32 eb + 8 (r/4) + 4 h + r%4]
     if (row_ok) {
@@ -532,11 +549,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
             }
         }
     }
+    KVP_STAMP(31);
 }
 
-template <int SRC, int NW> static int launch_variant(const AttnArgs &a, void *stream)
+template <int SRC, int NW, int STAGES> static int launch_variant(const AttnArgs &a, void *stream)
 {
-    constexpr int STAGES = NW == 8 ? 4 : 2;
     constexpr int lds_bytes = STAGES * STAGE_BYTES + (SRC == SRC_PAGED ? MAX_BLOCK_IDS * 4 : 0);
     static bool attr_set = false;
     if (!attr_set) {
@@ -550,17 +567,21 @@ template <int SRC, int NW> static int launch_variant(const AttnArgs &a, void *st
     return (int)hipGetLastError();
 }
 
-template <int NW> static int launch_nw(const AttnArgs &a, void *stream)
+template <int NW, int STAGES> static int launch_nw(const AttnArgs &a, void *stream)
 {
-    if (a.tiles) return launch_variant<SRC_PACKETS, NW>(a, stream);
-    return a.cache.layout != 0 ? launch_variant<SRC_PAGED, NW>(a, stream) : launch_variant<SRC_CONTIG, NW>(a, stream);
+    if (a.tiles) return launch_variant<SRC_PACKETS, NW, STAGES>(a, stream);
+    return a.cache.layout != 0 ? launch_variant<SRC_PAGED, NW, STAGES>(a, stream)
+                               : launch_variant<SRC_CONTIG, NW, STAGES>(a, stream);
 }
 
-// a.bm selects the workgroup shape: 128 packed rows (4 waves) or 256 (8 waves)
+// a.bm selects the workgroup shape: 128 packed rows (4 waves) or 256 (8 waves).  The 4-wave
+// shape runs with two tile stages so that two workgroups fit a CU, or -- when the launch has
+// no more items than the chip has CUs (a.deep_pipeline) -- alone on its CU with four stages.
 int launch_attention_mfma(const AttnArgs &a, void *stream)
 {
     if (a.d != D || (a.bm != 128 && a.bm != 256)) return (int)hipErrorInvalidValue;
-    return a.bm == 256 ? launch_nw<8>(a, stream) : launch_nw<4>(a, stream);
+    if (a.bm == 256) return launch_nw<8, 4>(a, stream);
+    return a.deep_pipeline ? launch_nw<4, 4>(a, stream) : launch_nw<4, 2>(a, stream);
 }
 
 }  // namespace kvp

@@ -110,6 +110,7 @@ struct AttnArgs {
     float *partials;  // [slot][bm][d + 2]: O~ rows, then m[bm], then l[bm]
     void *out;        // [tot_q][Hq][d]
     int32_t n_items, n_groups, layer, n_q_heads, n_kv, d, bm, g;
+    int32_t deep_pipeline;  // MFMA kernel: the launch has at most one item per CU
     float scale_log2e;  // log2(e) / sqrt(d)
 #ifdef KVP_TIMING
     unsigned long long *dbg;  // per-item timestamps (bench builds only)

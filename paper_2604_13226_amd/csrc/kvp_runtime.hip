@@ -862,6 +862,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     at.n_kv = g.n_kv_heads;
     at.d = g.head_dim;
     at.bm = pf.bm;
+    at.deep_pipeline = pf.n_items <= s->n_cu;
     at.g = g.n_q_heads / g.n_kv_heads;
     at.scale_log2e = (float)(1.4426950408889634 / sqrt((double)g.head_dim));
     e = launch_attention(g.dtype, at, pf.kind, hip_stream);
@@ -1069,6 +1070,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     at.n_kv = g.n_kv_heads;
     at.d = g.head_dim;
     at.bm = pk.bm;
+    at.deep_pipeline = pk.n_items <= s->n_cu;
     at.g = g.n_q_heads / g.n_kv_heads;
     at.scale_log2e = (float)(1.4426950408889634 / sqrt((double)g.head_dim));
     int e = launch_attention(g.dtype, at, ATTN_MFMA, hip_stream);
