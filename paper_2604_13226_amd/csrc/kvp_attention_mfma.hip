@@ -34,6 +34,7 @@ namespace kvp {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
@@ -58,6 +59,32 @@ __device__ __forceinline__ uint32_t pack_bf16_hw(float a, float b)
 template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// x of lane l and of lane l ^ 32, without a trip through the LDS crossbar: the half-swap
+// leaves lanes 0..31 of the first result with x[l], of the second with x[l + 32], and the
+// upper lanes with the same pair.  The second operand is made opaque to the compiler: given
+// the same value twice it was seen to use the first result for both.
+__device__ __forceinline__ void xhalf_pair(float x, float &lo, float &hi)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, x), w = u;
+    asm volatile("" : "+v"(w));
+    const auto r = __builtin_amdgcn_permlane32_swap(u, w, false, false);
+    uint32_t r0 = r[0], r1 = r[1];
+    asm volatile("" : "+v"(r0), "+v"(r1));
+    lo = __builtin_bit_cast(float, r0);
+    hi = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ float xhalf_max(float x)
+{
+    float lo, hi;
+    xhalf_pair(x, lo, hi);
+    return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float xhalf_sum(float x)
+{
+    float lo, hi;
+    xhalf_pair(x, lo, hi);
+    return lo + hi;
 }
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
@@ -132,8 +159,15 @@ enum { SRC_CONTIG = 0, SRC_PAGED = 1, SRC_PACKETS = 2 };
 // these to nothing.
 #ifdef KVP_TIMING
 #define KVP_STAMP(slot) do { if (threadIdx.x == 0 && (slot) < 32) a.dbg[blockIdx.x * 32 + (slot)] = wall_clock64(); } while (0)
+// per-wave cycle totals of the tile loop's phases
+#define KVP_PHASE_DECL unsigned long long ph_acc[6] = {0, 0, 0, 0, 0, 0}, ph_last = __builtin_readcyclecounter()
+#define KVP_PHASE(i) do { const unsigned long long t_ = __builtin_readcyclecounter(); ph_acc[i] += t_ - ph_last; ph_last = t_; } while (0)
+#define KVP_PHASE_WRITE do { if ((threadIdx.x & 63) == 0 && a.dbg2) for (int i_ = 0; i_ < 6; ++i_) a.dbg2[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 8 + i_] = ph_acc[i_]; } while (0)
 #else
 #define KVP_STAMP(slot) do {} while (0)
+#define KVP_PHASE_DECL do {} while (0)
+#define KVP_PHASE(i) do {} while (0)
+#define KVP_PHASE_WRITE do {} while (0)
 #endif
 
 // The query is held rotated and multiplied by log2(e)/sqrt(d), so S = K Q^T is in log2
@@ -147,22 +181,30 @@ enum { SRC_CONTIG = 0, SRC_PAGED = 1, SRC_PACKETS = 2 };
 // instead the query is rotated by (ctx_len + t) - Delta_j for that packet's tiles, which
 // gives the same scores (Eq. 1: scores depend on the position difference only).
 //
-// NW wavefronts per workgroup, 32 packed rows each (BM = 32 NW rows share every K/V tile):
-// NW = 4 with two tile stages lets two workgroups share a CU (small row blocks, many
-// items); NW = 8 reads each K/V row once per 256 packed rows and, alone on its CU, can
-// afford four tile stages, i.e. three tiles in flight.
-template <int STAGES, int SRC, int NW>
+// NW wavefronts per workgroup in KS groups of RW = NW / KS; a wave owns 32 packed rows, a
+// group owns BM = 32 RW rows, and all NW waves share the loading of every K/V tile.
+//   NW 4, KS 1, 2 stages: two workgroups share a CU (small row blocks, many items);
+//   NW 8, KS 1, 4 stages: each K/V row is fetched once per 256 packed rows, three tiles in
+//                         flight, one workgroup per CU;
+//   NW 8, KS 2, 4 stages: 128 rows, the two groups take alternate tiles of the item's range
+//                         (an in-workgroup split-KV that halves the serial chain of a
+//                         latency-bound item) and merge their (m, l, O) through LDS.
+template <int STAGES, int SRC, int NW, int KS>
 __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
 {
-    constexpr int BM = 32 * NW;
+    constexpr int RW = NW / KS;    // waves per group
+    constexpr int BM = 32 * RW;
     constexpr int NT = 64 * NW;    // threads
     constexpr int NI = 16 / NW;    // K (and V) load instructions per wave per tile
+    constexpr int PR = STAGES / KS - 1;  // rounds (of KS tiles) loaded ahead
+    static_assert(STAGES % KS == 0 && PR >= 1, "stages");
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     KVP_STAMP(0);
     const AttnItem it = a.items[blockIdx.x];
     if (it.n_rows <= 0) return;  // padding item of the launch order
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_r = wave % RW, grp = wave / RW;  // row wave inside its group, group
     const int n = lane & 31, h = lane >> 5;
     const int g = a.g;
 
@@ -307,18 +349,18 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
     }
 
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
+    for (int s = 0; s < KS * PR; ++s)
         if (s < n_tiles && !(s == 0 && early0)) issue(s);
 
     // this lane's query row
-    const int rr = 32 * wave + n;
+    const int rr = 32 * wave_r + n;
     const bool row_ok = rr < it.n_rows;
-    const bool wave_active = 32 * wave < it.n_rows;  // wave-uniform
+    const bool wave_active = 32 * wave_r < it.n_rows;  // wave-uniform
     const int m = it.m0 + (row_ok ? rr : 0);
     const int t = m / g, hq = it.kv_head * g + m % g;
     const int limit = row_ok ? it.ctx_len + t + 1 : 0;  // cache modes: kv rows [0, limit) are visible
     // smallest limit among the wave's rows (rows are ordered by query token)
-    const int wave_limit = it.ctx_len + (it.m0 + 32 * wave) / g + 1;
+    const int wave_limit = it.ctx_len + (it.m0 + 32 * wave_r) / g + 1;
 
     // B operand of S^T = K Q^T: lane holds Q[m][16 ks + 8 h .. +7] for ks = 0..7, rotated by
     // `rel` positions and multiplied by log2(e)/sqrt(d).  Element 16 ks + 8 h + j (ks < 4)
@@ -362,20 +404,50 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[eb][r] = 0.f;
     float m_ref = -INFINITY, l_i = 0.f;  // reference max (log2 units) and running sum
+    // -m_ref in all 16 slots (every accumulator of a lane belongs to the same query row): the
+    // first S MFMA of a tile takes it as its C operand, so S - m_ref costs no extra instruction.
+    // Rewritten only when the reference moves; pinned so that it is not rebuilt per tile.
+    // (The in-place packet variant has no registers to spare and rebuilds it per tile.)
+    constexpr bool KEEP_CINIT = SRC != SRC_PACKETS;
+    floatx16 cinit;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) cinit[r] = 0.f;
+    if (KEEP_CINIT) asm volatile("" : "+v"(cinit));
 
     const int tr_row = (lane & 15) >> 2;
     const int tr_x = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);  // 16-byte chunk inside the 64-byte column group
     const int tr_half = 8 * (lane & 1);
 
-    for (int ti = 0; ti < n_tiles; ++ti) {
-        // tile ti has landed once at most the loads of the tiles issued after it remain
-        const int ahead = n_tiles - 1 - ti < STAGES - 2 ? n_tiles - 1 - ti : STAGES - 2;
-        if (ahead >= 2) wait_vmcnt<2 * 2 * NI>();
-        else if (ahead == 1) wait_vmcnt<2 * NI>();
-        else wait_vmcnt<0>();
-        KVP_STAMP(4 + 2 * ti);
-        wg_barrier();  // every wave's part of tile ti is in LDS; everyone is done with tile ti-1
-        KVP_STAMP(5 + 2 * ti);
+
+    const int n_rounds = (n_tiles + KS - 1) / KS;
+    KVP_PHASE_DECL;
+    for (int rd = 0; rd < n_rounds; ++rd) {
+        KVP_PHASE(5);
+        // round rd's tiles have landed once only the loads of the rounds issued after it remain
+        {
+            const int hi = KS * (rd + PR) < n_tiles ? KS * (rd + PR) : n_tiles;
+            const int lo = KS * (rd + 1) < n_tiles ? KS * (rd + 1) : n_tiles;
+            const int younger = hi - lo;  // tiles issued after this round, 0 .. KS (PR - 1)
+            if (younger >= 3) wait_vmcnt<3 * 2 * NI>();
+            else if (younger == 2) wait_vmcnt<2 * 2 * NI>();
+            else if (younger == 1) wait_vmcnt<2 * NI>();
+            else wait_vmcnt<0>();
+        }
+        KVP_STAMP(4 + 2 * rd);
+        KVP_PHASE(0);
+        wg_barrier();  // every wave's part of the round is in LDS; everyone is done with round rd-1
+        KVP_STAMP(5 + 2 * rd);
+        KVP_PHASE(1);
+        auto refill = [&]() {  // the stages round rd-1 used take round rd+PR
+#pragma unroll
+            for (int k2 = 0; k2 < KS; ++k2)
+                if (KS * (rd + PR) + k2 < n_tiles) issue(KS * (rd + PR) + k2);
+        };
+        const int ti = KS * rd + grp;  // this group's tile of the round
+        if (ti >= n_tiles || !wave_active) {  // nothing to compute: only help to load
+            refill();
+            continue;
+        }
 
         const int kv0 = it.kv_begin + ti * BN;
         const char *kl = lds + (ti % STAGES) * STAGE_BYTES;
@@ -389,18 +461,13 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
             }
         }
 
-        if (!wave_active) {  // a wave without rows only helps to load the tiles
-            if (ti + STAGES - 1 < n_tiles) issue(ti + STAGES - 1);
-            continue;
-        }
-
         // ---- S^T - m_ref = K Q^T - m_ref : 2 blocks of 32 kv rows x 32 query rows
-        const float init = m_ref == -INFINITY ? 0.f : -m_ref;
         floatx16 sacc[2];
+        if (!KEEP_CINIT) {
+            const float c = m_ref == -INFINITY ? 0.f : -m_ref;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kb][r] = init;
+            for (int r = 0; r < 16; ++r) cinit[r] = c;
+        }
         // K fragments are requested in batches ahead of the MFMAs that use them, so the LDS
         // latency is paid once per batch instead of once per fragment.
         {
@@ -417,14 +484,16 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
                 __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the matrix code
 #pragma unroll
                 for (int i = 0; i < KS_PER_BATCH; ++i) {
-                    sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[2 * i]), qf[KS_PER_BATCH * b + i], sacc[0], 0, 0, 0);
-                    sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[2 * i + 1]), qf[KS_PER_BATCH * b + i], sacc[1], 0, 0, 0);
+                    const bool head = b == 0 && i == 0;  // compile-time: the tile's first k-step
+                    sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[2 * i]), qf[KS_PER_BATCH * b + i], head ? cinit : sacc[0], 0, 0, 0);
+                    sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[2 * i + 1]), qf[KS_PER_BATCH * b + i], head ? cinit : sacc[1], 0, 0, 0);
                 }
             }
         }
-        // The next tile's loads are issued while the matrix cores work on S: they refill the
-        // stage tile ti-1 used, which every wave left before the barrier above.
-        if (ti + STAGES - 1 < n_tiles) issue(ti + STAGES - 1);
+        // The next loads are issued while the matrix cores work on S: they refill the stages
+        // the previous round used, which every wave left before the barrier above.
+        refill();
+        KVP_PHASE(2);
 
         // ---- online softmax; accumulator r of block kb is tile row 32 kb + 8 (r/4) + 4 h + r%4
         if (SRC == SRC_PACKETS) {
@@ -451,7 +520,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
 #pragma unroll
         for (int r = 2; r < 15; ++r) mx = max3(mx, sacc[1][r], sacc[0][r + 1]);
         mx = fmaxf(mx, sacc[1][15]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));  // row max relative to m_ref
+        mx = xhalf_max(mx);  // row max relative to m_ref
         // The reference moves when a row sees its first visible entry (it becomes that
         // tile's maximum) and afterwards only when the maximum outgrows the slack.
         const bool first = m_ref == -INFINITY;
@@ -469,6 +538,12 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
             for (int eb = 0; eb < 4; ++eb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) oacc[eb][r] *= alpha;
+            if (KEEP_CINIT) {
+                const float c = m_ref == -INFINITY ? 0.f : -m_ref;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) cinit[r] = c;
+                asm volatile("" : "+v"(cinit));
+            }
         }
 
         // ---- P = exp2(S - m_ref) and O^T += V^T P^T, one 32-row block at a time so that the
@@ -476,7 +551,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
         // k-step j of block kb covers tile rows 32 kb + 16 j + [0, 16); P^T slots 0..7 of
         // lane-half h are rows 4h+{0..3} and 8+4h+{0..3} of that step, so the two transposing
         // reads fetch exactly those rows of V for column 32 eb + n.
+        KVP_PHASE(3);
         float rs0 = 0.f, rs1 = 0.f;
+        const bf16x2 bf16_ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
         typedef __attribute__((address_space(3))) short4v *lds_s4;
         short4v vfr[2][8];  // V fragments of one k-step: [buffer][2 eb + lo/hi]
         auto read_v = [&](int step, int buf) {  // step = 2 kb + j
@@ -496,9 +573,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
             for (int r = 0; r < 16; r += 2) {
                 float p0 = __builtin_amdgcn_exp2f(sacc[kb][r]);
                 float p1 = __builtin_amdgcn_exp2f(sacc[kb][r + 1]);
-                rs0 += p0;
-                rs1 += p1;
                 pk[r >> 1] = pack_bf16_hw(p0, p1);
+                // the row sum takes the rounded values, i.e. exactly what multiplies V
+                const bf16x2 pp = __builtin_bit_cast(bf16x2, pk[r >> 1]);
+                if (r & 2) rs1 = __builtin_amdgcn_fdot2_f32_bf16(pp, bf16_ones, rs1, false);
+                else rs0 = __builtin_amdgcn_fdot2_f32_bf16(pp, bf16_ones, rs0, false);
             }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -516,9 +595,47 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
             }
         }
         l_i += rs0 + rs1;  // this lane's half of the row; the halves are added once, at the end
+        KVP_PHASE(4);
     }
-    l_i += __shfl_xor(l_i, 32, 64);
+    KVP_PHASE_WRITE;
+    l_i = xhalf_sum(l_i);
     KVP_STAMP(30);
+
+    if (KS == 2) {
+        // ---- merge the two groups' (m, l, O) of each row through LDS (the tile stages are free
+        // once every wave has left the loop): group 1 writes, group 0 folds it in and goes on.
+        wg_barrier();
+        float *xo = (float *)lds;                      // [16][RW][64 lanes][4]
+        float *xm = xo + 16 * RW * 64 * 4;             // [RW][64] m, then [RW][64] l
+        if (grp == 1) {
+#pragma unroll
+            for (int eb = 0; eb < 4; ++eb)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    *(float4 *)(xo + (((4 * eb + q4) * RW + wave_r) * 64 + lane) * 4) =
+                        make_float4(oacc[eb][4 * q4], oacc[eb][4 * q4 + 1], oacc[eb][4 * q4 + 2], oacc[eb][4 * q4 + 3]);
+            xm[wave_r * 64 + lane] = m_ref;
+            xm[RW * 64 + wave_r * 64 + lane] = l_i;
+        }
+        __syncthreads();
+        if (grp == 1) return;
+        const float m1 = xm[wave_r * 64 + lane], l1 = xm[RW * 64 + wave_r * 64 + lane];
+        const float mm = fmaxf(m_ref, m1);
+        const float a0 = m_ref == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_ref - mm);
+        const float a1 = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m1 - mm);
+        m_ref = mm;
+        l_i = l_i * a0 + l1 * a1;
+#pragma unroll
+        for (int eb = 0; eb < 4; ++eb)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const float4 o1 = *(const float4 *)(xo + (((4 * eb + q4) * RW + wave_r) * 64 + lane) * 4);
+                oacc[eb][4 * q4] = oacc[eb][4 * q4] * a0 + o1.x * a1;
+                oacc[eb][4 * q4 + 1] = oacc[eb][4 * q4 + 1] * a0 + o1.y * a1;
+                oacc[eb][4 * q4 + 2] = oacc[eb][4 * q4 + 2] * a0 + o1.z * a1;
+                oacc[eb][4 * q4 + 3] = oacc[eb][4 * q4 + 3] * a0 + o1.w * a1;
+            }
+    }
 
     // ---- epilogue: lane holds O[m][32 eb + 8 (r/4) + 4 h + r%4]
     if (row_ok) {
@@ -552,36 +669,36 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
     KVP_STAMP(31);
 }
 
-template <int SRC, int NW, int STAGES> static int launch_variant(const AttnArgs &a, void *stream)
+template <int SRC, int NW, int KS, int STAGES> static int launch_variant(const AttnArgs &a, void *stream)
 {
     constexpr int lds_bytes = STAGES * STAGE_BYTES + (SRC == SRC_PAGED ? MAX_BLOCK_IDS * 4 : 0);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<STAGES, SRC, NW>,
+        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<STAGES, SRC, NW, KS>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return (int)e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((attention_mfma_kernel<STAGES, SRC, NW>), dim3(a.n_items), dim3(64 * NW), lds_bytes,
+    hipLaunchKernelGGL((attention_mfma_kernel<STAGES, SRC, NW, KS>), dim3(a.n_items), dim3(64 * NW), lds_bytes,
                        (hipStream_t)stream, a);
     return (int)hipGetLastError();
 }
 
-template <int NW, int STAGES> static int launch_nw(const AttnArgs &a, void *stream)
+template <int NW, int KS, int STAGES> static int launch_nw(const AttnArgs &a, void *stream)
 {
-    if (a.tiles) return launch_variant<SRC_PACKETS, NW, STAGES>(a, stream);
-    return a.cache.layout != 0 ? launch_variant<SRC_PAGED, NW, STAGES>(a, stream)
-                               : launch_variant<SRC_CONTIG, NW, STAGES>(a, stream);
+    if (a.tiles) return launch_variant<SRC_PACKETS, NW, KS, STAGES>(a, stream);
+    return a.cache.layout != 0 ? launch_variant<SRC_PAGED, NW, KS, STAGES>(a, stream)
+                               : launch_variant<SRC_CONTIG, NW, KS, STAGES>(a, stream);
 }
 
-// a.bm selects the workgroup shape: 128 packed rows (4 waves) or 256 (8 waves).  The 4-wave
-// shape runs with two tile stages so that two workgroups fit a CU, or -- when the launch has
-// no more items than the chip has CUs (a.deep_pipeline) -- alone on its CU with four stages.
+// a.bm selects the row block: 256 packed rows (8 waves) or 128.  128-row blocks run as 4 waves
+// with two tile stages (two workgroups per CU), or -- a.split_in_wg, chosen when the launch
+// has at most one item per CU -- as 8 waves in two groups that take alternate tiles.
 int launch_attention_mfma(const AttnArgs &a, void *stream)
 {
     if (a.d != D || (a.bm != 128 && a.bm != 256)) return (int)hipErrorInvalidValue;
-    if (a.bm == 256) return launch_nw<8, 4>(a, stream);
-    return a.deep_pipeline ? launch_nw<4, 4>(a, stream) : launch_nw<4, 2>(a, stream);
+    if (a.bm == 256) return launch_nw<8, 1, 4>(a, stream);
+    return a.split_in_wg ? launch_nw<8, 2, 4>(a, stream) : launch_nw<4, 1, 2>(a, stream);
 }
 
 }  // namespace kvp

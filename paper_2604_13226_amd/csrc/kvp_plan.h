@@ -110,10 +110,11 @@ struct AttnArgs {
     float *partials;  // [slot][bm][d + 2]: O~ rows, then m[bm], then l[bm]
     void *out;        // [tot_q][Hq][d]
     int32_t n_items, n_groups, layer, n_q_heads, n_kv, d, bm, g;
-    int32_t deep_pipeline;  // MFMA kernel: the launch has at most one item per CU
+    int32_t split_in_wg;  // MFMA kernel, 128-row blocks: two wave groups take alternate tiles
     float scale_log2e;  // log2(e) / sqrt(d)
 #ifdef KVP_TIMING
     unsigned long long *dbg;  // per-item timestamps (bench builds only)
+    unsigned long long *dbg2;  // per-wave phase cycle totals (bench builds only)
 #endif
 };
 

@@ -172,6 +172,17 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a)
     const int64_t slot = (int64_t)a.bm * (d + 2);
     const float *base = a.partials + (int64_t)gp.part0 * slot;
     const float *ml = base + (int64_t)a.bm * d + rr;
+    const float *row = base + (int64_t)rr * d;
+    // The first splits' O pieces are requested before the weights are known, so that their
+    // trip overlaps the (m, l) loads and the reductions instead of following them.
+    constexpr int EARLY = 8;  // float4 loads per lane issued up front: 2 EARLY splits of 128 columns
+    const bool early = (d & 3) == 0 && 4 * li < d;
+    float4 v0[EARLY];
+#pragma unroll
+    for (int i = 0; i < EARLY; ++i) {
+        const int sq = 2 * i + hf, sp = sq < ns ? sq : ns - 1;
+        v0[i] = early ? *(const float4 *)(row + sp * slot + 4 * li) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
     float mi = -INFINITY, lv = 0.f;
     if (lane < ns) { mi = ml[lane * slot]; lv = ml[lane * slot + a.bm]; }
     float mx = mi;
@@ -182,14 +193,24 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a)
     const int m = gp.m0 + rr;
     const int t = m / a.g, hq = gp.kv_head * a.g + m % a.g;
     T *op = (T *)a.out + ((int64_t)(rq.q_off + t) * a.n_q_heads + hq) * d;
-    const float *row = base + (int64_t)rr * d;
     if ((d & 3) == 0) {
         for (int e = 4 * li; e < d; e += 128) {
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            int s_from = 0;
+            if (e == 4 * li) {  // the pieces already on their way
+#pragma unroll
+                for (int i = 0; i < EARLY; ++i) {
+                    const int sq = 2 * i + hf, sp = sq < ns ? sq : ns - 1;
+                    float ws = __shfl(w, sp, 64);  // executed by all 64 lanes
+                    if (sq >= ns) ws = 0.f;
+                    acc.x += v0[i].x * ws; acc.y += v0[i].y * ws; acc.z += v0[i].z * ws; acc.w += v0[i].w * ws;
+                }
+                s_from = 2 * EARLY;
+            }
 #pragma unroll 8
-            for (int s2 = 0; s2 < ns; s2 += 2) {  // same trip count in both halves
+            for (int s2 = s_from; s2 < ns; s2 += 2) {  // same trip count in both halves
                 const int sq = s2 + hf, sp = sq < ns ? sq : ns - 1;
-                float ws = __shfl(w, sp, 64);  // executed by all 64 lanes
+                float ws = __shfl(w, sp, 64);
                 if (sq >= ns) ws = 0.f;
                 const float4 v = *(const float4 *)(row + sp * slot + e);
                 acc.x += v.x * ws; acc.y += v.y * ws; acc.z += v.z * ws; acc.w += v.w * ws;

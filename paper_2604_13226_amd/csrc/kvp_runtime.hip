@@ -132,9 +132,10 @@ struct kvp_store {
     bool dry = false;
     int n_cu = 256;
     int force_generic = 0;
-    int target_items = 0;  // 0: the CU count
+    int target_items = 0;  // 0: three quarters of the CU count (measured optimum at 8K context)
     int asm_tile_rows = 32, asm_nontemporal = 0;
     int force_bm = 0;  // test knob: row-block size of the MFMA attention kernel
+    int force_split_in_wg = -1;  // test knob: 0 / 1 forces the 4-wave / 8-wave-in-two-groups shape of 128-row blocks
     size_t esize = 2;
 };
 
@@ -324,6 +325,7 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
     const char *nt = getenv("KVP_ASM_NONTEMPORAL");
     if (nt) s->asm_nontemporal = nt[0] == '1';
     if (const char *fb = getenv("KVP_ATTN_BM")) s->force_bm = atoi(fb);
+    if (const char *fd = getenv("KVP_ATTN_SPLIT_IN_WG")) s->force_split_in_wg = atoi(fd) != 0;
     const char *ti = getenv("KVP_ATTN_TARGET_ITEMS");  // test knob: how finely split-KV cuts
     if (ti && atoi(ti) > 0) s->target_items = std::min(atoi(ti), 1 << 16);
     if (!dry) {
@@ -582,7 +584,7 @@ constexpr int MFMA_BM = 128;
 constexpr int GENERIC_BM = 8;
 constexpr int MAX_SPLITS = 64;
 
-int target_items(const kvp_store *s) { return s->target_items > 0 ? s->target_items : s->n_cu; }
+int target_items(const kvp_store *s) { return s->target_items > 0 ? s->target_items : s->n_cu * 3 / 4; }
 
 // Groups of packed rows and their split-KV items.  Every group of a request gets the same
 // split length (a multiple of bn rows), chosen so the launch has about target_items work
@@ -862,7 +864,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     at.n_kv = g.n_kv_heads;
     at.d = g.head_dim;
     at.bm = pf.bm;
-    at.deep_pipeline = pf.n_items <= s->n_cu;
+    at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : 0;
     at.g = g.n_q_heads / g.n_kv_heads;
     at.scale_log2e = (float)(1.4426950408889634 / sqrt((double)g.head_dim));
     e = launch_attention(g.dtype, at, pf.kind, hip_stream);
@@ -1070,7 +1072,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     at.n_kv = g.n_kv_heads;
     at.d = g.head_dim;
     at.bm = pk.bm;
-    at.deep_pipeline = pk.n_items <= s->n_cu;
+    at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : 0;
     at.g = g.n_q_heads / g.n_kv_heads;
     at.scale_log2e = (float)(1.4426950408889634 / sqrt((double)g.head_dim));
     int e = launch_attention(g.dtype, at, ATTN_MFMA, hip_stream);

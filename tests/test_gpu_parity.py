@@ -13,6 +13,26 @@ from tests.gpu_harness import build_store, make_cache, oracle_workload, run_work
 pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-5, "bf16": 2e-2}
+# Second bar, on the root-mean-square error relative to the root-mean-square output.  The
+# bf16 path rounds Q (after rotation and scaling), P and the output to 8 significant bits,
+# each a relative error of at most 2^-9 with no preferred sign; a systematic slip of a few
+# per cent (a wrong normaliser, a reference maximum that differs between lanes of one row)
+# stays under the absolute bar on outputs of size 0.05 but not under this one.
+REL_RMS_TOL = {"f32": 2e-6, "bf16": 6e-3}
+WORST_REL_RMS = {"f32": 0.0, "bf16": 0.0}
+
+
+def check_output(o, ref, dtype, tag):
+    """Both bars for one request-layer output; returns the maximum absolute error."""
+    assert np.all(np.isfinite(o)), ("non-finite output",) + tuple(tag)
+    err = float(np.max(np.abs(o - ref)))
+    assert err <= TOL[dtype], tuple(tag) + (err,)
+    rms_ref = float(np.sqrt(np.mean(ref * ref)))
+    if rms_ref > 0:
+        rel = float(np.sqrt(np.mean((o - ref) ** 2))) / rms_ref
+        WORST_REL_RMS[dtype] = max(WORST_REL_RMS[dtype], rel)
+        assert rel <= REL_RMS_TOL[dtype], tuple(tag) + ("relative rms", rel)
+    return err
 
 
 def compare(w, got, ref, layers=None):
@@ -25,11 +45,7 @@ def compare(w, got, ref, layers=None):
             assert np.array_equal(got["v"][r][layer], ref["v"][r][layer]), (w.name, "V", r, layer)
             if w.requests[r].n_q == 0:
                 continue
-            o = got["out"][r][layer]
-            assert np.all(np.isfinite(o)), (w.name, "non-finite output", r, layer)
-            err = float(np.max(np.abs(o - ref["out"][r][layer])))
-            worst = max(worst, err)
-            assert err <= TOL[w.dtype], (w.name, r, layer, err)
+            worst = max(worst, check_output(got["out"][r][layer], ref["out"][r][layer], w.dtype, (w.name, r, layer)))
     return worst
 
 
@@ -242,8 +258,7 @@ def test_full_size_llama_k5_sampled(gpu_device):
         assert np.array_equal(got["k"][r][layer][:, :rows], ref["k"][r][layer][:, :rows]), layer
         assert np.array_equal(got["v"][r][layer][:, :rows], ref["v"][r][layer][:, :rows]), layer
     for layer in layers:
-        err = float(np.max(np.abs(got["out"][r][layer] - ref["out"][r][layer])))
-        assert err <= 2e-2, (layer, err)
+        check_output(got["out"][r][layer], ref["out"][r][layer], w.dtype, (w.name, layer))
 
 
 @pytest.mark.parametrize("mk", [lambda: W.tiny_fp32(), lambda: W.llama_k5(n_layers=1, n_packets=8)])
@@ -279,8 +294,7 @@ def test_decode_steps_after_prefill(gpu_device, mk):
         kvp.kvp_query_prefill(store, cache, 0, q, kn, vn, [0, n_q], ws, out)
         torch.cuda.synchronize()
         ref = oracle.query_prefill(w.dtype, W.to_numpy(q), W.to_numpy(kn), W.to_numpy(vn), f, ctx, ko[0], vo[0])
-        err = float(np.max(np.abs(out.float().cpu().numpy().astype(np.float64) - ref)))
-        assert err <= TOL[w.dtype], (step, err)
+        check_output(out.float().cpu().numpy().astype(np.float64), ref, w.dtype, ("decode step", step))
         ctx += n_q
         cache.ctx_len[0] = ctx            # the caller advances the context after the layer(s)
         k, v = cache.logical(0, 0, ctx)
@@ -326,11 +340,7 @@ def _check_packets(w, layers, outs, tails, ref):
             continue
         ctx = ref["ctx"][r]
         for layer in layers:
-            o = outs[r][layer]
-            assert np.all(np.isfinite(o)), (w.name, r, layer)
-            err = float(np.max(np.abs(o - ref["out"][r][layer])))
-            worst = max(worst, err)
-            assert err <= TOL["bf16"], (w.name, r, layer, err)
+            worst = max(worst, check_output(outs[r][layer], ref["out"][r][layer], "bf16", (w.name, r, layer)))
             # rotated K_new: the rows the cache path would have appended, bit for bit
             want = ref["k"][r][layer][:, ctx:ctx + rq.n_q].transpose(1, 0, 2)     # [n_q][Hkv][d]
             assert np.array_equal(tails[r][layer], want), (w.name, "k_tail", r, layer)
@@ -380,8 +390,7 @@ def _compare_sampled(w, got, ref, sample, layers):
         for layer in layers:
             assert np.array_equal(got["k"][r][layer][:, :rows], ref["k"][r][layer][:, :rows]), (w.name, "K", r, layer)
             assert np.array_equal(got["v"][r][layer][:, :rows], ref["v"][r][layer][:, :rows]), (w.name, "V", r, layer)
-            err = float(np.max(np.abs(got["out"][r][layer] - ref["out"][r][layer])))
-            assert np.isfinite(err) and err <= 2e-2, (w.name, r, layer, err)
+            check_output(got["out"][r][layer], ref["out"][r][layer], w.dtype, (w.name, r, layer))
 
 
 def test_full_size_llama_8k_sampled(gpu_device):
@@ -397,8 +406,7 @@ def test_full_size_llama_8k_sampled(gpu_device):
         assert np.array_equal(got["k"][0][layer][:, :rows], ref["k"][0][layer][:, :rows]), layer
         assert np.array_equal(got["v"][0][layer][:, :rows], ref["v"][0][layer][:, :rows]), layer
     for layer in layers:
-        err = float(np.max(np.abs(got["out"][0][layer] - ref["out"][0][layer])))
-        assert err <= 2e-2, (layer, err)
+        check_output(got["out"][0][layer], ref["out"][0][layer], w.dtype, (w.name, layer))
 
 
 def test_full_size_long_context_batch_sampled(gpu_device):
@@ -418,3 +426,8 @@ def test_full_size_serving_mix_sampled(gpu_device):
     sample = sorted({int(np.argmax(ctx)), int(np.argmin(ctx)), 7, 41})
     got = run_workload(w)
     _compare_sampled(w, got, oracle_workload(w, requests=sample), sample, [0])
+
+
+def test_zz_report_worst_relative_rms(gpu_device):
+    """Prints the largest relative rms error the tests above saw (run with -s to see it)."""
+    print("worst relative rms error:", WORST_REL_RMS)
