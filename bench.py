@@ -163,6 +163,7 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     asm_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
     pre_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    step_ms = np.array([e[0].elapsed_time(e[2]) for e in events])   # GPU time of each timed step
 
     # algorithmic bytes / flops
     tok_bytes = w.kv_bytes_per_token_layer()
@@ -201,6 +202,9 @@ def main():
                     "hbm_frac": pre_gbs / HBM_PEAK_GBS, "achieved_TFLOPs": pre_tflops,
                     "mfma_frac": pre_tflops / BF16_PEAK_TFLOPS},
         "assemble_us_per_layer": asm_ms * 1e3 / w.n_layers,
+        "step_us_per_layer": {"p50": float(np.percentile(step_ms, 50)) * 1e3 / w.n_layers,
+                              "p99": float(np.percentile(step_ms, 99)) * 1e3 / w.n_layers,
+                              "what": "per timed step, HIP events around assemble + all layers' prefill"},
     }
     total_rows = sum(ctx) + tot_q
     res["tokens_per_s"] = total_rows * w.n_layers / (ms_per_step * 1e-3) / w.n_layers  # context + query rows per second

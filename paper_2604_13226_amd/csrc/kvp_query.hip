@@ -181,7 +181,7 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a)
 #pragma unroll
     for (int i = 0; i < EARLY; ++i) {
         const int sq = 2 * i + hf, sp = sq < ns ? sq : ns - 1;
-        v0[i] = early ? *(const float4 *)(row + sp * slot + 4 * li) : make_float4(0.f, 0.f, 0.f, 0.f);
+        v0[i] = early && sq < ns ? *(const float4 *)(row + sp * slot + 4 * li) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
     float mi = -INFINITY, lv = 0.f;
     if (lane < ns) { mi = ml[lane * slot]; lv = ml[lane * slot + a.bm]; }
