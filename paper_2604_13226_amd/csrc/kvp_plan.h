@@ -65,8 +65,8 @@ struct ReqMeta {
 // A group is rows [m0, m0 + bm) of one pair; a work item is one kv range of a group.
 struct AttnGroup {
     int32_t req, kv_head, m0, n_rows;  // n_rows <= bm
-    int32_t part0, n_splits;           // partial slots part0 .. part0 + n_splits - 1
-    int32_t pad0, pad1;
+    int32_t part0, n_splits;           // partial slots part0 .. part0 + n_splits - 1 (part0 = group index x AttnArgs::part_stride)
+    int32_t q_off, pad1;               // first row of the request in q / out
 };
 // Self-contained (one 64-byte read tells a workgroup everything it needs).
 struct AttnItem {
@@ -111,6 +111,7 @@ struct AttnArgs {
     void *out;        // [tot_q][Hq][d]
     int32_t n_items, n_groups, layer, n_q_heads, n_kv, d, bm, g;
     int32_t split_in_wg;  // MFMA kernel, 128-row blocks: two wave groups take alternate tiles
+    int32_t part_stride;  // partial slots per group
     float scale_log2e;  // log2(e) / sqrt(d)
 #ifdef KVP_TIMING
     unsigned long long *dbg;  // per-item timestamps (bench builds only)

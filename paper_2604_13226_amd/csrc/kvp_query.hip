@@ -162,29 +162,30 @@ constexpr int COMBINE_ROWS = 4;  // rows per 256-thread workgroup
 template <typename T>
 __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a)
 {
-    const AttnGroup gp = a.groups[blockIdx.x];
-    if (gp.n_splits <= 1) return;
     const int lane = threadIdx.x & 63, li = lane & 31, hf = lane >> 5;
     const int rr = (int)blockIdx.y * COMBINE_ROWS + (threadIdx.x >> 6);
-    if (rr >= gp.n_rows) return;
-    const ReqMeta rq = a.reqs[gp.req];
-    const int d = a.d, ns = gp.n_splits;
+    const int d = a.d, stride = a.part_stride;
     const int64_t slot = (int64_t)a.bm * (d + 2);
-    const float *base = a.partials + (int64_t)gp.part0 * slot;
+    // Group gi's partial slots start at gi * stride, so the first loads below do not wait for
+    // the group's record; slots and rows the group does not use hold stale bytes of the
+    // workspace (in bounds) and are masked once the record has arrived.
+    const float *base = a.partials + (int64_t)blockIdx.x * stride * slot;
     const float *ml = base + (int64_t)a.bm * d + rr;
     const float *row = base + (int64_t)rr * d;
-    // The first splits' O pieces are requested before the weights are known, so that their
-    // trip overlaps the (m, l) loads and the reductions instead of following them.
     constexpr int EARLY = 8;  // float4 loads per lane issued up front: 2 EARLY splits of 128 columns
-    const bool early = (d & 3) == 0 && 4 * li < d;
+    const bool early = (d & 3) == 0 && 4 * li < d && rr < a.bm;
     float4 v0[EARLY];
 #pragma unroll
     for (int i = 0; i < EARLY; ++i) {
-        const int sq = 2 * i + hf, sp = sq < ns ? sq : ns - 1;
-        v0[i] = early && sq < ns ? *(const float4 *)(row + sp * slot + 4 * li) : make_float4(0.f, 0.f, 0.f, 0.f);
+        const int sq = 2 * i + hf;
+        v0[i] = early && sq < stride ? *(const float4 *)(row + sq * slot + 4 * li) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
     float mi = -INFINITY, lv = 0.f;
-    if (lane < ns) { mi = ml[lane * slot]; lv = ml[lane * slot + a.bm]; }
+    if (lane < stride && rr < a.bm) { mi = ml[lane * slot]; lv = ml[lane * slot + a.bm]; }
+    const AttnGroup gp = a.groups[blockIdx.x];
+    const int ns = gp.n_splits;
+    if (ns <= 1 || rr >= gp.n_rows) return;
+    if (lane >= ns) { mi = -INFINITY; lv = 0.f; }
     float mx = mi;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a)
     const float inv = 1.f / wave_sum(lv * w);
     const int m = gp.m0 + rr;
     const int t = m / a.g, hq = gp.kv_head * a.g + m % a.g;
-    T *op = (T *)a.out + ((int64_t)(rq.q_off + t) * a.n_q_heads + hq) * d;
+    T *op = (T *)a.out + ((int64_t)(gp.q_off + t) * a.n_q_heads + hq) * d;
     if ((d & 3) == 0) {
         for (int e = 4 * li; e < d; e += 128) {
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -201,9 +202,8 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a)
 #pragma unroll
                 for (int i = 0; i < EARLY; ++i) {
                     const int sq = 2 * i + hf, sp = sq < ns ? sq : ns - 1;
-                    float ws = __shfl(w, sp, 64);  // executed by all 64 lanes
-                    if (sq >= ns) ws = 0.f;
-                    acc.x += v0[i].x * ws; acc.y += v0[i].y * ws; acc.z += v0[i].z * ws; acc.w += v0[i].w * ws;
+                    const float ws = __shfl(w, sp, 64);  // executed by all 64 lanes
+                    if (sq < ns) { acc.x += v0[i].x * ws; acc.y += v0[i].y * ws; acc.z += v0[i].z * ws; acc.w += v0[i].w * ws; }
                 }
                 s_from = 2 * EARLY;
             }

@@ -122,7 +122,7 @@ struct kvp_store {
         const AttnGroup *groups_dev = nullptr;
         const AttnItem *items_dev = nullptr;
         const AttnTile *tiles_dev = nullptr;
-        int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0;
+        int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0, part_stride = 1;
         bool any_split = false;
         uint64_t need = 0;
     } pf, pk;  // pf: kvp_query_prefill, pk: kvp_prefill_packets
@@ -531,6 +531,17 @@ namespace {
 // blocks) are therefore placed 8 apart, next to each other in launch order: they run on
 // one XCD at about the same time and all but the first find the tiles in its L2.  Cohorts
 // of unequal size are padded with null items (n_rows = 0: the workgroup exits at once).
+// Partial slots: group gi owns slots gi * stride .. + stride - 1 (stride = the largest split
+// count of the call), so the combine kernel knows where a group's partials are before it has
+// read the group's record.  stride 0: nothing is split, no slots.
+void assign_part_slots(std::vector<AttnGroup> &groups, std::vector<AttnItem> &items, int stride, int &n_slots)
+{
+    for (size_t gi = 0; gi < groups.size(); ++gi) groups[gi].part0 = (int32_t)gi * stride;
+    for (auto &it : items)
+        if (it.part_slot >= 0) it.part_slot += groups[it.group].part0;
+    n_slots = (int)groups.size() * stride;
+}
+
 void xcd_order(std::vector<AttnItem> &items)
 {
     constexpr int XCDS = 8;
@@ -576,7 +587,7 @@ struct PrefillPlan {
     std::vector<int32_t> row_req;
     std::vector<AttnGroup> groups;
     std::vector<AttnItem> items;
-    int n_slots = 0;
+    int n_slots = 0, part_stride = 1;
     bool any_split = false;
 };
 
@@ -644,12 +655,11 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
                 const int t_last = (m0 + gp.n_rows - 1) / gq;
                 const int vis = rq.ctx_len + t_last + 1;
                 gp.n_splits = (vis + split_len - 1) / split_len;
-                gp.part0 = p.n_slots;
-                gp.pad0 = gp.pad1 = 0;
-                if (gp.n_splits > 1) {
-                    p.n_slots += gp.n_splits;
-                    p.any_split = true;
-                }
+                gp.part0 = 0;  // set below, once the slot stride is known
+                gp.q_off = rq.q_off;
+                gp.pad1 = 0;
+                if (gp.n_splits > 1) p.any_split = true;
+                p.part_stride = std::max(p.part_stride, gp.n_splits);
                 for (int sp = 0; sp < gp.n_splits; ++sp) {
                     AttnItem it{};
                     it.group = (int)p.groups.size();
@@ -662,13 +672,14 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
                     it.n_rows = gp.n_rows;
                     it.ctx_len = rq.ctx_len;
                     it.q_off = rq.q_off;
-                    it.part_slot = gp.n_splits > 1 ? gp.part0 + sp : -1;
+                    it.part_slot = gp.n_splits > 1 ? sp : -1;  // relative to the group until the stride is known
                     it.n_q = rq.n_q;
                     p.items.push_back(it);
                 }
                 p.groups.push_back(gp);
             }
     }
+    assign_part_slots(p.groups, p.items, p.any_split ? p.part_stride : 0, p.n_slots);
     xcd_order(p.items);
 }
 
@@ -794,6 +805,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         pf.bt_stride = bt_stride;
         pf.tot_q = tot_q;
         pf.any_split = p.any_split;
+        pf.part_stride = p.part_stride;
         pf.need = need;
         pf.sig = sig;
         pf.stream = hip_stream;
@@ -865,6 +877,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     at.d = g.head_dim;
     at.bm = pf.bm;
     at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : 0;
+    at.part_stride = pf.part_stride;
     at.g = g.n_q_heads / g.n_kv_heads;
     at.scale_log2e = (float)(1.4426950408889634 / sqrt((double)g.head_dim));
     e = launch_attention(g.dtype, at, pf.kind, hip_stream);
@@ -946,7 +959,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         }
         std::vector<AttnGroup> groups;
         std::vector<AttnItem> items;
-        int n_slots = 0;
+        int n_slots = 0, part_stride = 1;
         bool any_split = false;
         int want = n_groups_total ? (int)std::min<int64_t>(MAX_SPLITS, (target_items(s) + n_groups_total - 1) / n_groups_total) : 1;
         if (want < 1) want = 1;
@@ -966,12 +979,11 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
                     const int t_last = (m0 + gp.n_rows - 1) / gq;
                     const int vis_tiles = n_pkt_tiles[r] + t_last / 64 + 1;  // causal: later query tiles are invisible
                     gp.n_splits = (vis_tiles + per_item - 1) / per_item;
-                    gp.part0 = n_slots;
-                    gp.pad0 = gp.pad1 = 0;
-                    if (gp.n_splits > 1) {
-                        n_slots += gp.n_splits;
-                        any_split = true;
-                    }
+                    gp.part0 = 0;
+                    gp.q_off = rq.q_off;
+                    gp.pad1 = 0;
+                    if (gp.n_splits > 1) any_split = true;
+                    part_stride = std::max(part_stride, gp.n_splits);
                     for (int sp = 0; sp < gp.n_splits; ++sp) {
                         AttnItem it{};
                         it.group = (int)groups.size();
@@ -984,13 +996,14 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
                         it.n_rows = gp.n_rows;
                         it.ctx_len = rq.ctx_len;
                         it.q_off = rq.q_off;
-                        it.part_slot = gp.n_splits > 1 ? gp.part0 + sp : -1;
+                        it.part_slot = gp.n_splits > 1 ? sp : -1;
                         it.n_q = rq.n_q;
                         items.push_back(it);
                     }
                     groups.push_back(gp);
                 }
         }
+        assign_part_slots(groups, items, any_split ? part_stride : 0, n_slots);
         xcd_order(items);
         const uint64_t need = (uint64_t)n_slots * MFMA_BM * (g.head_dim + 2) * sizeof(float);
         const uint64_t bytes = metas.size() * sizeof(ReqMeta) + groups.size() * sizeof(AttnGroup) +
@@ -1033,6 +1046,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         pk.n_groups = (int)groups.size();
         pk.tot_q = tot_q;
         pk.any_split = any_split;
+        pk.part_stride = part_stride;
         pk.need = need;
         pk.sig = sig;
         pk.stream = hip_stream;
@@ -1073,6 +1087,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     at.d = g.head_dim;
     at.bm = pk.bm;
     at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : 0;
+    at.part_stride = pk.part_stride;
     at.g = g.n_q_heads / g.n_kv_heads;
     at.scale_log2e = (float)(1.4426950408889634 / sqrt((double)g.head_dim));
     int e = launch_attention(g.dtype, at, ATTN_MFMA, hip_stream);

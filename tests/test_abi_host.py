@@ -204,11 +204,15 @@ def test_prefill_plan_covers_every_row_and_kv_exactly_once(cfg):
                 assert (r, h, m) in seen
     assert len(seen) == sum(n_q) * s.cfg.n_q_heads
     # split groups own disjoint partial slots; the workspace bound covers the need
+    # (group gi owns slots gi * stride .., stride = the largest split count of the call)
     used = []
-    for r, h, m0, n_rows, part0, n_splits in groups:
+    stride = max([n_splits for *_, n_splits in groups if n_splits > 1] + [0])
+    for gi, (r, h, m0, n_rows, part0, n_splits) in enumerate(groups):
+        assert part0 == gi * stride
         if n_splits > 1:
             used += list(range(part0, part0 + n_splits))
-    assert sorted(used) == list(range(slots))
+    assert len(set(used)) == len(used) and all(0 <= u < slots for u in used)
+    assert slots == len(groups) * stride
     bound = kvp.kvp_prefill_workspace_bytes(s, n_req, int(q_off[-1]), max(c + q for c, q in zip(ctx, n_q)))
     assert bound >= need
 
