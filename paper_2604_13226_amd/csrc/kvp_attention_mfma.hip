@@ -651,8 +651,32 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
                     u.y = pack_bf16_hw(oacc[eb][4 * q4 + 2] * inv, oacc[eb][4 * q4 + 3] * inv);
                     *(uint2 *)(op + 32 * eb + 8 * q4 + 4 * h) = u;
                 }
-        } else {
-            float *pp = a.partials + (int64_t)it.part_slot * BM * (D + 2);
+        }
+    }
+    if (it.part_slot >= 0) {
+        float *pp = a.partials + (int64_t)it.part_slot * BM * (D + 2);
+        if (KS == 1) {
+            // The split's unnormalised O rows go through LDS so that they leave as whole 512-byte
+            // rows (two per store instruction) instead of 32-byte pieces: each wave parks its
+            // 32 x 128 floats in its own 16 KiB of the (now idle) tile stages, 16-byte chunk c of
+            // row n at chunk c ^ n, and reads them back row by row.
+            wg_barrier();  // every wave is done with the tiles
+            char *reg = lds + wave * (32 * D * 4);
+#pragma unroll
+            for (int eb = 0; eb < 4; ++eb)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    *(float4 *)(reg + n * (D * 4) + 16 * ((8 * eb + 2 * q4 + h) ^ n)) =
+                        make_float4(oacc[eb][4 * q4], oacc[eb][4 * q4 + 1], oacc[eb][4 * q4 + 2], oacc[eb][4 * q4 + 3]);
+            // (a wave reads only what it wrote itself: no barrier, the compiler orders the two)
+            const int c = lane & 31;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int r = 2 * j + (lane >> 5);
+                const float4 f = *(const float4 *)(reg + r * (D * 4) + 16 * (c ^ r));
+                if (32 * wave_r + r < it.n_rows) *(float4 *)(pp + (int64_t)(32 * wave_r + r) * D + 4 * c) = f;
+            }
+        } else if (row_ok) {
 #pragma unroll
             for (int eb = 0; eb < 4; ++eb)
 #pragma unroll
@@ -660,10 +684,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
                     float4 f = make_float4(oacc[eb][4 * q4], oacc[eb][4 * q4 + 1], oacc[eb][4 * q4 + 2], oacc[eb][4 * q4 + 3]);
                     *(float4 *)(pp + (int64_t)rr * D + 32 * eb + 8 * q4 + 4 * h) = f;
                 }
-            if (h == 0) {
-                pp[BM * D + rr] = m_ref;
-                pp[BM * D + BM + rr] = l_i;
-            }
+        }
+        if (row_ok && h == 0) {
+            pp[BM * D + rr] = m_ref;
+            pp[BM * D + BM + rr] = l_i;
         }
     }
     KVP_STAMP(31);
