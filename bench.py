@@ -16,6 +16,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+PCIE_PEAK_GBS = 63.0     # PCIe 5.0 x16, one direction
 HBM_PEAK_GBS = 8000.0
 BF16_PEAK_TFLOPS = 2500.0
 
@@ -87,6 +88,11 @@ def main():
     ap.add_argument("--path", default="cache", choices=["cache", "packets"],
                     help="cache: kvp_assemble + kvp_query_prefill (the metric's path); packets: "
                          "kvp_prefill_packets, attention read in place from the store, no assembly")
+    ap.add_argument("--store", default="device", choices=["device", "host"],
+                    help="device: packet store in HBM (the metric's configuration); host: in pinned host "
+                         "memory, read over PCIe at every assembly (the paper's tier; reported apart)")
+    ap.add_argument("--pipeline", action="store_true",
+                    help="assemble layer by layer on a second stream, under the previous layer's prefill")
     ap.add_argument("--per-request", action="store_true",
                     help="batched workloads: also time every request alone (p50 / p99 latency)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -108,7 +114,7 @@ def main():
     w = make_workload(args.workload)
     n_req = len(w.requests)
     store = build_store(w, kvp, dev, packets=list(range(len(w.packet_lens)))
-                        if len(w.packet_lens) <= 256 else None)
+                        if len(w.packet_lens) <= 256 and args.store == "device" else None, arena=args.store)
     cache = make_cache(w, kvp, store, dev, t_slack=0)
     reqs = [(rq.packet_ids, rq.base_pos) for rq in w.requests]
     q_off = np.zeros(n_req + 1, np.int32)
@@ -128,9 +134,34 @@ def main():
     k_tail = torch.empty_like(qkv[0][1])
     reqs0 = [(rq.packet_ids, 0) for rq in w.requests]
 
+    pipelined = args.pipeline and args.path == "cache"
+    if pipelined:
+        # layer l is assembled on a side stream (default priority) while layer l-1 is attended
+        # to; ready[l] orders prefill(l) behind assemble(l), free[l] orders the next step's
+        # assemble(l) behind this step's prefill(l)
+        side = torch.cuda.Stream()
+        main = torch.cuda.current_stream()
+        ready = [torch.cuda.Event() for _ in range(w.n_layers)]
+        free = [torch.cuda.Event() for _ in range(w.n_layers)]
+        for e in free:
+            e.record(main)
+
     def step(ev=None):
         if ev:
             ev[0].record()
+        if pipelined:
+            for layer in range(w.n_layers):
+                side.wait_event(free[layer])
+                kvp.kvp_assemble(store, reqs, cache, layer, layer + 1, stream=side)
+                ready[layer].record(side)
+                main.wait_event(ready[layer])
+                q, kn, vn = qkv[layer]
+                kvp.kvp_query_prefill(store, cache, layer, q, kn, vn, q_off, ws, out)
+                free[layer].record(main)
+            if ev:
+                ev[1].record()
+                ev[2].record()
+            return
         if args.path == "cache":
             kvp.kvp_assemble(store, reqs, cache)
         if ev:
@@ -173,6 +204,8 @@ def main():
     pre_flops = sum(4.0 * rq.n_q * c * w.n_q_heads * w.head_dim
                     + 2.0 * rq.n_q * rq.n_q * w.n_q_heads * w.head_dim
                     for c, rq in zip(ctx, w.requests))                                 # per layer
+    if pipelined:  # the two overlap: only the whole step is observable
+        asm_ms, pre_ms = ms_per_step, ms_per_step
     asm_gbs = asm_bytes / (max(asm_ms, 1e-6) * 1e-3) / 1e9
     pre_us_layer = pre_ms * 1e3 / w.n_layers
     pre_gbs = pre_bytes / (pre_us_layer * 1e-6) / 1e9
@@ -192,7 +225,8 @@ def main():
         "config": {"workload": "%s: %d layers, Hq %d / Hkv %d, d %d, %d request(s), ctx %s, n_q %s"
                    % (w.name, w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, n_req,
                       ctx[:4], [rq.n_q for rq in w.requests[:4]]),
-                   "layout": "paged" if w.paged else "contiguous", "path": args.path},
+                   "layout": "paged" if w.paged else "contiguous", "path": args.path,
+                   "store": args.store, "pipelined": bool(pipelined)},
         "roofline": {"bound": "hbm", "kernel": "assemble_vec_kernel (all layers, one launch)",
                      "achieved": asm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": asm_gbs / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
@@ -206,6 +240,14 @@ def main():
                               "p99": float(np.percentile(step_ms, 99)) * 1e3 / w.n_layers,
                               "what": "per timed step, HIP events around assemble + all layers' prefill"},
     }
+    if args.store == "host":
+        # the packets cross PCIe at every assembly (or at every in-place read): that link bounds
+        # the step; its rate is whole-step bytes read from the store over wall time
+        store_bytes = (asm_bytes / 2.0) if args.path == "cache" else pre_bytes * w.n_layers
+        res["roofline"] = {"bound": "pcie", "kernel": "reads of the host-resident store",
+                           "achieved": store_bytes / (ms_per_step * 1e-3) / 1e9, "peak": PCIE_PEAK_GBS,
+                           "unit": "GB/s", "frac": store_bytes / (ms_per_step * 1e-3) / 1e9 / PCIE_PEAK_GBS,
+                           "traffic": None, "bytes_per_step": store_bytes}
     total_rows = sum(ctx) + tot_q
     res["tokens_per_s"] = total_rows * w.n_layers / (ms_per_step * 1e-3) / w.n_layers  # context + query rows per second
     if n_req > 1 and args.per_request:

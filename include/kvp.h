@@ -80,7 +80,10 @@ typedef struct {
     int32_t max_positions;       /* bound on ctx_len + n_q; sizes the cos/sin table */
     double rope_base;
     const float *inv_freq; /* HOST, nullable, [head_dim/2]; replaces rope_base */
-    void *arena;           /* DEVICE, 256-byte aligned, caller-owned packet storage */
+    void *arena;           /* caller-owned packet storage, 256-byte aligned: DEVICE memory, or pinned
+                            * HOST memory mapped into the device (hipHostMalloc, torch pin_memory):
+                            * the tier the paper keeps its packets in (Sec. 5.1); the kernels then
+                            * read the packets over PCIe, in place, at every assembly */
     uint64_t arena_bytes;
     int32_t device; /* HIP device ordinal, or KVP_DEVICE_NONE */
 } kvp_config_t;
@@ -111,6 +114,8 @@ int kvp_store_put(kvp_store_t *store, int64_t packet_id, int32_t n_tokens, const
 int32_t kvp_store_packet_len(const kvp_store_t *store, int64_t packet_id);
 /* Bytes of the arena in use. */
 uint64_t kvp_store_bytes_used(const kvp_store_t *store);
+/* 1 if the arena is pinned host memory (packets are read over PCIe), 0 if device memory. */
+int32_t kvp_store_arena_on_host(const kvp_store_t *store);
 /* Arena bytes a packet of n_tokens rows takes (alignment included). */
 uint64_t kvp_packet_bytes(const kvp_config_t *cfg, int32_t n_tokens);
 

@@ -46,6 +46,7 @@ EXPORTS = {
     "kvp_store_put": (_i32, [_vp, _i64, _i32, _vp, _vp, _i32, _vp]),
     "kvp_store_packet_len": (_i32, [_vp, _i64]),
     "kvp_store_bytes_used": (_u64, [_vp]),
+    "kvp_store_arena_on_host": (_i32, [_vp]),
     "kvp_packet_bytes": (_u64, [ctypes.POINTER(kvp_config_t), _i32]),
     "kvp_assemble": (_i32, [_vp, ctypes.POINTER(kvp_request_t), _i32, _i32, _i32,
                             ctypes.POINTER(kvp_cache_t), _vp]),
@@ -119,9 +120,10 @@ class Store:
 
 
 def kvp_store_create(n_layers, n_q_heads, n_kv_heads, head_dim, dtype, rope_base, max_positions,
-                     arena_bytes, n_header=0, n_trailer=0, device=0, inv_freq=None):
-    """kvp_store_create: allocates the arena with torch on `device` and creates the store.
-    device=KVP_DEVICE_NONE makes a planning-only store (no GPU touched)."""
+                     arena_bytes, n_header=0, n_trailer=0, device=0, inv_freq=None, arena="device"):
+    """kvp_store_create: allocates the arena with torch (on `device`, or with arena="host" in
+    pinned host memory) and creates the store.  device=KVP_DEVICE_NONE makes a planning-only
+    store (no GPU touched)."""
     L = load()
     cfg = kvp_config_t()
     cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim = n_layers, n_q_heads, n_kv_heads, head_dim
@@ -133,9 +135,13 @@ def kvp_store_create(n_layers, n_q_heads, n_kv_heads, head_dim, dtype, rope_base
     if inv_freq is not None:
         keep = np.ascontiguousarray(inv_freq, np.float32)
         cfg.inv_freq = keep.ctypes.data
-    arena = None
+    where, arena = arena, None
     if device != KVP_DEVICE_NONE:
-        arena = torch.empty(int(arena_bytes) + 256, dtype=torch.uint8, device="cuda:%d" % device)
+        if where == "host":
+            arena = torch.empty(int(arena_bytes) + 256, dtype=torch.uint8, pin_memory=True)
+        else:
+            assert where == "device", where
+            arena = torch.empty(int(arena_bytes) + 256, dtype=torch.uint8, device="cuda:%d" % device)
         base = (arena.data_ptr() + 255) // 256 * 256
         cfg.arena = base
     cfg.arena_bytes = int(arena_bytes)
@@ -175,6 +181,10 @@ def kvp_store_packet_len(store, packet_id):
 
 def kvp_store_bytes_used(store):
     return int(load().kvp_store_bytes_used(store.handle))
+
+
+def kvp_store_arena_on_host(store):
+    return int(load().kvp_store_arena_on_host(store.handle))
 
 
 def kvp_packet_bytes(store, n_tokens):

@@ -107,6 +107,8 @@ struct kvp_store {
     std::unordered_map<int64_t, PacketRec> dir;
     uint64_t used_bytes = 0;
     float2 *cs_dev = nullptr;
+    void *arena_dev = nullptr;  // the arena as the kernels address it
+    bool arena_host = false;    // the arena is pinned host memory mapped into the device (read over PCIe)
     PlanRing ring;          // plans of kvp_assemble
     PlanRing ring_prefill;  // plans of kvp_query_prefill
     // The prefill plan depends only on the request geometry (context lengths, query
@@ -334,6 +336,21 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
             hipDeviceProp_t prop;
             if (hipGetDeviceProperties(&prop, cfg->device) == hipSuccess && prop.multiProcessorCount > 0)
                 s->n_cu = prop.multiProcessorCount;
+            // The arena is device memory, or pinned host memory that the device can address
+            // (the paper's own tier, Sec. 5.1: packets wait in CPU memory).
+            s->arena_dev = cfg->arena;
+            if (cfg->arena) {
+                hipPointerAttribute_t attr;
+                hipError_t pe = hipPointerGetAttributes(&attr, cfg->arena);
+                if (pe == hipSuccess && attr.type == hipMemoryTypeHost && attr.devicePointer) {
+                    s->arena_host = true;
+                    s->arena_dev = attr.devicePointer;
+                } else if (pe != hipSuccess || attr.type != hipMemoryTypeDevice) {
+                    (void)hipGetLastError();
+                    delete s;
+                    return fail(nullptr, KVP_E_INVAL, "arena must be device memory or pinned (device-mapped) host memory");
+                }
+            }
             std::vector<float2> cs;
             build_cos_sin(s->inv_freq, cfg->max_positions, cs);
             e = hipMalloc((void **)&s->cs_dev, cs.size() * sizeof(float2));
@@ -386,7 +403,7 @@ int kvp_store_put(kvp_store_t *s, int64_t packet_id, int32_t n_tokens, const voi
     if (!s->dry) {
         HIP_TRY(s, hipSetDevice(g.device));
         char *dst = (char *)g.arena + s->used_bytes;
-        hipMemcpyKind kind = src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+        hipMemcpyKind kind = s->arena_host ? hipMemcpyDefault : src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
         hipStream_t st = (hipStream_t)hip_stream;
         const uint64_t slice_bytes = (uint64_t)n_tokens * row_bytes;
         HIP_TRY(s, hipMemcpy2DAsync(dst, stride * row_bytes, k, slice_bytes, slice_bytes, n_slices, kind, st));
@@ -406,6 +423,8 @@ int32_t kvp_store_packet_len(const kvp_store_t *s, int64_t packet_id)
 }
 
 uint64_t kvp_store_bytes_used(const kvp_store_t *s) { return s ? s->used_bytes : 0; }
+
+int32_t kvp_store_arena_on_host(const kvp_store_t *s) { return s ? (s->arena_host ? 1 : 0) : KVP_E_INVAL; }
 
 // -------------------------------------------------------------------------------------
 int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32_t layer_begin,
@@ -493,7 +512,7 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
     if (!s->dry && !tiles.empty() && n_layers_launch > 0) {
         hipStream_t st = (hipStream_t)hip_stream;
         AsmArgs a;
-        a.arena = g.arena;
+        a.arena = s->arena_dev;
         a.cs = s->cs_dev;
         a.tiles = nullptr;
         a.n_inline = 0;
@@ -1071,7 +1090,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     at.cs = s->cs_dev;
     at.prerotated = (flags & KVP_PREROTATED) ? 1 : 0;
     at.tiles = pk.tiles_dev;
-    at.arena = g.arena;
+    at.arena = s->arena_dev;
     at.k_tail = k_tail;
     at.n_layers_total = g.n_layers;
     at.reqs = pk.reqs_dev;

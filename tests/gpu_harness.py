@@ -19,15 +19,15 @@ def needed_packets(w):
     return sorted({p for rq in w.requests for p in rq.packet_ids})
 
 
-def build_store(w, kvp, device="cuda:0", packets=None, max_positions=None, extra_bytes=0):
+def build_store(w, kvp, device="cuda:0", packets=None, max_positions=None, extra_bytes=0, arena="device"):
     packets = needed_packets(w) if packets is None else packets
-    arena = sum(kvp.packet_bytes(w.n_layers, w.n_kv_heads, w.head_dim, w.dtype, int(w.packet_lens[p]))
-                for p in packets) + extra_bytes
+    arena_bytes = sum(kvp.packet_bytes(w.n_layers, w.n_kv_heads, w.head_dim, w.dtype, int(w.packet_lens[p]))
+                      for p in packets) + extra_bytes
     if max_positions is None:
         max_positions = max([w.ctx_len(r) + w.requests[r].n_q for r in range(len(w.requests))] + [1]) + 64
     store = kvp.kvp_store_create(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype,
-                                 w.rope_base, max_positions, max(arena, 256), w.n_header,
-                                 w.n_trailer, device=0)
+                                 w.rope_base, max_positions, max(arena_bytes, 256), w.n_header,
+                                 w.n_trailer, device=0, arena=arena)
     for p in packets:
         k, v = w.packet_kv(p, device=device)
         kvp.kvp_store_put(store, p, k, v)

@@ -302,10 +302,10 @@ def test_decode_steps_after_prefill(gpu_device, mk):
         n_q = 1
 
 
-def _run_packets(w, layers, flags=0, prerotate_with=None):
+def _run_packets(w, layers, flags=0, prerotate_with=None, arena="device"):
     """kvp_prefill_packets over the workload: returns (out[r][layer], k_tail[r][layer])."""
     import paper_2604_13226_amd as kvp
-    store = build_store(w, kvp)
+    store = build_store(w, kvp, arena=arena)
     n_req = len(w.requests)
     q_off = np.zeros(n_req + 1, np.int32)
     for r in range(n_req):
@@ -426,6 +426,23 @@ def test_full_size_serving_mix_sampled(gpu_device):
     sample = sorted({int(np.argmax(ctx)), int(np.argmin(ctx)), 7, 41})
     got = run_workload(w)
     _compare_sampled(w, got, oracle_workload(w, requests=sample), sample, [0])
+
+
+def test_host_pinned_arena(gpu_device):
+    """The packets wait in pinned host memory (the paper's tier, Sec. 5.1) and are read over
+    PCIe in place: assembly stays bit-exact, both attention paths match the oracle."""
+    import paper_2604_13226_amd as kvp
+    w = W.llama_k5(n_layers=2, n_packets=8)
+    ref = oracle_workload(w)
+    store = build_store(w, kvp, arena="host")
+    assert kvp.kvp_store_arena_on_host(store) == 1
+    assert store.arena.is_pinned() and not store.arena.is_cuda
+    got = run_workload(w, store=store)
+    compare(w, got, ref)
+    outs, tails = _run_packets(w, [0, 1], arena="host")
+    _check_packets(w, [0, 1], outs, tails, ref)
+    dev_store = build_store(w, kvp)
+    assert kvp.kvp_store_arena_on_host(dev_store) == 0
 
 
 def test_zz_report_worst_relative_rms(gpu_device):
