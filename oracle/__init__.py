@@ -55,6 +55,11 @@ def lib():
         L.kvo_query_rope_append.restype = None
         L.kvo_attention.argtypes = [i32, i32, i32, i32, i32, i64, vp, vp, vp, i64, vp]
         L.kvo_attention.restype = None
+        L.kvo_assemble_layer_spans.argtypes = [i32, i32, i32, vp, i32, vp, vp, vp, vp, i64, i64, vp, vp, vp]
+        L.kvo_assemble_layer_spans.restype = i64
+        L.kvo_query_rope_append_at.argtypes = [i32, i32, i32, i32, vp, i32, i64, i64, vp, vp, vp,
+                                               i32, vp, vp, i64, vp]
+        L.kvo_query_rope_append_at.restype = None
         L.kvo_num_threads.argtypes = []
         L.kvo_num_threads.restype = i32
         _lib = L
@@ -159,6 +164,56 @@ def query_rope_append(dtype, q, k_new, v_new, inv_f, ctx_len, k_layer, v_layer, 
                                 _p(q), _p(k_new), _p(v_new), int(bool(prerotated)),
                                 _p(k_layer), _p(v_layer), int(t_cap), _p(q_rot))
     return q_rot
+
+
+def assemble_layer_spans(dtype, packets_k, packets_v, spans, inv_f, base_pos=0, t_cap=None):
+    """One layer of a cache composed of compressed packets (Sec. 5.4).
+
+    packets_k/v: lists of arrays [n_kv][rows_j][d] (the rows packet j kept in this layer);
+    spans[j]: positions packet j occupies.  Returns (k_layer, v_layer, n_rows, pos_end),
+    layers [n_kv][t_cap][d]."""
+    inv_f = _chk(inv_f, "f32")
+    k = len(packets_k)
+    assert k >= 1 and len(spans) == k
+    d = 2 * inv_f.shape[0]
+    rows = np.array([p.shape[1] for p in packets_k], np.int32)
+    spans = np.ascontiguousarray(spans, np.int32)
+    n_kv = packets_k[0].shape[0]
+    if t_cap is None:
+        t_cap = int(rows.sum())
+    pk = [_chk(p, dtype, (n_kv, int(r), d)) for p, r in zip(packets_k, rows)]
+    pv = [_chk(p, dtype, (n_kv, int(r), d)) for p, r in zip(packets_v, rows)]
+    k_out = np.zeros((n_kv, t_cap, d), _NP[dtype])
+    v_out = np.zeros((n_kv, t_cap, d), _NP[dtype])
+    arr_t = ctypes.c_void_p * k
+    ak, av = arr_t(*[p.ctypes.data for p in pk]), arr_t(*[p.ctypes.data for p in pv])
+    pos_end = np.zeros(1, np.int64)
+    r = lib().kvo_assemble_layer_spans(_DT[dtype], n_kv, d, _p(inv_f), k, ctypes.cast(ak, ctypes.c_void_p),
+                                       ctypes.cast(av, ctypes.c_void_p), _p(rows), _p(spans), int(base_pos),
+                                       int(t_cap), _p(k_out), _p(v_out), _p(pos_end))
+    if r < 0:
+        raise ValueError("rows do not fit t_cap")
+    return k_out, v_out, int(r), int(pos_end[0])
+
+
+def query_prefill_at(dtype, q, k_new, v_new, inv_f, row0, pos0, k_layer, v_layer, prerotated=False):
+    """One layer of the query side when rows and positions differ: the query tokens sit at
+    positions pos0 + t, their K/V go to cache rows row0 + t; then attention over rows
+    0 .. row0 + t."""
+    inv_f = _chk(inv_f, "f32")
+    q = _chk(q, dtype)
+    n_q, n_q_heads, d = q.shape
+    n_kv, t_cap, _ = k_layer.shape
+    k_new = _chk(k_new, dtype, (n_q, n_kv, d))
+    v_new = _chk(v_new, dtype, (n_q, n_kv, d))
+    assert k_layer.flags.c_contiguous and v_layer.flags.c_contiguous
+    assert k_layer.dtype == _NP[dtype] and v_layer.dtype == _NP[dtype]
+    assert row0 + n_q <= t_cap
+    q_rot = np.empty((n_q, n_q_heads, d), np.float32)
+    lib().kvo_query_rope_append_at(_DT[dtype], n_q_heads, n_kv, d, _p(inv_f), n_q, int(row0), int(pos0),
+                                   _p(q), _p(k_new), _p(v_new), int(bool(prerotated)),
+                                   _p(k_layer), _p(v_layer), int(t_cap), _p(q_rot))
+    return attention(dtype, q_rot, k_layer, v_layer, row0)
 
 
 def attention(dtype, q_rot, k_layer, v_layer, ctx_len):

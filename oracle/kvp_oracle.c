@@ -208,6 +208,94 @@ void kvo_query_rope_append(int dtype, int n_q_heads, int n_kv, int d,
 }
 
 /*
+ * Compressed packets (Sec. 5.4: pruning keeps a different subset of a packet's rows in every
+ * layer, and the packet stays an opaque unit).  One layer of the composed cache: packet j kept
+ * rows[j] of its rows in this layer and still occupies spans[j] positions, so its keys are
+ * rotated by Delta_j = base_pos + sum of the spans before it (Eq. 1 needs no position of the
+ * single row: a kept key carries the rotation of the local position it was cached at), while
+ * its rows land right behind the kept rows of the packets before it.
+ *   pk_k[j], pk_v[j] : [n_kv][rows[j]][d] dtype      k_out, v_out : [n_kv][t_cap][d] dtype
+ * Returns the number of rows written (or -1 if they exceed t_cap); *pos_end = base_pos + sum of
+ * the spans, the position of the first token after the packets.
+ */
+int64_t kvo_assemble_layer_spans(int dtype, int n_kv, int d, const float *inv_freq, int k,
+                                 const void *const *pk_k, const void *const *pk_v,
+                                 const int32_t *rows, const int32_t *spans, int64_t base_pos,
+                                 int64_t t_cap, void *k_out, void *v_out, int64_t *pos_end)
+{
+    int64_t total = 0;
+    for (int j = 0; j < k; ++j)
+        total += rows[j];
+    if (total > t_cap || base_pos < 0)
+        return -1;
+    size_t es = elem_size(dtype);
+    float c[512], s[512], x[1024], y[1024];
+    int64_t row0 = 0;         /* destination row of packet j's first kept row */
+    int64_t delta = base_pos; /* Delta_j */
+    for (int j = 0; j < k; ++j) {
+        kvo_cos_sin(delta, inv_freq, d, c, s);
+        for (int h = 0; h < n_kv; ++h) {
+            size_t src0 = (size_t)h * (size_t)rows[j] * d;
+            size_t dst0 = ((size_t)h * (size_t)t_cap + (size_t)row0) * d;
+            for (int t = 0; t < rows[j]; ++t) {
+                for (int e = 0; e < d; ++e)
+                    x[e] = load_elem(pk_k[j], dtype, src0 + (size_t)t * d + e);
+                kvo_rotate(x, d, c, s, y);
+                for (int e = 0; e < d; ++e)
+                    store_elem(k_out, dtype, dst0 + (size_t)t * d + e, y[e]);
+            }
+            memcpy((char *)v_out + dst0 * es, (const char *)pk_v[j] + src0 * es,
+                   (size_t)rows[j] * d * es);
+        }
+        row0 += rows[j];
+        delta += spans[j];
+    }
+    *pos_end = delta;
+    return total;
+}
+
+/*
+ * Query side of one layer when rows and positions differ (compressed packets): query token t
+ * sits at position pos0 + t and its K_new / V_new are appended at cache row row0 + t.
+ * Arguments otherwise as kvo_query_rope_append.
+ */
+void kvo_query_rope_append_at(int dtype, int n_q_heads, int n_kv, int d,
+                              const float *inv_freq, int n_q, int64_t row0, int64_t pos0,
+                              const void *q, const void *k_new, const void *v_new,
+                              int prerotated, void *k_layer, void *v_layer,
+                              int64_t t_cap, float *q_rot)
+{
+    size_t es = elem_size(dtype);
+    float c[512], s[512], x[1024], y[1024];
+    for (int t = 0; t < n_q; ++t) {
+        kvo_cos_sin(pos0 + t, inv_freq, d, c, s);
+        for (int hq = 0; hq < n_q_heads; ++hq) {
+            size_t o = ((size_t)t * n_q_heads + hq) * d;
+            for (int e = 0; e < d; ++e)
+                x[e] = load_elem(q, dtype, o + e);
+            if (prerotated)
+                memcpy(y, x, sizeof(float) * (size_t)d);
+            else
+                kvo_rotate(x, d, c, s, y);
+            memcpy(q_rot + o, y, sizeof(float) * (size_t)d);
+        }
+        for (int h = 0; h < n_kv; ++h) {
+            size_t o = ((size_t)t * n_kv + h) * d;
+            size_t dst = ((size_t)h * (size_t)t_cap + (size_t)(row0 + t)) * d;
+            for (int e = 0; e < d; ++e)
+                x[e] = load_elem(k_new, dtype, o + e);
+            if (prerotated)
+                memcpy(y, x, sizeof(float) * (size_t)d);
+            else
+                kvo_rotate(x, d, c, s, y);
+            for (int e = 0; e < d; ++e)
+                store_elem(k_layer, dtype, dst + e, y[e]);
+            memcpy((char *)v_layer + dst * es, (const char *)v_new + o * es, (size_t)d * es);
+        }
+    }
+}
+
+/*
  * Softmax attention of the n_q query tokens over one layer's cache, by the
  * definition: query token t (at row ctx_len + t) sees rows 0 .. ctx_len + t.
  *   q_rot : [n_q][n_q_heads][d] fp32       out : [n_q][n_q_heads][d] fp64

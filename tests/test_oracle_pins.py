@@ -462,3 +462,94 @@ def test_realignment_flop_fraction_matches_the_papers_printed_range():
     full = 2 * params                                     # forward flop per token, attention excluded
     frac = realign / full
     assert lo * 0.9 <= frac <= hi
+
+
+# --------------------------------------------------------------------------
+# Compressed packets (Sec. 5.4): per layer a packet keeps a subset of its rows
+# --------------------------------------------------------------------------
+def _pruned_case(dtype, seed=21, d=8, n_kv=2, lens=(9, 1, 14), keep_prob=0.6):
+    """Packets of one layer + the rows each keeps (sorted, possibly none)."""
+    rng = np.random.default_rng(seed)
+    w = W.random_small(seed, dtype=dtype, d=d, n_q_heads=2 * n_kv, n_kv_heads=n_kv, n_layers=1,
+                       n_packets=len(lens), k=len(lens), n_q=4)
+    f = oracle.inv_freq(w.rope_base, d)
+    ks, vs, keeps = [], [], []
+    for j, L in enumerate(lens):
+        k = W.normal_tensor((1, n_kv, L, d), seed, 1, j, 1.0, w.torch_dtype)
+        v = W.normal_tensor((1, n_kv, L, d), seed, 2, j, 1.0, w.torch_dtype)
+        ks.append(_np(k)), vs.append(_np(v))
+        keep = np.flatnonzero(rng.random(L) < keep_prob)
+        keeps.append(keep)
+    keeps[1] = np.array([0])            # a one-row packet keeps its row
+    return w, f, ks, vs, keeps
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("base_pos", [0, 5])
+def test_pruning_commutes_with_realignment(dtype, base_pos):
+    """Realigning the kept rows of compressed packets (spans = the uncompressed lengths) gives,
+    bit for bit, the rows a full assembly puts at those places: Eq. 1 rotates every key of a
+    packet by the same Delta_j whatever its own position.  The full assembly is the function the
+    pins above fix; the selection is plain indexing."""
+    w, f, ks, vs, keeps = _pruned_case(dtype)
+    lens = [k.shape[2] for k in ks]
+    K, V, ctx = oracle.assemble(dtype, ks, vs, f, base_pos)
+    pk = [np.ascontiguousarray(k[0][:, keep]) for k, keep in zip(ks, keeps)]
+    pv = [np.ascontiguousarray(v[0][:, keep]) for v, keep in zip(vs, keeps)]
+    Kc, Vc, rows, pos_end = oracle.assemble_layer_spans(dtype, pk, pv, lens, f, base_pos)
+    assert rows == sum(len(k) for k in keeps) and pos_end == ctx == base_pos + sum(lens)
+    sel = np.concatenate([base_pos + sum(lens[:j]) + keep for j, keep in enumerate(keeps)])
+    assert np.array_equal(Kc, K[0][:, sel]) and np.array_equal(Vc, V[0][:, sel])
+
+
+def test_uncompressed_spans_reduce_to_plain_assembly():
+    w, f, ks, vs, _ = _pruned_case("bf16")
+    lens = [k.shape[2] for k in ks]
+    K, V, ctx = oracle.assemble("bf16", ks, vs, f, 3, t_cap=3 + sum(lens))
+    Kc, Vc, rows, pos_end = oracle.assemble_layer_spans("bf16", [k[0] for k in ks], [v[0] for v in vs], lens, f, 3)
+    assert rows == sum(lens) and pos_end == ctx
+    assert np.array_equal(Kc, K[0][:, 3:]) and np.array_equal(Vc, V[0][:, 3:])
+
+
+def test_pruned_attention_against_brute_force_with_explicit_positions():
+    """Float64 brute force from the un-rotated keys: kept row s of packet j sits at position
+    Delta_j + s with Delta_j counted in uncompressed lengths, the query at the sum of the
+    lengths + t; an explicit score matrix over the kept rows and the query rows."""
+    dtype = "f32"
+    w, f, ks_raw, vs, keeps = _pruned_case(dtype, seed=33, lens=(6, 11, 1, 8))
+    lens = [k.shape[2] for k in ks_raw]
+    d, n_kv = w.head_dim, w.n_kv_heads
+    # what a packet stores: its keys rotated at their local positions 0 .. len-1
+    stored = []
+    for k in ks_raw:
+        st = np.stack([[oracle.rotate(k[0][h, s], s, f) for s in range(k.shape[2])] for h in range(n_kv)])
+        stored.append(st.astype(np.float32))
+    pk = [np.ascontiguousarray(st[:, keep]) for st, keep in zip(stored, keeps)]
+    pv = [np.ascontiguousarray(v[0][:, keep]) for v, keep in zip(vs, keeps)]
+    base_pos = 2
+    n_q = w.requests[0].n_q
+    rows_total = sum(len(k) for k in keeps)
+    Kc, Vc, rows, pos_end = oracle.assemble_layer_spans(dtype, pk, pv, lens, f, base_pos, t_cap=rows_total + n_q)
+    q, kn, vn = (_np(x) for x in w.query(0, 0))
+    out = oracle.query_prefill_at(dtype, q, kn, vn, f, rows, pos_end, Kc, Vc)
+    # brute force
+    Kb = np.zeros((n_kv, rows_total + n_q, d)); Vb = np.zeros_like(Kb)
+    at = 0
+    for j, keep in enumerate(keeps):
+        delta = base_pos + sum(lens[:j])
+        for s in keep:
+            R = bf.rot_matrix(delta + int(s), f)
+            Kb[:, at] = np.einsum("ef,hf->he", R, ks_raw[j][0][:, s].astype(np.float64))
+            Vb[:, at] = vs[j][0][:, s]
+            at += 1
+    pos_q = base_pos + sum(lens)
+    assert at == rows and pos_end == pos_q
+    q_rot = np.stack([np.einsum("ef,hf->he", bf.rot_matrix(pos_q + t, f), q[t].astype(np.float64)) for t in range(n_q)])
+    for t in range(n_q):
+        Kb[:, at + t] = np.einsum("ef,hf->he", bf.rot_matrix(pos_q + t, f), kn[t].astype(np.float64))
+        Vb[:, at + t] = vn[t]
+    ref = bf.attention(q_rot, Kb, Vb, rows)
+    assert np.max(np.abs(out - ref)) < 3e-5
+    # the appended rows sit behind the kept rows, at the query's positions
+    assert np.max(np.abs(Kc[:, rows:rows + n_q].astype(np.float64) - Kb[:, rows:])) < 3e-5
+    assert np.array_equal(Vc[:, rows:rows + n_q].astype(np.float64), Vb[:, rows:])
