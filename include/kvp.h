@@ -110,8 +110,29 @@ int kvp_store_destroy(kvp_store_t *store);
 int kvp_store_put(kvp_store_t *store, int64_t packet_id, int32_t n_tokens, const void *k,
                   const void *v, int32_t src_on_device, void *hip_stream);
 
-/* Rows of a stored packet, or KVP_E_NOTFOUND. */
+/*
+ * Sec. 5.4 (compatibility with KV compression): a packet whose rows were pruned, with a
+ * different subset kept in every layer, stays an opaque unit that is realigned and
+ * concatenated like any other.  n_rows[l] (HOST, [n_layers], each in [0, span]) rows survive in
+ * layer l; the packet still occupies `span` positions (its uncompressed length), so the
+ * packets after it and the query keep the positions they would have without compression, and
+ * Eq. 1 rotates every kept key by the packet's Delta_j (a kept key carries the rotation of the
+ * local position it was cached at; no per-row position is needed).  In the composed cache the
+ * kept rows of a layer follow each other without gaps, so layers have different row counts
+ * (kvp_cache_t.ctx_rows).
+ * k, v: layer after layer, layer l as [n_kv_heads][n_rows[l]][head_dim].
+ * Other arguments, copies and errors as kvp_store_put.  kvp_prefill_packets does not take
+ * compressed packets (KVP_E_INVAL).
+ */
+int kvp_store_put_compressed(kvp_store_t *store, int64_t packet_id, int32_t span, const int32_t *n_rows,
+                             const void *k, const void *v, int32_t src_on_device, void *hip_stream);
+
+/* Rows of a stored packet (for a compressed packet: the positions it occupies), or
+ * KVP_E_NOTFOUND. */
 int32_t kvp_store_packet_len(const kvp_store_t *store, int64_t packet_id);
+/* Rows a stored packet holds in one layer (its length, unless compressed), or KVP_E_NOTFOUND /
+ * KVP_E_INVAL. */
+int32_t kvp_store_packet_rows(const kvp_store_t *store, int64_t packet_id, int32_t layer);
 /* Bytes of the arena in use. */
 uint64_t kvp_store_bytes_used(const kvp_store_t *store);
 /* 1 if the arena is pinned host memory (packets are read over PCIe), 0 if device memory. */
@@ -140,6 +161,12 @@ typedef struct {
     int32_t *ctx_len; /* HOST [n_req].  Written by kvp_assemble (base_pos + T); read by
                          kvp_query_prefill, which does not change it: after the last
                          layer the caller adds n_q. */
+    int32_t *ctx_rows; /* HOST [n_req][n_layers], or NULL.  Rows of the composed cache per layer.
+                          They differ from ctx_len (a position) only when a request names a
+                          compressed packet (kvp_store_put_compressed); such requests need this
+                          array.  Written by kvp_assemble for the layers it assembles, read by
+                          kvp_query_prefill; after the last layer the caller adds n_q to every
+                          entry as well. */
 } kvp_cache_t;
 
 /*

@@ -37,14 +37,16 @@ class kvp_request_t(ctypes.Structure):
 class kvp_cache_t(ctypes.Structure):
     _fields_ = [("layout", _i32), ("k", _vp), ("v", _vp), ("t_cap", _i32), ("n_blocks", _i32),
                 ("block_size", _i32), ("block_table", _vp), ("max_blocks_per_req", _i32),
-                ("ctx_len", _vp)]
+                ("ctx_len", _vp), ("ctx_rows", _vp)]
 
 
 EXPORTS = {
     "kvp_store_create": (_i32, [ctypes.POINTER(kvp_config_t), ctypes.POINTER(_vp)]),
     "kvp_store_destroy": (_i32, [_vp]),
     "kvp_store_put": (_i32, [_vp, _i64, _i32, _vp, _vp, _i32, _vp]),
+    "kvp_store_put_compressed": (_i32, [_vp, _i64, _i32, _vp, _vp, _vp, _i32, _vp]),
     "kvp_store_packet_len": (_i32, [_vp, _i64]),
+    "kvp_store_packet_rows": (_i32, [_vp, _i64, _i32]),
     "kvp_store_bytes_used": (_u64, [_vp]),
     "kvp_store_arena_on_host": (_i32, [_vp]),
     "kvp_packet_bytes": (_u64, [ctypes.POINTER(kvp_config_t), _i32]),
@@ -175,8 +177,35 @@ def kvp_store_put(store, packet_id, k, v, stream=None, n_tokens=None):
     _check(store.handle, rc)
 
 
+def kvp_store_put_compressed(store, packet_id, span, k_layers, v_layers, stream=None, n_rows=None):
+    """A compressed packet: k_layers[l], v_layers[l] are torch tensors [n_kv_heads][rows_l][head_dim]
+    (the rows layer l kept), all on the GPU or all on the CPU; span = the positions it occupies."""
+    c = store.cfg
+    if store.dry:
+        rows = np.ascontiguousarray(n_rows, np.int32)
+        rc = load().kvp_store_put_compressed(store.handle, int(packet_id), int(span), rows.ctypes.data,
+                                             None, None, 0, None)
+        return _check(store.handle, rc)
+    assert len(k_layers) == c.n_layers == len(v_layers)
+    rows = np.array([int(k.shape[1]) for k in k_layers], np.int32)
+    for k, v in zip(k_layers, v_layers):
+        assert k.shape == v.shape and k.shape[0] == c.n_kv_heads and k.shape[2] == c.head_dim
+        assert k.dtype == store.torch_dtype and v.dtype == store.torch_dtype
+    kk = torch.cat([k.reshape(-1) for k in k_layers]).contiguous()
+    vv = torch.cat([v.reshape(-1) for v in v_layers]).contiguous()
+    rc = load().kvp_store_put_compressed(store.handle, int(packet_id), int(span), rows.ctypes.data,
+                                         kk.data_ptr(), vv.data_ptr(), 1 if kk.is_cuda else 0, _stream(stream))
+    if kk.is_cuda:
+        torch.cuda.synchronize()  # kk, vv are temporaries
+    _check(store.handle, rc)
+
+
 def kvp_store_packet_len(store, packet_id):
     return int(load().kvp_store_packet_len(store.handle, int(packet_id)))
+
+
+def kvp_store_packet_rows(store, packet_id, layer):
+    return int(load().kvp_store_packet_rows(store.handle, int(packet_id), int(layer)))
 
 
 def kvp_store_bytes_used(store):
@@ -224,7 +253,14 @@ class Cache:
             c.block_table = self.block_table.ctypes.data
             c.max_blocks_per_req = int(self.block_table.shape[1])
         c.ctx_len = self.ctx_len.ctypes.data
+        self.ctx_rows = None
         self.c = c
+
+    def with_ctx_rows(self, n_layers):
+        """Adds the per-layer row counts (kvp_cache_t.ctx_rows) that compressed packets need."""
+        self.ctx_rows = np.zeros((max(self.n_req, 1), n_layers), np.int32)
+        self.c.ctx_rows = self.ctx_rows.ctypes.data
+        return self
 
     @staticmethod
     def contiguous(store, n_req, t_cap, device="cuda:0"):

@@ -105,8 +105,11 @@ __global__ __launch_bounds__(ASM_THREADS) void assemble_vec_kernel(AsmArgs a)
     const int tid = threadIdx.x;
 
     const T *arena = (const T *)a.arena;
-    const int64_t blob = (int64_t)a.n_layers_total * a.n_kv * tile.stride * D;
-    const T *ksrc = arena + tile.src_base + (((int64_t)layer * a.n_kv + head) * tile.stride + tile.tok0) * D;
+    // stride < 0: a compressed packet, src_base is this layer's own [K: Hkv x rows][V: Hkv x rows]
+    const bool per_layer = tile.stride < 0;
+    const int stride = per_layer ? -tile.stride : tile.stride;
+    const int64_t blob = (int64_t)(per_layer ? 1 : a.n_layers_total) * a.n_kv * stride * D;
+    const T *ksrc = arena + tile.src_base + (((int64_t)(per_layer ? 0 : layer) * a.n_kv + head) * stride + tile.tok0) * D;
     const T *vsrc = ksrc + blob;
     T *kdst = (T *)a.cache.k;
     T *vdst = (T *)a.cache.v;
@@ -175,8 +178,10 @@ __global__ __launch_bounds__(ASM_THREADS) void assemble_scalar_kernel(AsmArgs a)
     const int head = lh % a.n_kv;
     const int d = a.d, half = d / 2;
     const T *arena = (const T *)a.arena;
-    const int64_t blob = (int64_t)a.n_layers_total * a.n_kv * tile.stride * d;
-    const T *ksrc = arena + tile.src_base + (((int64_t)layer * a.n_kv + head) * tile.stride + tile.tok0) * d;
+    const bool per_layer = tile.stride < 0;  // compressed packet: see the vector kernel
+    const int stride = per_layer ? -tile.stride : tile.stride;
+    const int64_t blob = (int64_t)(per_layer ? 1 : a.n_layers_total) * a.n_kv * stride * d;
+    const T *ksrc = arena + tile.src_base + (((int64_t)(per_layer ? 0 : layer) * a.n_kv + head) * stride + tile.tok0) * d;
     const T *vsrc = ksrc + blob;
     T *kdst = (T *)a.cache.k;
     T *vdst = (T *)a.cache.v;

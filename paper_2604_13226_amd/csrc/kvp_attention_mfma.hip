@@ -314,7 +314,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
             const int n_chunks = SRC == SRC_PACKETS ? 8 : 24;  // 8 K chunk pairs (+ 16 V chunks)
             for (int idx = tid; idx < n_tail * n_chunks; idx += NT) {
                 const int qr = tail_lo + idx / n_chunks, cidx = idx % n_chunks;
-                const int row = it.ctx_len + qr;  // position of the row
+                const int row = it.ctx_len + qr;  // cache row of the query token
+                const int pos = it.pos0 + qr;     // its position
                 const int64_t src = ((int64_t)(it.q_off + qr) * a.n_kv + it.kv_head) * D;
                 int64_t dst;
                 if (SRC == SRC_PACKETS) {
@@ -333,7 +334,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
                     const int e = 8 * cidx;
                     const uint4 ulo = *(const uint4 *)((const bf16_t *)a.k_new + src + e);
                     const uint4 uhi = *(const uint4 *)((const bf16_t *)a.k_new + src + 64 + e);
-                    const float4 *csr = (const float4 *)(a.cs + (int64_t)row * 64 + e);
+                    const float4 *csr = (const float4 *)(a.cs + (int64_t)pos * 64 + e);
                     float4 cs4[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) cs4[j] = a.prerotated ? make_float4(1.f, 0.f, 1.f, 0.f) : csr[j];
@@ -367,7 +368,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
     // pairs with the same slot of ks + 4, so the rotation stays inside the lane.
     bf16x8 qf[8];
     const bf16_t *qp = (const bf16_t *)a.q + ((int64_t)(it.q_off + t) * a.n_q_heads + hq) * D + 8 * h;
-    const int q_pos = a.prerotated ? 0 : it.ctx_len + t;  // rotation the query still needs
+    const int q_pos = a.prerotated ? 0 : it.pos0 + t;  // rotation the query still needs
     auto load_q = [&](int delta) {
         uint4 qraw[8];
 #pragma unroll

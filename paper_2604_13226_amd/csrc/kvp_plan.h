@@ -9,7 +9,8 @@ namespace kvp {
 // The same tile list serves every (layer, kv head): blockIdx.y selects those.
 struct AsmTile {
     int64_t src_base;  // element offset of the packet's K blob in the arena
-    int32_t stride;    // rows between consecutive (layer, head) slices of the blob
+    int32_t stride;    // rows between consecutive (layer, head) slices of the blob; negative: a compressed
+                       // packet, src_base is one layer's own part and -stride its rows in that layer
     int32_t tok0;      // first packet row of this tile
     int32_t n_tok;     // rows in this tile
     int32_t dst_row;   // cache row (absolute position) of tok0
@@ -33,7 +34,8 @@ struct CacheView {
 struct AsmPacket {
     int64_t src_base;  // element offset of the packet's K blob in the arena
     int32_t n_pkt;     // rows of the packet
-    int32_t stride;    // rows between consecutive (layer, head) slices of the blob
+    int32_t stride;    // rows between consecutive (layer, head) slices of the blob; negative: a compressed
+                       // packet, src_base is one layer's own part and -stride its rows in that layer
     int32_t pos;       // Delta_j = cache row of the packet's first row
     int32_t req;
     int32_t tile0;     // index of the packet's first tile
@@ -54,10 +56,10 @@ struct AsmArgs {
 
 // ---- query prefill -------------------------------------------------------------
 struct ReqMeta {
-    int32_t ctx_len;  // rows already in the cache = position of query row 0
+    int32_t ctx_len;  // rows already in this layer of the cache
     int32_t q_off;    // first query row in q / out
     int32_t n_q;
-    int32_t pad;
+    int32_t pos0;     // position of query row 0 (= ctx_len unless compressed packets are in the context)
 };
 
 // Packed row m of a (request, kv head) pair: query token t = m / g, query head
@@ -75,7 +77,8 @@ struct AttnItem {
     int32_t ctx_len, q_off;                  // copy of the request
     int32_t part_slot;                       // partial slot to write, or -1: write `out` directly
     int32_t n_q;                             // query rows of the request
-    int32_t pad[4];
+    int32_t pos0;                            // position of query row 0 (rows and positions differ with compressed packets)
+    int32_t pad[3];
 };
 static_assert(sizeof(AttnItem) == 64, "AttnItem is 64 bytes");
 

@@ -24,7 +24,9 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a)
         int row = (int)(rh / heads);
         int req = a.row_req[row];
         ReqMeta m = a.reqs[req];
-        int pos = m.ctx_len + (row - m.q_off);
+        const int row_in_req = row - m.q_off;
+        int pos = m.pos0 + row_in_req;            // the token's position
+        const int cache_row = m.ctx_len + row_in_req;  // the cache row its K / V go to
         float c = 1.f, s = 0.f;
         if (!a.prerotated) {
             float2 t = a.cs[(int64_t)pos * half + i];
@@ -44,7 +46,7 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a)
             int64_t o = ((int64_t)row * a.n_kv + h) * a.d;
             const T *ks = (const T *)a.k_new + o;
             const T *vs = (const T *)a.v_new + o;
-            int64_t co = cache_row_off(a.cache, req, a.layer, h, pos, a.n_kv, a.d);
+            int64_t co = cache_row_off(a.cache, req, a.layer, h, cache_row, a.n_kv, a.d);
             T *kd = (T *)a.cache.k + co;
             T *vd = (T *)a.cache.v + co;
             float x = ld_elem(ks + i), y = ld_elem(ks + half + i);

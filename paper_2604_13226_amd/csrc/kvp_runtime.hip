@@ -26,8 +26,13 @@ inline uint64_t align_up(uint64_t x, uint64_t a = ALIGN) { return (x + a - 1) / 
 
 struct PacketRec {
     int64_t elem_off;  // element offset of the blob in the arena
-    int32_t n_tokens;
+    int32_t n_tokens;  // rows (positions) of the packet
     int32_t stride;    // rows between (layer, head) slices: n_tokens + slice padding
+    // compressed packets only: rows kept per layer and the element offset of each layer's
+    // part of the blob ([K: Hkv x rows][V: Hkv x rows], layer after layer)
+    std::vector<int32_t> rows;
+    std::vector<int64_t> layer_off;
+    bool compressed() const { return !rows.empty(); }
 };
 
 // Ring of pinned-host / device twin buffers that carry one call's plan each.  A slot is
@@ -273,6 +278,127 @@ struct PlanWriter {
     }
 };
 
+// kvp_assemble for requests with compressed packets (Sec. 5.4): positions advance by the
+// packets' spans, rows by what each layer kept, so every layer has its own tile list and its
+// own launch (one plan upload for all of them).
+int assemble_compressed(kvp_store *s, const kvp_request_t *reqs, int n_req, int layer_begin, int layer_end,
+                        kvp_cache_t *cache, const CacheCheck &cc, void *hip_stream)
+{
+    const kvp_config_t &g = s->cfg;
+    if (!cache->ctx_rows) return fail(s, KVP_E_INVAL, "compressed packets need kvp_cache_t.ctx_rows");
+    const int n_l = layer_end - layer_begin;
+    std::vector<std::vector<AsmTile>> tiles(std::max(n_l, 0));
+    std::vector<int> pos_end(n_req), first_blk(n_req, 0), n_blk(n_req, 0);
+    std::vector<int64_t> rows_end((size_t)n_req * std::max(n_l, 1), 0);
+    for (int r = 0; r < n_req; ++r) {
+        const kvp_request_t &q = reqs[r];
+        if (q.base_pos < 0) return fail(s, KVP_E_INVAL, "request %d: base_pos %d < 0", r, q.base_pos);
+        int64_t pos = q.base_pos, max_rows = q.base_pos;
+        std::vector<int64_t> row(std::max(n_l, 1), q.base_pos);  // the caller's rows below base_pos are not compressed
+        for (int j = 0; j < q.k; ++j) {
+            auto it = s->dir.find(q.packet_ids[j]);
+            if (it == s->dir.end()) return fail(s, KVP_E_NOTFOUND, "request %d: packet %lld not in the store", r, (long long)q.packet_ids[j]);
+            const PacketRec &p = it->second;
+            if (pos + p.n_tokens > g.max_positions)
+                return fail(s, KVP_E_CAPACITY, "request %d: context exceeds max_positions %d", r, g.max_positions);
+            for (int li = 0; li < n_l; ++li) {
+                const int l = layer_begin + li;
+                const int n = p.compressed() ? p.rows[l] : p.n_tokens;
+                for (int t0 = 0; t0 < n; t0 += s->asm_tile_rows) {
+                    AsmTile t;
+                    // a negative stride marks a blob laid out layer by layer
+                    t.src_base = p.compressed() ? p.layer_off[l] : p.elem_off;
+                    t.stride = p.compressed() ? -std::max(n, 1) : p.stride;
+                    t.tok0 = t0;
+                    t.n_tok = std::min(s->asm_tile_rows, n - t0);
+                    t.dst_row = (int32_t)row[li] + t0;
+                    t.pos = (int32_t)pos;
+                    t.req = r;
+                    tiles[li].push_back(t);
+                }
+                row[li] += n;
+            }
+            pos += p.n_tokens;
+        }
+        for (int li = 0; li < n_l; ++li) {
+            rows_end[(size_t)r * n_l + li] = row[li];
+            max_rows = std::max(max_rows, row[li]);
+        }
+        if (max_rows > cc.cap_rows) return fail(s, KVP_E_CAPACITY, "request %d: %lld rows do not fit the cache (%lld)", r, (long long)max_rows, (long long)cc.cap_rows);
+        pos_end[r] = (int)pos;
+        if (cache->layout == KVP_PAGED && max_rows > q.base_pos) {
+            first_blk[r] = q.base_pos >> cc.shift;
+            n_blk[r] = (int)((max_rows - 1) >> cc.shift) + 1;
+        }
+    }
+    int bt_stride = 0;
+    for (int r = 0; r < n_req; ++r) bt_stride = std::max(bt_stride, n_blk[r]);
+    uint64_t n_tiles_total = 0;
+    for (auto &v : tiles) n_tiles_total += v.size();
+
+    s->dbg_asm.clear();
+    s->dbg_asm.push_back((int64_t)n_tiles_total);
+    for (auto &v : tiles)
+        for (const AsmTile &t : v) {
+            int64_t rowv[8] = {t.src_base, t.stride, t.tok0, t.n_tok, t.dst_row, t.pos, t.req, 0};
+            s->dbg_asm.insert(s->dbg_asm.end(), rowv, rowv + 8);
+        }
+
+    if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
+    if (n_tiles_total > 0) {
+        const uint64_t bytes = align_up(n_tiles_total * sizeof(AsmTile), 64) + (uint64_t)n_req * bt_stride * 4 + 256;
+        PlanRing::Slot *slot = nullptr;
+        int hrc = s->ring.acquire(bytes, &slot);
+        if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
+        PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
+        const AsmTile *tiles_dev = nullptr;
+        const int32_t *bt_dev = nullptr;
+        AsmTile *th = w.put<AsmTile>(n_tiles_total, &tiles_dev);
+        uint64_t at = 0;
+        std::vector<uint64_t> first(n_l);
+        for (int li = 0; li < n_l; ++li) {
+            first[li] = at;
+            if (!tiles[li].empty()) memcpy(th + at, tiles[li].data(), tiles[li].size() * sizeof(AsmTile));
+            at += tiles[li].size();
+        }
+        if (cache->layout == KVP_PAGED && bt_stride > 0) {
+            int32_t *bh = w.put<int32_t>((uint64_t)n_req * bt_stride, &bt_dev);
+            int rc = compact_block_table(s, cache, n_req, first_blk, n_blk, bt_stride, bh);
+            if (rc) return rc;
+        }
+        if (!s->dry) {
+            hipStream_t st = (hipStream_t)hip_stream;
+            HIP_TRY(s, hipMemcpyAsync(slot->dev, slot->host, w.off, hipMemcpyHostToDevice, st));
+            for (int li = 0; li < n_l; ++li) {
+                if (tiles[li].empty()) continue;
+                AsmArgs a;
+                a.arena = s->arena_dev;
+                a.cs = s->cs_dev;
+                a.tiles = tiles_dev + first[li];
+                a.n_inline = 0;
+                a.cache = make_view(s, cache, cc.shift, bt_dev, bt_stride);
+                a.n_tiles = (int)tiles[li].size();
+                a.tile_rows = s->asm_tile_rows;
+                a.nontemporal = s->asm_nontemporal;
+                a.layer_begin = layer_begin + li;
+                a.n_layers_total = g.n_layers;
+                a.n_kv = g.n_kv_heads;
+                a.d = g.head_dim;
+                int e = launch_assemble(g.dtype, a, 1, hip_stream);
+                if (e) return hip_fail(s, (hipError_t)e, "assemble launch");
+            }
+            HIP_TRY(s, hipEventRecord(slot->ev, st));
+            slot->pending = true;
+        }
+    }
+    for (int r = 0; r < n_req; ++r) {
+        cache->ctx_len[r] = pos_end[r];
+        for (int li = 0; li < n_l; ++li)
+            cache->ctx_rows[(int64_t)r * g.n_layers + layer_begin + li] = (int32_t)rows_end[(size_t)r * n_l + li];
+    }
+    return KVP_OK;
+}
+
 }  // namespace
 
 // =====================================================================================
@@ -410,7 +536,7 @@ int kvp_store_put(kvp_store_t *s, int64_t packet_id, int32_t n_tokens, const voi
         HIP_TRY(s, hipMemcpy2DAsync(dst + half_bytes, stride * row_bytes, v, slice_bytes, slice_bytes, n_slices, kind, st));
         if (!src_on_device) HIP_TRY(s, hipStreamSynchronize(st));  // host buffers may be reused on return
     }
-    s->dir[packet_id] = PacketRec{(int64_t)(s->used_bytes / s->esize), n_tokens, stride};
+    s->dir[packet_id] = PacketRec{(int64_t)(s->used_bytes / s->esize), n_tokens, stride, {}, {}};
     s->used_bytes += need;
     return KVP_OK;
 }
@@ -420,6 +546,57 @@ int32_t kvp_store_packet_len(const kvp_store_t *s, int64_t packet_id)
     if (!s) return KVP_E_INVAL;
     auto it = s->dir.find(packet_id);
     return it == s->dir.end() ? KVP_E_NOTFOUND : it->second.n_tokens;
+}
+
+int32_t kvp_store_packet_rows(const kvp_store_t *s, int64_t packet_id, int32_t layer)
+{
+    if (!s || layer < 0 || layer >= s->cfg.n_layers) return KVP_E_INVAL;
+    auto it = s->dir.find(packet_id);
+    if (it == s->dir.end()) return KVP_E_NOTFOUND;
+    return it->second.compressed() ? it->second.rows[layer] : it->second.n_tokens;
+}
+
+int kvp_store_put_compressed(kvp_store_t *s, int64_t packet_id, int32_t span, const int32_t *n_rows,
+                             const void *k, const void *v, int32_t src_on_device, void *hip_stream)
+{
+    if (!s) return KVP_E_INVAL;
+    if (packet_id < 0) return fail(s, KVP_E_INVAL, "packet id %lld < 0", (long long)packet_id);
+    if (span < 1) return fail(s, KVP_E_INVAL, "span %d < 1", span);
+    if (!n_rows) return fail(s, KVP_E_INVAL, "n_rows is null");
+    if (s->dir.count(packet_id)) return fail(s, KVP_E_EXISTS, "packet %lld already stored", (long long)packet_id);
+    const kvp_config_t &g = s->cfg;
+    const uint64_t row_bytes = (uint64_t)g.head_dim * s->esize;
+    PacketRec rec{(int64_t)(s->used_bytes / s->esize), span, span, {}, {}};
+    uint64_t total_rows = 0;
+    for (int l = 0; l < g.n_layers; ++l) {
+        if (n_rows[l] < 0 || n_rows[l] > span) return fail(s, KVP_E_INVAL, "layer %d keeps %d rows of a span of %d", l, n_rows[l], span);
+        rec.rows.push_back(n_rows[l]);
+        rec.layer_off.push_back(rec.elem_off + (int64_t)(2 * total_rows * g.n_kv_heads * g.head_dim));
+        total_rows += (uint64_t)n_rows[l];
+    }
+    if (!s->dry && total_rows > 0 && (!k || !v)) return fail(s, KVP_E_INVAL, "k or v is null");
+    const uint64_t need = align_up(std::max<uint64_t>(2 * total_rows * g.n_kv_heads * row_bytes, 1));
+    if (s->used_bytes + need > g.arena_bytes)
+        return fail(s, KVP_E_NOSPACE, "arena full: %llu used + %llu needed > %llu", (unsigned long long)s->used_bytes,
+                    (unsigned long long)need, (unsigned long long)g.arena_bytes);
+    if (!s->dry) {
+        HIP_TRY(s, hipSetDevice(g.device));
+        hipMemcpyKind kind = s->arena_host ? hipMemcpyDefault : src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+        hipStream_t st = (hipStream_t)hip_stream;
+        uint64_t src_off = 0;
+        for (int l = 0; l < g.n_layers; ++l) {
+            const uint64_t part = (uint64_t)n_rows[l] * g.n_kv_heads * row_bytes;  // K (or V) of this layer
+            if (!part) continue;
+            char *dst = (char *)g.arena + (uint64_t)rec.layer_off[l] * s->esize;
+            HIP_TRY(s, hipMemcpyAsync(dst, (const char *)k + src_off, part, kind, st));
+            HIP_TRY(s, hipMemcpyAsync(dst + part, (const char *)v + src_off, part, kind, st));
+            src_off += part;
+        }
+        if (!src_on_device) HIP_TRY(s, hipStreamSynchronize(st));
+    }
+    s->dir[packet_id] = rec;
+    s->used_bytes += need;
+    return KVP_OK;
 }
 
 uint64_t kvp_store_bytes_used(const kvp_store_t *s) { return s ? s->used_bytes : 0; }
@@ -438,6 +615,18 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
     CacheCheck cc;
     int rc = check_cache(s, cache, n_req, cc);
     if (rc) return rc;
+
+    // A request that names a compressed packet (Sec. 5.4) takes the layer-by-layer route: its
+    // layers have different row counts.
+    for (int r = 0; r < n_req; ++r) {
+        const kvp_request_t &q = reqs[r];
+        if (q.k < 0 || (q.k > 0 && !q.packet_ids)) return fail(s, KVP_E_INVAL, "request %d: bad packet list", r);
+        for (int j = 0; j < q.k; ++j) {
+            auto it = s->dir.find(q.packet_ids[j]);
+            if (it != s->dir.end() && it->second.compressed())
+                return assemble_compressed(s, reqs, n_req, layer_begin, layer_end, cache, cc, hip_stream);
+        }
+    }
 
     // offsets Delta_j (Sec. 4.2.1 step 4: realign, then concatenate) and gather tiles
     std::vector<AsmTile> tiles;
@@ -538,7 +727,11 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
             slot->pending = true;
         }
     }
-    for (int r = 0; r < n_req; ++r) cache->ctx_len[r] = ctx[r];
+    for (int r = 0; r < n_req; ++r) {
+        cache->ctx_len[r] = ctx[r];
+        if (cache->ctx_rows)
+            for (int l = layer_begin; l < layer_end; ++l) cache->ctx_rows[(int64_t)r * g.n_layers + l] = ctx[r];
+    }
     return KVP_OK;
 }
 
@@ -626,7 +819,7 @@ bool use_mfma(const kvp_store *s, const kvp_cache_t *c)
     return !(c && c->layout == KVP_PAGED && c->block_size < MFMA_MIN_BLOCK_SIZE);
 }
 
-void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const int32_t *ctx_len, const int32_t *q_off,
+void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const int32_t *ctx_len, const int32_t *pos0, const int32_t *q_off,
                   PrefillPlan &p)
 {
     const kvp_config_t &g = s->cfg;
@@ -648,7 +841,7 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
     int64_t n_groups = 0;
     for (int r = 0; r < n_req; ++r) {
         int n_q = q_off[r + 1] - q_off[r];
-        p.reqs[r] = ReqMeta{ctx_len[r], q_off[r], n_q, 0};
+        p.reqs[r] = ReqMeta{ctx_len[r], q_off[r], n_q, pos0[r]};
         for (int t = 0; t < n_q; ++t) p.row_req.push_back(r);
         n_groups += (int64_t)g.n_kv_heads * (((int64_t)n_q * gq + p.bm - 1) / p.bm);
     }
@@ -690,6 +883,7 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
                     it.m0 = m0;
                     it.n_rows = gp.n_rows;
                     it.ctx_len = rq.ctx_len;
+                    it.pos0 = rq.pos0;
                     it.q_off = rq.q_off;
                     it.part_slot = gp.n_splits > 1 ? sp : -1;  // relative to the group until the stride is known
                     it.n_q = rq.n_q;
@@ -740,13 +934,17 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     if (rc) return rc;
     if (q_offsets[0] != 0) return fail(s, KVP_E_INVAL, "q_offsets[0] must be 0");
     std::vector<int> first_blk(n_req, 0), n_blk(n_req, 0);
+    std::vector<int32_t> rows(n_req, 0);  // rows of this layer per request (= ctx_len without compressed packets)
     for (int r = 0; r < n_req; ++r) {
         int n_q = q_offsets[r + 1] - q_offsets[r];
         if (n_q < 0) return fail(s, KVP_E_INVAL, "q_offsets is not non-decreasing at %d", r);
-        int c = cache->ctx_len[r];
-        if (c < 0) return fail(s, KVP_E_INVAL, "request %d: ctx_len %d < 0", r, c);
+        const int pos = cache->ctx_len[r];  // position of the first query token
+        const int c = cache->ctx_rows ? cache->ctx_rows[(int64_t)r * g.n_layers + layer] : pos;  // rows of this layer
+        if (pos < 0) return fail(s, KVP_E_INVAL, "request %d: ctx_len %d < 0", r, pos);
+        if (c < 0 || c > pos) return fail(s, KVP_E_INVAL, "request %d: ctx_rows %d outside [0, ctx_len %d]", r, c, pos);
+        rows[r] = c;
         int64_t total = (int64_t)c + n_q;
-        if (total > g.max_positions) return fail(s, KVP_E_CAPACITY, "request %d: %lld rows exceed max_positions %d", r, (long long)total, g.max_positions);
+        if ((int64_t)pos + n_q > g.max_positions) return fail(s, KVP_E_CAPACITY, "request %d: %lld positions exceed max_positions %d", r, (long long)pos + n_q, g.max_positions);
         if (total > cc.cap_rows) return fail(s, KVP_E_CAPACITY, "request %d: %lld rows do not fit the cache (%lld)", r, (long long)total, (long long)cc.cap_rows);
         if (cache->layout == KVP_PAGED && n_q > 0) n_blk[r] = (int)((total - 1) >> cc.shift) + 1;
     }
@@ -768,6 +966,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     sig.push_back(cache->layout == KVP_CONTIG ? cache->t_cap : cache->block_size);
     sig.push_back(cache->layout == KVP_CONTIG ? 0 : cache->n_blocks);
     for (int r = 0; r < n_req; ++r) sig.push_back(cache->ctx_len[r]);
+    for (int r = 0; r < n_req; ++r) sig.push_back(rows[r]);
     for (int r = 0; r <= n_req; ++r) sig.push_back(q_offsets[r]);
     if (cache->layout == KVP_PAGED)
         for (int r = 0; r < n_req; ++r) {
@@ -781,7 +980,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
 
     if (!hit) {
         PrefillPlan p;
-        plan_prefill(s, cache, n_req, cache->ctx_len, q_offsets, p);
+        plan_prefill(s, cache, n_req, rows.data(), cache->ctx_len, q_offsets, p);
         const uint64_t need = qrb + (uint64_t)p.n_slots * p.bm * (g.head_dim + 2) * sizeof(float);
         const uint64_t bytes = p.reqs.size() * sizeof(ReqMeta) + p.row_req.size() * 4 + p.groups.size() * sizeof(AttnGroup) +
                                p.items.size() * sizeof(AttnItem) + (uint64_t)n_req * bt_stride * 4 + 6 * 64;
@@ -966,6 +1165,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
                 auto itp = s->dir.find(rq.packet_ids[j]);
                 if (itp == s->dir.end()) return fail(s, KVP_E_NOTFOUND, "request %d: packet %lld not in the store", r, (long long)rq.packet_ids[j]);
                 const PacketRec &p = itp->second;
+                if (p.compressed()) return fail(s, KVP_E_INVAL, "request %d: packet %lld is compressed; kvp_prefill_packets reads uncompressed packets only", r, (long long)rq.packet_ids[j]);
                 for (int r0 = 0; r0 < p.n_tokens; r0 += 64)
                     tiles.push_back(AttnTile{p.elem_off, p.stride, r0, std::min(64, p.n_tokens - r0), (int32_t)pos, 0, 0});
                 pos += p.n_tokens;
@@ -973,7 +1173,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
             if (pos + n_q > g.max_positions) return fail(s, KVP_E_CAPACITY, "request %d: %lld rows exceed max_positions %d", r, (long long)(pos + n_q), g.max_positions);
             n_pkt_tiles[r] = (int)tiles.size() - tile_begin[r];
             for (int r0 = 0; r0 < n_q; r0 += 64) tiles.push_back(AttnTile{0, 0, r0, std::min(64, n_q - r0), 0, 1, 0});
-            metas[r] = ReqMeta{(int32_t)pos, q_offsets[r], n_q, 0};
+            metas[r] = ReqMeta{(int32_t)pos, q_offsets[r], n_q, (int32_t)pos};
             n_groups_total += (int64_t)g.n_kv_heads * (((int64_t)n_q * gq + MFMA_BM - 1) / MFMA_BM);
         }
         std::vector<AttnGroup> groups;
@@ -1014,6 +1214,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
                         it.m0 = m0;
                         it.n_rows = gp.n_rows;
                         it.ctx_len = rq.ctx_len;
+                        it.pos0 = rq.pos0;
                         it.q_off = rq.q_off;
                         it.part_slot = gp.n_splits > 1 ? sp : -1;
                         it.n_q = rq.n_q;

@@ -296,3 +296,70 @@ def test_items_that_share_kv_rows_land_on_one_xcd():
     for idx in where.values():
         assert len({i % 8 for i in idx}) == 1            # one XCD
         assert max(idx) - min(idx) <= 24                 # adjacent in launch order
+
+
+def test_compressed_packets_plan_rows_and_positions():
+    """Sec. 5.4: positions advance by the packets' spans, rows by what each layer kept."""
+    s = dry_store(n_layers=3)
+    kvp.kvp_store_put(s, 0, None, None, n_tokens=40)                       # uncompressed
+    kvp.kvp_store_put_compressed(s, 1, 100, None, None, n_rows=[100, 37, 0])  # 100 positions
+    kvp.kvp_store_put_compressed(s, 2, 70, None, None, n_rows=[1, 70, 65])
+    assert kvp.kvp_store_packet_len(s, 1) == 100
+    assert [kvp.kvp_store_packet_rows(s, 1, l) for l in range(3)] == [100, 37, 0]
+    assert kvp.kvp_store_packet_rows(s, 0, 2) == 40
+    cache = kvp.Cache.dry(2, t_cap=400).with_ctx_rows(3)
+    kvp.kvp_assemble(s, [([1, 0, 2], 5), ([0], 0)], cache)
+    assert list(cache.ctx_len[:2]) == [5 + 100 + 40 + 70, 40]
+    assert cache.ctx_rows[0].tolist() == [5 + 100 + 40 + 1, 5 + 37 + 40 + 70, 5 + 0 + 40 + 65]
+    assert cache.ctx_rows[1].tolist() == [40, 40, 40]
+    t = _tiles(s)
+    # every tile of request 0 is rotated by the Delta of its packet: 5, 105, 145
+    assert sorted(set(t[t[:, 6] == 0][:, 5])) == [5, 105, 145]
+    # tiles of compressed packets carry a negative stride (their blob is laid out layer by layer)
+    neg = t[t[:, 1] < 0]
+    assert len(neg) and set(-neg[:, 1]) <= {100, 37, 1, 70, 65}
+    # a layer range writes only its own entries
+    cache2 = kvp.Cache.dry(1, t_cap=400).with_ctx_rows(3)
+    cache2.ctx_rows[:] = -1
+    kvp.kvp_assemble(s, [([1], 0)], cache2, 1, 2)
+    assert cache2.ctx_rows[0].tolist() == [-1, 37, -1] and cache2.ctx_len[0] == 100
+    # the query side plans with the layer's rows and the request's position
+    kvp.kvp_assemble(s, [([1, 0, 2], 5), ([0], 0)], cache)
+    q_off = np.array([0, 4, 7], np.int32)
+    kvp.kvp_query_prefill(s, cache, 1, None, None, None, q_off, None, None)
+    kind, bm, groups, items, slots, need = _attn_plan(s)
+    ends = {r: max(e for g_, sp, b, e in items if groups[g_][0] == r) for r in (0, 1)}
+    assert ends[0] == cache.ctx_rows[0][1] + 4 and ends[1] == 40 + 3
+
+
+def test_compressed_packets_errors():
+    s = dry_store(n_layers=2)
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_store_put_compressed(s, 0, 10, None, None, n_rows=[11, 3])
+    assert e.value.code == kvp.KVP_E_INVAL
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_store_put_compressed(s, 0, 0, None, None, n_rows=[0, 0])
+    assert e.value.code == kvp.KVP_E_INVAL
+    kvp.kvp_store_put_compressed(s, 0, 10, None, None, n_rows=[10, 3])
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_store_put_compressed(s, 0, 10, None, None, n_rows=[1, 1])
+    assert e.value.code == kvp.KVP_E_EXISTS
+    cache = kvp.Cache.dry(1, t_cap=100)             # no ctx_rows
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_assemble(s, [([0], 0)], cache)
+    assert e.value.code == kvp.KVP_E_INVAL and "ctx_rows" in str(e.value)
+    cache = kvp.Cache.dry(1, t_cap=9).with_ctx_rows(2)   # layer 0 keeps 10 rows
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_assemble(s, [([0], 0)], cache)
+    assert e.value.code == kvp.KVP_E_CAPACITY
+    # the in-place attention path reads uncompressed packets only
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_prefill_packets(s, [([0], 0)], 0, None, None, None, np.array([0, 2], np.int32), None, None, None)
+    assert e.value.code == kvp.KVP_E_INVAL
+    # rows of a layer cannot exceed the position
+    cache = kvp.Cache.dry(1, t_cap=100).with_ctx_rows(2)
+    cache.ctx_len[0] = 5
+    cache.ctx_rows[0] = [6, 5]
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_query_prefill(s, cache, 0, None, None, None, np.array([0, 1], np.int32), None, None)
+    assert e.value.code == kvp.KVP_E_INVAL

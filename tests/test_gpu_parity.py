@@ -445,6 +445,118 @@ def test_host_pinned_arena(gpu_device):
     assert kvp.kvp_store_arena_on_host(dev_store) == 0
 
 
+def _compressed_case(w, seed, keep_prob, compressed_ids):
+    """Per packet and layer the sorted rows a pruning pass kept (None: the packet stays whole)."""
+    rng = np.random.default_rng(seed)
+    keeps = {}
+    for p in sorted({p for rq in w.requests for p in rq.packet_ids}):
+        L = int(w.packet_lens[p])
+        if p not in compressed_ids:
+            keeps[p] = None
+            continue
+        keeps[p] = [np.flatnonzero(rng.random(L) < keep_prob) for _ in range(w.n_layers)]
+    return keeps
+
+
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_compressed_packets_match_oracle(gpu_device, dtype, paged):
+    """Sec. 5.4: packets whose layers kept different row subsets are realigned by the Delta of
+    their uncompressed spans and concatenated without gaps; assembly bit-exact per layer (rows
+    and their count), attention within tolerance with the query at the position after the spans."""
+    import paper_2604_13226_amd as kvp
+    import oracle
+    if dtype == "bf16":
+        w = W.llama_k5(n_layers=3, n_packets=6)
+        w.packet_lens[:] = [300, 65, 128, 1, 517, 64]
+        w.requests[0].packet_ids = [4, 1, 0, 3, 2]
+        w.requests.append(W.Request(packet_ids=[5, 0], n_q=7, base_pos=0))     # a whole packet, then a compressed one
+        w.requests.append(W.Request(packet_ids=[1], n_q=33, base_pos=3))
+        comp = {0, 2, 3, 4}
+    else:
+        w = W.random_small(77, dtype="f32", d=64, n_q_heads=4, n_kv_heads=2, n_layers=2, n_packets=4, k=3, n_q=5, max_len=90)
+        comp = {w.requests[0].packet_ids[0], w.requests[0].packet_ids[-1]}
+    w.paged = paged
+    w.block_size = 16
+    keeps = _compressed_case(w, 5, 0.55, comp)
+    if dtype == "bf16":
+        keeps[3] = [np.array([0]), np.array([], int), np.array([0])]          # a one-row packet, pruned away in layer 1
+    f = oracle.inv_freq(w.rope_base, w.head_dim)
+    n_req, L = len(w.requests), w.n_layers
+    spans = {p: int(w.packet_lens[p]) for p in keeps}
+
+    # ---- library
+    pk = {p: w.packet_kv(p, device="cuda") for p in keeps}
+    arena = sum(kvp.packet_bytes(L, w.n_kv_heads, w.head_dim, w.dtype, spans[p]) for p in keeps) + 4096
+    pos_q = [rq.base_pos + sum(spans[p] for p in rq.packet_ids) for rq in w.requests]
+    store = kvp.kvp_store_create(L, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, w.rope_base,
+                                 max(pos_q) + 64, arena, w.n_header, w.n_trailer, device=0)
+    for p, keep in keeps.items():
+        k, v = pk[p]
+        if keep is None:
+            kvp.kvp_store_put(store, p, k, v)
+        else:
+            idx = [torch.as_tensor(kk, device="cuda") for kk in keep]
+            kvp.kvp_store_put_compressed(store, p, spans[p], [k[l][:, idx[l]].contiguous() for l in range(L)],
+                                         [v[l][:, idx[l]].contiguous() for l in range(L)])
+    rows_max = max(pos_q) + max(rq.n_q for rq in w.requests)
+    if paged:
+        bs = 16
+        nblk = [(pos_q[r] + w.requests[r].n_q + bs - 1) // bs for r in range(n_req)]
+        total = sum(nblk) + 2
+        perm = np.random.default_rng(9).permutation(total)
+        table = np.zeros((n_req, max(nblk)), np.int32)
+        at = 0
+        for r in range(n_req):
+            table[r, :nblk[r]] = perm[at:at + nblk[r]]
+            at += nblk[r]
+        cache = kvp.Cache.paged(store, n_req, total, table, bs)
+    else:
+        cache = kvp.Cache.contiguous(store, n_req, rows_max + 3)
+    cache.with_ctx_rows(L)
+    kvp.kvp_assemble(store, [(rq.packet_ids, rq.base_pos) for rq in w.requests], cache)
+    assert [int(x) for x in cache.ctx_len[:n_req]] == pos_q
+    q_off = np.zeros(n_req + 1, np.int32)
+    for r in range(n_req):
+        q_off[r + 1] = q_off[r] + w.requests[r].n_q
+    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, n_req, int(q_off[-1]), rows_max))
+    outs = {}
+    for layer in range(L):
+        parts = [w.query(r, layer, "cuda") for r in range(n_req)]
+        q, kn, vn = (torch.cat([p_[i] for p_ in parts]).contiguous() for i in range(3))
+        out = torch.full_like(q, float("nan"))
+        kvp.kvp_query_prefill(store, cache, layer, q, kn, vn, q_off, ws, out)
+        torch.cuda.synchronize()
+        outs[layer] = out.float().cpu().numpy().astype(np.float64)
+
+    # ---- oracle, layer by layer
+    for r, rq in enumerate(w.requests):
+        for layer in range(L):
+            ks, vs = [], []
+            for p in rq.packet_ids:
+                k, v = (W.to_numpy(x) for x in w.packet_kv(p))
+                sel = np.arange(spans[p]) if keeps[p] is None else keeps[p][layer]
+                ks.append(np.ascontiguousarray(k[layer][:, sel]))
+                vs.append(np.ascontiguousarray(v[layer][:, sel]))
+            n_rows = rq.base_pos + sum(k.shape[1] for k in ks)
+            Ko, Vo, rows, pos_end = oracle.assemble_layer_spans(w.dtype, ks, vs, [spans[p] for p in rq.packet_ids], f,
+                                                                rq.base_pos, t_cap=n_rows - rq.base_pos + rq.n_q)
+            assert pos_end == pos_q[r]
+            assert int(cache.ctx_rows[r][layer]) == n_rows
+            # the oracle's layer starts at the first packet row; the cache has base_pos caller rows before it
+            kg, vg = cache.logical(r, layer, n_rows + rq.n_q)
+            kg, vg = W.to_numpy(kg)[:, rq.base_pos:], W.to_numpy(vg)[:, rq.base_pos:]
+            assert np.array_equal(kg[:, :rows], Ko[:, :rows]), (r, layer, "K")
+            assert np.array_equal(vg[:, :rows], Vo[:, :rows]), (r, layer, "V")
+            if rq.base_pos:      # the caller's rows take part in attention: keep this case assembly-only
+                continue
+            qq, kn, vn = (W.to_numpy(x) for x in w.query(r, layer))
+            ref = oracle.query_prefill_at(w.dtype, qq, kn, vn, f, rows, pos_end, Ko, Vo)
+            assert np.array_equal(kg[:, rows:rows + rq.n_q], Ko[:, rows:rows + rq.n_q]), (r, layer, "K_new")
+            assert np.array_equal(vg[:, rows:rows + rq.n_q], Vo[:, rows:rows + rq.n_q]), (r, layer, "V_new")
+            check_output(outs[layer][q_off[r]:q_off[r + 1]], ref, w.dtype, ("compressed", r, layer))
+
+
 def test_zz_report_worst_relative_rms(gpu_device):
     """Prints the largest relative rms error the tests above saw (run with -s to see it)."""
     print("worst relative rms error:", WORST_REL_RMS)
