@@ -38,6 +38,7 @@ def make_workload(name):
     import kvp_workloads as W
     return {
         "llama_8k": lambda: W.llama_8k(),
+        "llama_8k_decode": lambda: W.llama_8k_decode(),
         "llama_k5": lambda: W.llama_k5(),
         "qwen_k20": lambda: W.qwen_k20(),
         "llama_long_b8": lambda: W.llama_long_b8(n_layers=4),

@@ -214,13 +214,18 @@ def serving_mix(seed=1005, n_layers=1, n_packets=16384, n_req=64, sigma=0.6):
                     reqs, paged=True, block_size=16)
 
 
-def llama_8k(seed=1008, n_layers=32, n_packets=64):
+def llama_8k(seed=1008, n_layers=32, n_packets=64, n_q=32, name="llama_8k"):
     """Headline point: Llama shape, k=16 packets of 8+496+8 = 512 rows -> T=8192, n_q=32."""
     rng = np.random.default_rng(seed)
     lens = np.full(n_packets, 512, np.int64)
     ids = [int(x) for x in rng.choice(n_packets, size=16, replace=False)]
-    return Workload("llama_8k", "bf16", n_layers, 32, 8, 128, 5.0e5, 8, 8, seed, 0.5, lens,
-                    [Request(ids, 32)])
+    return Workload(name, "bf16", n_layers, 32, 8, 128, 5.0e5, 8, 8, seed, 0.5, lens,
+                    [Request(ids, n_q)])
+
+
+def llama_8k_decode(seed=1008, n_layers=32, n_packets=64):
+    """One generated token over the headline point's composed cache (n_q = 1)."""
+    return llama_8k(seed, n_layers, n_packets, n_q=1, name="llama_8k_decode")
 
 
 def random_small(seed, dtype="f32", d=8, n_q_heads=4, n_kv_heads=2, n_layers=2, n_packets=5,

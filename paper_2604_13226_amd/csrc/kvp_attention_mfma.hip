@@ -97,6 +97,16 @@ __device__ __forceinline__ void load_to_lds_16(const void *sbase, uint32_t voff,
 {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
 }
+// A 16-byte global load whose wait is ours to place: before the first use of a load it knows,
+// the compiler waits for every load issued up to there, the tile loads included (it cannot
+// count those), so the query-side loads are made opaque to it as well and waited for by count.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4_t load16_nowait(const void *p)
+{
+    u32x4_t v;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
 // a pointer the program knows to be wave-uniform, made so for the compiler too
 __device__ __forceinline__ const char *uniform_ptr(const void *p)
 {
@@ -291,6 +301,88 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
             }
         }
     };
+    // this lane's query row
+    const int rr = 32 * wave_r + n;
+    const bool row_ok = rr < it.n_rows;
+    const bool wave_active = 32 * wave_r < it.n_rows;  // wave-uniform
+    const int m = it.m0 + (row_ok ? rr : 0);
+    const int t = m / g, hq = it.kv_head * g + m % g;
+    const int limit = row_ok ? it.ctx_len + t + 1 : 0;  // cache modes: kv rows [0, limit) are visible
+    // smallest limit among the wave's rows (rows are ordered by query token)
+    const int wave_limit = it.ctx_len + (it.m0 + 32 * wave_r) / g + 1;
+
+    // B operand of S^T = K Q^T: lane holds Q[m][16 ks + 8 h .. +7] for ks = 0..7, rotated by
+    // `rel` positions and multiplied by log2(e)/sqrt(d).  Element 16 ks + 8 h + j (ks < 4)
+    // pairs with the same slot of ks + 4, so the rotation stays inside the lane.
+    bf16x8 qf[8];
+    const bf16_t *qp = (const bf16_t *)a.q + ((int64_t)(it.q_off + t) * a.n_q_heads + hq) * D + 8 * h;
+    const int q_pos = a.prerotated ? 0 : it.pos0 + t;  // rotation the query still needs
+    u32x4_t qraw[8], csraw[16];
+    auto q_issue = [&](int delta) {  // 24 loads: the raw query row and the (cos, sin) of its rotation
+        const bf16_t *qsrc = row_ok ? qp : (const bf16_t *)a.q + 8 * h;  // idle lanes read row 0 (and drop it)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qraw[ks] = load16_nowait(qsrc + 16 * ks);
+        const int rel = row_ok ? q_pos - delta : 0;
+        const float4 *csr = (const float4 *)(a.cs + (int64_t)(rel < 0 ? -rel : rel) * 64 + 8 * h);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) csraw[4 * ks + j] = load16_nowait(csr + 8 * ks + j);
+    };
+    // `younger`: tiles whose loads were issued after q_issue and may still be on their way
+    auto q_finish = [&](int delta, int younger) {
+        if (younger >= 3) wait_vmcnt<3 * 2 * NI>();
+        else if (younger == 2) wait_vmcnt<2 * 2 * NI>();
+        else if (younger == 1) wait_vmcnt<2 * NI>();
+        else wait_vmcnt<0>();
+        // the registers are valid from here on: keep every use below this point
+#pragma unroll
+        for (int i = 0; i < 8; ++i) asm volatile("" : "+v"(qraw[i]));
+#pragma unroll
+        for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(csraw[i]));
+        const int rel = row_ok ? q_pos - delta : 0;
+        const float sign = rel < 0 ? -1.f : 1.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            float4 cs4[4];  // (cos, sin) pairs of elements 16 ks + 8 h + 2 j, + 1
+#pragma unroll
+            for (int j = 0; j < 4; ++j) cs4[j] = __builtin_bit_cast(float4, csraw[4 * ks + j]);
+            uint4 lo = __builtin_bit_cast(uint4, qraw[ks]), hi = __builtin_bit_cast(uint4, qraw[ks + 4]);
+            if (!row_ok) lo = hi = make_uint4(0, 0, 0, 0);
+            uint4 olo, ohi;
+            rotate_chunk_pair<false>(lo, hi, cs4, sign, a.scale_log2e, olo, ohi);
+            qf[ks] = __builtin_bit_cast(bf16x8, olo);
+            qf[ks + 4] = __builtin_bit_cast(bf16x8, ohi);
+        }
+        // pinned: nothing of this is recomputed or waited for inside the tile loop
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));
+    };
+    // Re-rotation inside the tile loop (in-place packet reads, at every packet boundary): plain
+    // loads, whose wait the compiler places (it drains the tile loads in flight as well).
+    auto reload_q = [&](int delta) {
+        uint4 qr[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qr[ks] = row_ok ? *(const uint4 *)(qp + 16 * ks) : make_uint4(0, 0, 0, 0);
+        const int rel = row_ok ? q_pos - delta : 0;
+        const float sign = rel < 0 ? -1.f : 1.f;
+        const float4 *csr = (const float4 *)(a.cs + (int64_t)(rel < 0 ? -rel : rel) * 64 + 8 * h);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            float4 cs4[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) cs4[j] = csr[8 * ks + j];
+            uint4 olo, ohi;
+            rotate_chunk_pair<false>(qr[ks], qr[ks + 4], cs4, sign, a.scale_log2e, olo, ohi);
+            qf[ks] = __builtin_bit_cast(bf16x8, olo);
+            qf[ks + 4] = __builtin_bit_cast(bf16x8, ohi);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));
+    };
+    int cur_delta = SRC == SRC_PACKETS && n_tiles > 0 ? a.tiles[it.kv_begin].pos : 0;
+    KVP_STAMP(1);
+    q_issue(cur_delta);  // first, so that the query arrives ahead of the tiles
     // a first tile that cannot contain query rows can start its trip right away
     const bool early0 = n_tiles > 0 && (SRC == SRC_PACKETS ? a.tiles[it.kv_begin].kind == 0 : it.kv_begin + BN <= it.ctx_len);
     if (early0) issue(0);
@@ -353,50 +445,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
     for (int s = 0; s < KS * PR; ++s)
         if (s < n_tiles && !(s == 0 && early0)) issue(s);
 
-    // this lane's query row
-    const int rr = 32 * wave_r + n;
-    const bool row_ok = rr < it.n_rows;
-    const bool wave_active = 32 * wave_r < it.n_rows;  // wave-uniform
-    const int m = it.m0 + (row_ok ? rr : 0);
-    const int t = m / g, hq = it.kv_head * g + m % g;
-    const int limit = row_ok ? it.ctx_len + t + 1 : 0;  // cache modes: kv rows [0, limit) are visible
-    // smallest limit among the wave's rows (rows are ordered by query token)
-    const int wave_limit = it.ctx_len + (it.m0 + 32 * wave_r) / g + 1;
-
-    // B operand of S^T = K Q^T: lane holds Q[m][16 ks + 8 h .. +7] for ks = 0..7, rotated by
-    // `rel` positions and multiplied by log2(e)/sqrt(d).  Element 16 ks + 8 h + j (ks < 4)
-    // pairs with the same slot of ks + 4, so the rotation stays inside the lane.
-    bf16x8 qf[8];
-    const bf16_t *qp = (const bf16_t *)a.q + ((int64_t)(it.q_off + t) * a.n_q_heads + hq) * D + 8 * h;
-    const int q_pos = a.prerotated ? 0 : it.pos0 + t;  // rotation the query still needs
-    auto load_q = [&](int delta) {
-        uint4 qraw[8];
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qraw[ks] = row_ok ? *(const uint4 *)(qp + 16 * ks) : make_uint4(0, 0, 0, 0);
-        const int rel = row_ok ? q_pos - delta : 0;
-        const float sign = rel < 0 ? -1.f : 1.f;
-        const float4 *csr = (const float4 *)(a.cs + (int64_t)(rel < 0 ? -rel : rel) * 64 + 8 * h);
-        float4 cs4[4][4];  // (cos, sin) pairs of elements 16 ks + 8 h + 2 j, + 1
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) cs4[ks][j] = csr[8 * ks + j];
-        __builtin_amdgcn_sched_barrier(0);  // all 24 loads are in flight before the first use
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            uint4 olo, ohi;
-            rotate_chunk_pair<false>(qraw[ks], qraw[ks + 4], cs4[ks], sign, a.scale_log2e, olo, ohi);
-            qf[ks] = __builtin_bit_cast(bf16x8, olo);
-            qf[ks + 4] = __builtin_bit_cast(bf16x8, ohi);
-        }
-        // Pin Q in registers here: the compiler then places its wait for these loads right
-        // here instead of at their first use inside the tile loop's matrix code.
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));
-    };
-    int cur_delta = SRC == SRC_PACKETS && n_tiles > 0 ? a.tiles[it.kv_begin].pos : 0;
-    KVP_STAMP(1);
-    load_q(cur_delta);
+    q_finish(cur_delta, n_tiles < KS * PR ? n_tiles : KS * PR);
     KVP_STAMP(2);
 
     floatx16 oacc[4];
@@ -458,7 +507,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
             td = a.tiles[it.kv_begin + ti];
             if (td.pos != cur_delta && wave_active) {  // the tile belongs to another packet: re-rotate the query
                 cur_delta = td.pos;
-                load_q(cur_delta);
+                reload_q(cur_delta);
             }
         }
 

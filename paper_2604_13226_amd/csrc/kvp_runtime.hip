@@ -738,11 +738,6 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
 // -------------------------------------------------------------------------------------
 namespace {
 
-// Workgroups are dealt to the 8 XCDs round-robin by index, and each XCD has its own L2.
-// Items that read the same K/V rows (same request, KV head and kv range, different row
-// blocks) are therefore placed 8 apart, next to each other in launch order: they run on
-// one XCD at about the same time and all but the first find the tiles in its L2.  Cohorts
-// of unequal size are padded with null items (n_rows = 0: the workgroup exits at once).
 // Partial slots: group gi owns slots gi * stride .. + stride - 1 (stride = the largest split
 // count of the call), so the combine kernel knows where a group's partials are before it has
 // read the group's record.  stride 0: nothing is split, no slots.
@@ -754,6 +749,11 @@ void assign_part_slots(std::vector<AttnGroup> &groups, std::vector<AttnItem> &it
     n_slots = (int)groups.size() * stride;
 }
 
+// Workgroups are dealt to the 8 XCDs round-robin by index, and each XCD has its own L2.
+// Items that read the same K/V rows (same request, KV head and kv range, different row
+// blocks) are therefore placed 8 apart, next to each other in launch order: they run on
+// one XCD at about the same time and all but the first find the tiles in its L2.  Cohorts
+// of unequal size are padded with null items (n_rows = 0: the workgroup exits at once).
 void xcd_order(std::vector<AttnItem> &items)
 {
     constexpr int XCDS = 8;
