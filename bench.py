@@ -42,6 +42,8 @@ def make_workload(name):
         "llama_k5": lambda: W.llama_k5(),
         "qwen_k20": lambda: W.qwen_k20(),
         "llama_long_b8": lambda: W.llama_long_b8(n_layers=4),
+        "llama_long_b8_q32": lambda: W.llama_long_b8(n_layers=4, n_q=32),   # the same contexts, HBM-bound (n_q g = 128)
+        "llama_long_b8_q1": lambda: W.llama_long_b8(n_layers=4, n_q=1),     # one decode step over them
         "serving_mix": lambda: W.serving_mix(n_layers=1),
         "tiny_fp32": lambda: W.tiny_fp32(),
     }[name]()

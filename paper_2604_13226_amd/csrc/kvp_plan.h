@@ -115,6 +115,7 @@ struct AttnArgs {
     int32_t n_items, n_groups, layer, n_q_heads, n_kv, d, bm, g;
     int32_t split_in_wg;  // MFMA kernel, 128-row blocks: two wave groups take alternate tiles
     int32_t part_stride;  // partial slots per group
+    int32_t max_group_rows;  // largest n_rows among the groups that are split (the combine grid covers no more)
     float scale_log2e;  // log2(e) / sqrt(d)
 #ifdef KVP_TIMING
     unsigned long long *dbg;  // per-item timestamps (bench builds only)

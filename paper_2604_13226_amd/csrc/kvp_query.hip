@@ -240,7 +240,8 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a)
 int launch_combine(int dtype, const AttnArgs &a, void *stream)
 {
     if (a.n_groups == 0) return 0;
-    dim3 grid((unsigned)a.n_groups, (unsigned)((a.bm + COMBINE_ROWS - 1) / COMBINE_ROWS));
+    const int rows = a.max_group_rows > 0 && a.max_group_rows < a.bm ? a.max_group_rows : a.bm;
+    dim3 grid((unsigned)a.n_groups, (unsigned)((rows + COMBINE_ROWS - 1) / COMBINE_ROWS));
     if (dtype == 1) hipLaunchKernelGGL((combine_kernel<bf16_t>), grid, dim3(256), 0, (hipStream_t)stream, a);
     else hipLaunchKernelGGL((combine_kernel<float>), grid, dim3(256), 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();

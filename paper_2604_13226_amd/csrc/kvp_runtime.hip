@@ -129,7 +129,7 @@ struct kvp_store {
         const AttnGroup *groups_dev = nullptr;
         const AttnItem *items_dev = nullptr;
         const AttnTile *tiles_dev = nullptr;
-        int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0, part_stride = 1;
+        int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0, part_stride = 1, max_group_rows = 0;
         bool any_split = false;
         uint64_t need = 0;
     } pf, pk;  // pf: kvp_query_prefill, pk: kvp_prefill_packets
@@ -799,7 +799,7 @@ struct PrefillPlan {
     std::vector<int32_t> row_req;
     std::vector<AttnGroup> groups;
     std::vector<AttnItem> items;
-    int n_slots = 0, part_stride = 1;
+    int n_slots = 0, part_stride = 1, max_group_rows = 0;
     bool any_split = false;
 };
 
@@ -807,7 +807,17 @@ constexpr int MFMA_BM = 128;
 constexpr int GENERIC_BM = 8;
 constexpr int MAX_SPLITS = 64;
 
-int target_items(const kvp_store *s) { return s->target_items > 0 ? s->target_items : s->n_cu * 3 / 4; }
+// Work items a launch should have.  Three quarters of the CU count when the call reads little
+// (one 8K request: every extra split costs partial traffic and the items are latency-bound
+// anyway); two per CU -- the 128-row kernel's occupancy -- once there are many tiles per CU to
+// stream, where bytes in flight are what counts (measured: 8 requests of 16.9K context with 32
+// query rows, 158 -> 133 us per layer).
+int target_items(const kvp_store *s, int64_t tiles = 0, int bm = 0)
+{
+    if (s->target_items > 0) return s->target_items;
+    if (bm == 128 && tiles >= 16 * (int64_t)s->n_cu) return 2 * s->n_cu;
+    return s->n_cu * 3 / 4;
+}
 
 // Groups of packed rows and their split-KV items.  Every group of a request gets the same
 // split length (a multiple of bn rows), chosen so the launch has about target_items work
@@ -846,7 +856,10 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
         n_groups += (int64_t)g.n_kv_heads * (((int64_t)n_q * gq + p.bm - 1) / p.bm);
     }
     if (n_groups == 0) return;
-    int want = (int)std::min<int64_t>(MAX_SPLITS, (target_items(s) + n_groups - 1) / n_groups);
+    int64_t tiles = 0;  // 64-row tiles all the items together will read
+    for (int r = 0; r < n_req; ++r)
+        tiles += (int64_t)g.n_kv_heads * (((int64_t)p.reqs[r].n_q * gq + p.bm - 1) / p.bm) * ((p.reqs[r].ctx_len + p.reqs[r].n_q + 63) / 64);
+    int want = (int)std::min<int64_t>(MAX_SPLITS, (target_items(s, tiles, mfma ? p.bm : 0) + n_groups - 1) / n_groups);
     if (want < 1) want = 1;
     for (int r = 0; r < n_req; ++r) {
         const ReqMeta &rq = p.reqs[r];
@@ -870,7 +883,10 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
                 gp.part0 = 0;  // set below, once the slot stride is known
                 gp.q_off = rq.q_off;
                 gp.pad1 = 0;
-                if (gp.n_splits > 1) p.any_split = true;
+                if (gp.n_splits > 1) {
+                    p.any_split = true;
+                    p.max_group_rows = std::max(p.max_group_rows, gp.n_rows);
+                }
                 p.part_stride = std::max(p.part_stride, gp.n_splits);
                 for (int sp = 0; sp < gp.n_splits; ++sp) {
                     AttnItem it{};
@@ -915,7 +931,7 @@ uint64_t kvp_prefill_workspace_bytes(const kvp_store_t *s, int32_t n_req, int32_
     const uint64_t groups = (uint64_t)g.n_kv_heads * ((uint64_t)max_tot_q * gq / bm + (uint64_t)n_req);
     // (a paged cache may force extra splits: at most max_ctx / 32704 more per group)
     const uint64_t extra = (uint64_t)max_ctx / ((MFMA_MAX_ITEM_BLOCKS - 1) * MFMA_MIN_BLOCK_SIZE / 64 * 64);
-    const uint64_t slots = (uint64_t)target_items(s) + (2 + extra) * groups;
+    const uint64_t slots = (uint64_t)std::max(target_items(s), 2 * s->n_cu) + (2 + extra) * groups;
     // (the MFMA kernel may pick 256-row blocks: twice the rows per slot, no more slots)
     return q_rot_bytes(s, max_tot_q) + slots * (mfma ? 2 * bm : bm) * (g.head_dim + 2) * sizeof(float) + ALIGN;
 }
@@ -1024,6 +1040,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         pf.tot_q = tot_q;
         pf.any_split = p.any_split;
         pf.part_stride = p.part_stride;
+        pf.max_group_rows = p.max_group_rows;
         pf.need = need;
         pf.sig = sig;
         pf.stream = hip_stream;
@@ -1096,6 +1113,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     at.bm = pf.bm;
     at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : 0;
     at.part_stride = pf.part_stride;
+    at.max_group_rows = pf.max_group_rows;
     at.g = g.n_q_heads / g.n_kv_heads;
     at.scale_log2e = (float)(1.4426950408889634 / sqrt((double)g.head_dim));
     e = launch_attention(g.dtype, at, pf.kind, hip_stream);
@@ -1178,7 +1196,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         }
         std::vector<AttnGroup> groups;
         std::vector<AttnItem> items;
-        int n_slots = 0, part_stride = 1;
+        int n_slots = 0, part_stride = 1, max_group_rows = 0;
         bool any_split = false;
         int want = n_groups_total ? (int)std::min<int64_t>(MAX_SPLITS, (target_items(s) + n_groups_total - 1) / n_groups_total) : 1;
         if (want < 1) want = 1;
@@ -1201,7 +1219,10 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
                     gp.part0 = 0;
                     gp.q_off = rq.q_off;
                     gp.pad1 = 0;
-                    if (gp.n_splits > 1) any_split = true;
+                    if (gp.n_splits > 1) {
+                        any_split = true;
+                        max_group_rows = std::max(max_group_rows, gp.n_rows);
+                    }
                     part_stride = std::max(part_stride, gp.n_splits);
                     for (int sp = 0; sp < gp.n_splits; ++sp) {
                         AttnItem it{};
@@ -1267,6 +1288,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         pk.tot_q = tot_q;
         pk.any_split = any_split;
         pk.part_stride = part_stride;
+        pk.max_group_rows = max_group_rows;
         pk.need = need;
         pk.sig = sig;
         pk.stream = hip_stream;
@@ -1308,6 +1330,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     at.bm = pk.bm;
     at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : 0;
     at.part_stride = pk.part_stride;
+    at.max_group_rows = pk.max_group_rows;
     at.g = g.n_q_heads / g.n_kv_heads;
     at.scale_log2e = (float)(1.4426950408889634 / sqrt((double)g.head_dim));
     int e = launch_attention(g.dtype, at, ATTN_MFMA, hip_stream);
