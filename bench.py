@@ -115,6 +115,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     w = make_workload(args.workload)
+    w.name = args.workload
     n_req = len(w.requests)
     store = build_store(w, kvp, dev, packets=list(range(len(w.packet_lens)))
                         if len(w.packet_lens) <= 256 and args.store == "device" else None, arena=args.store)
@@ -243,6 +244,11 @@ def main():
                               "p99": float(np.percentile(step_ms, 99)) * 1e3 / w.n_layers,
                               "what": "per timed step, HIP events around assemble + all layers' prefill"},
     }
+    if args.path == "packets" and args.store == "device":
+        # nothing is assembled: the dominant kernel is the attention reading the store in place
+        res["roofline"] = {"bound": "hbm", "kernel": "attention_mfma_kernel (packets read in place) + combine, per layer",
+                           "achieved": pre_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pre_gbs / HBM_PEAK_GBS,
+                           "traffic": None, "bytes_per_launch": pre_bytes, "us_per_launch": pre_us_layer}
     if args.store == "host":
         # the packets cross PCIe at every assembly (or at every in-place read): that link bounds
         # the step; its rate is whole-step bytes read from the store over wall time
