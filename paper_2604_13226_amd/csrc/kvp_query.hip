@@ -155,6 +155,7 @@ __global__ __launch_bounds__(256) void attention_generic_kernel(AttnArgs a)
 //   m = max m_i;  l = sum l_i 2^(m_i - m);  O = sum O~_i 2^(m_i - m) / l.
 // A split that saw no visible row has m_i = -inf, l_i = 0 and contributes nothing.
 // ---------------------------------------------------------------------------------
+// Two shapes.  Many splits per group (the latency-bound single-request calls):
 // One wavefront per packed row.  Lane i first holds the log-sum-exp weight of split i (at
 // most 64 splits); then lane half hf = i / 32 sweeps the splits of its parity, columns
 // 4 (i % 32) .. +3 (+128 j) with 16-byte loads, several splits in flight at once, and the
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(256) void attention_generic_kernel(AttnArgs a)
 constexpr int COMBINE_ROWS = 4;  // rows per 256-thread workgroup
 
 template <typename T>
-__global__ __launch_bounds__(256) void combine_kernel(AttnArgs a)
+__global__ __launch_bounds__(256) void combine_wave_kernel(AttnArgs a)
 {
     const int lane = threadIdx.x & 63, li = lane & 31, hf = lane >> 5;
     const int rr = (int)blockIdx.y * COMBINE_ROWS + (threadIdx.x >> 6);
@@ -237,13 +238,117 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a)
     }
 }
 
+// Few splits per group (at most COMBINE_EARLY: the batched calls, where rows are many):
+// One thread per (row, column chunk): VW columns of one packed row, so a 256-thread workgroup
+// covers 256 VW / d rows.  The threads of a row first put the (m, l) of its splits into LDS
+// (one load each) while every thread already has the O pieces of the first EARLY splits on
+// their way -- group gi's partial slots start at gi * part_stride, so none of these loads waits
+// for the group's record; slots and rows the group does not use hold stale bytes of the
+// workspace (in bounds) and are masked once the record is there.  Then each thread merges its
+// own columns: no exchange between lanes.
+constexpr int COMBINE_EARLY = 8;
+constexpr int COMBINE_MAX_SPLITS = 64;  // the planner's bound on splits per group
+__host__ __device__ inline int combine_rows_per_block(int cpr) { int r = 256 / cpr; return r > 32 ? 32 : r; }
+
+template <int VW> struct CombineVec;
+template <> struct CombineVec<4> { typedef float4 type; };
+template <> struct CombineVec<1> { typedef float type; };
+
+__device__ __forceinline__ void cv_fma(float4 &acc, const float4 &v, float w) { acc.x += v.x * w; acc.y += v.y * w; acc.z += v.z * w; acc.w += v.w * w; }
+__device__ __forceinline__ void cv_fma(float &acc, const float &v, float w) { acc += v * w; }
+__device__ __forceinline__ void cv_zero(float4 &v) { v = make_float4(0.f, 0.f, 0.f, 0.f); }
+__device__ __forceinline__ void cv_zero(float &v) { v = 0.f; }
+template <typename T> __device__ __forceinline__ void cv_store(T *p, const float4 &v, float s)
+{
+    st_elem(p, v.x * s); st_elem(p + 1, v.y * s); st_elem(p + 2, v.z * s); st_elem(p + 3, v.w * s);
+}
+template <typename T> __device__ __forceinline__ void cv_store(T *p, const float &v, float s) { st_elem(p, v * s); }
+
+template <typename T, int VW>
+__global__ __launch_bounds__(256) void combine_thread_kernel(AttnArgs a)
+{
+    typedef typename CombineVec<VW>::type vec_t;
+    extern __shared__ float ml_lds[];  // [rows per block][2][stride]
+    const int d = a.d, cpr = d / VW;   // chunks (threads) per row
+    const int rpb = combine_rows_per_block(cpr);
+    const int rb = (int)threadIdx.x / cpr, c = (int)threadIdx.x % cpr;
+    const bool active = rb < rpb;      // threads beyond the block's last whole row only keep the barrier company
+    const int rr = active ? (int)blockIdx.y * rpb + rb : a.bm;
+    const int stride = a.part_stride;
+    const int64_t slot = (int64_t)a.bm * (d + 2);
+    const float *base = a.partials + (int64_t)blockIdx.x * stride * slot;
+    const bool in_slot = rr < a.bm;
+    const float *ml = base + (int64_t)a.bm * d + rr;
+    const vec_t *row = (const vec_t *)(base + (int64_t)rr * d) + c;
+    const int64_t vslot = slot / VW;  // slot is a multiple of VW whenever d is
+
+    vec_t v0[COMBINE_EARLY];
+#pragma unroll
+    for (int i = 0; i < COMBINE_EARLY; ++i) {
+        cv_zero(v0[i]);
+        if (in_slot && i < stride) v0[i] = row[i * vslot];
+    }
+    float *my_m = ml_lds + ((active ? rb : 0) * 2) * stride, *my_l = my_m + stride;
+    for (int sp = c; active && sp < stride; sp += cpr) {
+        my_m[sp] = in_slot ? ml[sp * slot] : -INFINITY;
+        my_l[sp] = in_slot ? ml[sp * slot + a.bm] : 0.f;
+    }
+    const AttnGroup gp = a.groups[blockIdx.x];
+    __syncthreads();
+    const int ns = gp.n_splits;
+    if (ns <= 1 || rr >= gp.n_rows) return;
+    float mx = -INFINITY;
+    for (int sp = 0; sp < ns; ++sp) mx = fmaxf(mx, my_m[sp]);
+    vec_t acc;
+    cv_zero(acc);
+    float lsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < COMBINE_EARLY; ++i)
+        if (i < ns) {
+            const float mi = my_m[i];
+            const float w = mi == -INFINITY ? 0.f : exp2f(mi - mx);
+            lsum += my_l[i] * w;
+            if (w != 0.f) cv_fma(acc, v0[i], w);  // a split without visible rows may hold anything
+        }
+#pragma unroll 4
+    for (int sp = COMBINE_EARLY; sp < ns; ++sp) {
+        const float mi = my_m[sp];
+        const float w = mi == -INFINITY ? 0.f : exp2f(mi - mx);
+        lsum += my_l[sp] * w;
+        const vec_t v = row[sp * vslot];
+        if (w != 0.f) cv_fma(acc, v, w);
+    }
+    const int m = gp.m0 + rr;
+    const int t = m / a.g, hq = gp.kv_head * a.g + m % a.g;
+    T *op = (T *)a.out + ((int64_t)(gp.q_off + t) * a.n_q_heads + hq) * d + c * VW;
+    cv_store(op, acc, 1.f / lsum);
+}
+
 int launch_combine(int dtype, const AttnArgs &a, void *stream)
 {
     if (a.n_groups == 0) return 0;
     const int rows = a.max_group_rows > 0 && a.max_group_rows < a.bm ? a.max_group_rows : a.bm;
-    dim3 grid((unsigned)a.n_groups, (unsigned)((rows + COMBINE_ROWS - 1) / COMBINE_ROWS));
-    if (dtype == 1) hipLaunchKernelGGL((combine_kernel<bf16_t>), grid, dim3(256), 0, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL((combine_kernel<float>), grid, dim3(256), 0, (hipStream_t)stream, a);
+    hipStream_t st = (hipStream_t)stream;
+    if (a.part_stride > COMBINE_MAX_SPLITS) return (int)hipErrorInvalidValue;
+    if (a.part_stride > COMBINE_EARLY) {  // many splits: a wavefront per row, its lanes over the splits
+        dim3 grid((unsigned)a.n_groups, (unsigned)((rows + COMBINE_ROWS - 1) / COMBINE_ROWS));
+        if (dtype == 1) hipLaunchKernelGGL((combine_wave_kernel<bf16_t>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((combine_wave_kernel<float>), grid, dim3(256), 0, st, a);
+        return (int)hipGetLastError();
+    }
+    const int vw = a.d % 4 == 0 ? 4 : 1;
+    const int cpr = a.d / vw;
+    if (cpr < 1 || cpr > 256) return (int)hipErrorInvalidValue;
+    const int rpb = combine_rows_per_block(cpr);
+    dim3 grid((unsigned)a.n_groups, (unsigned)((rows + rpb - 1) / rpb));
+    const size_t lds = (size_t)rpb * 2 * a.part_stride * sizeof(float);
+    if (dtype == 1) {
+        if (vw == 4) hipLaunchKernelGGL((combine_thread_kernel<bf16_t, 4>), grid, dim3(256), lds, st, a);
+        else hipLaunchKernelGGL((combine_thread_kernel<bf16_t, 1>), grid, dim3(256), lds, st, a);
+    } else {
+        if (vw == 4) hipLaunchKernelGGL((combine_thread_kernel<float, 4>), grid, dim3(256), lds, st, a);
+        else hipLaunchKernelGGL((combine_thread_kernel<float, 1>), grid, dim3(256), lds, st, a);
+    }
     return (int)hipGetLastError();
 }
 
