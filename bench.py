@@ -86,6 +86,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=100,
                     help="untimed steps first: the GPU clock takes some 20 ms of load to settle")
     ap.add_argument("--workload", default="llama_8k")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="instantiate only this many layers of the workload (counter runs, where every "
+                         "dispatch is slow, keep the store small with it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=16)
     ap.add_argument("--path", default="cache", choices=["cache", "packets"],
@@ -113,12 +116,20 @@ def main():
     from tests.gpu_harness import build_store, make_cache
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    t_start = time.perf_counter()
+
+    def note(what):  # progress on stderr: a profiled run is slow, not silent
+        print("[%7.2f s] %s" % (time.perf_counter() - t_start, what), file=sys.stderr, flush=True)
+
     dev = "cuda:0"
     w = make_workload(args.workload)
     w.name = args.workload
+    if args.layers > 0:
+        w.n_layers = min(w.n_layers, args.layers)
     n_req = len(w.requests)
     store = build_store(w, kvp, dev, packets=list(range(len(w.packet_lens)))
-                        if len(w.packet_lens) <= 256 and args.store == "device" else None, arena=args.store)
+                        if len(w.packet_lens) <= 256 and args.store == "device" else None, arena=args.store,
+                        progress=lambda i, n: print("store: packet %d of %d" % (i, n), file=sys.stderr, flush=True))
     cache = make_cache(w, kvp, store, dev, t_slack=0)
     reqs = [(rq.packet_ids, rq.base_pos) for rq in w.requests]
     q_off = np.zeros(n_req + 1, np.int32)
@@ -134,6 +145,7 @@ def main():
         qkv.append(tuple(torch.cat([p[i] for p in parts]).contiguous() for i in range(3)))
     out = torch.empty_like(qkv[0][0])
     torch.cuda.synchronize()
+    note("store, cache and inputs ready")
 
     k_tail = torch.empty_like(qkv[0][1])
     reqs0 = [(rq.packet_ids, 0) for rq in w.requests]
@@ -186,15 +198,20 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
+    for i in range(args.warmup):
         step()
+        if i == 0:
+            torch.cuda.synchronize()
+            note("first step done")
     torch.cuda.synchronize()
+    note("warm-up done")
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(events[i])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    note("timed steps done")
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     asm_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
     pre_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))

@@ -19,7 +19,8 @@ def needed_packets(w):
     return sorted({p for rq in w.requests for p in rq.packet_ids})
 
 
-def build_store(w, kvp, device="cuda:0", packets=None, max_positions=None, extra_bytes=0, arena="device"):
+def build_store(w, kvp, device="cuda:0", packets=None, max_positions=None, extra_bytes=0, arena="device",
+                progress=None):
     packets = needed_packets(w) if packets is None else packets
     arena_bytes = sum(kvp.packet_bytes(w.n_layers, w.n_kv_heads, w.head_dim, w.dtype, int(w.packet_lens[p]))
                       for p in packets) + extra_bytes
@@ -28,9 +29,11 @@ def build_store(w, kvp, device="cuda:0", packets=None, max_positions=None, extra
     store = kvp.kvp_store_create(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype,
                                  w.rope_base, max_positions, max(arena_bytes, 256), w.n_header,
                                  w.n_trailer, device=0, arena=arena)
-    for p in packets:
+    for i, p in enumerate(packets):
         k, v = w.packet_kv(p, device=device)
         kvp.kvp_store_put(store, p, k, v)
+        if progress is not None and i % 32 == 31:
+            progress(i + 1, len(packets))
     torch.cuda.synchronize()
     return store
 
