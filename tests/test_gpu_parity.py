@@ -557,6 +557,31 @@ def test_compressed_packets_match_oracle(gpu_device, dtype, paged):
             check_output(outs[layer][q_off[r]:q_off[r + 1]], ref, w.dtype, ("compressed", r, layer))
 
 
+def test_repeated_calls_reuse_the_plan_and_give_the_same_bits(gpu_device):
+    """The same geometry layer after layer reuses the uploaded plan: six calls in a row match the
+    oracle and each other bit for bit (same items, same merge order)."""
+    import paper_2604_13226_amd as kvp
+    w = W.llama_8k(n_layers=1, n_packets=16)
+    ref = oracle_workload(w)
+    store = build_store(w, kvp)
+    cache = make_cache(w, kvp, store)
+    kvp.kvp_assemble(store, [(rq.packet_ids, rq.base_pos) for rq in w.requests], cache)
+    q, kn, vn = w.query(0, 0, "cuda")
+    n_q = w.requests[0].n_q
+    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, 1, n_q, w.ctx_len(0) + n_q))
+    outs = []
+    for rep in range(6):
+        out = torch.full_like(q, float("nan"))
+        kvp.kvp_query_prefill(store, cache, 0, q, kn, vn, [0, n_q], ws, out)
+        torch.cuda.synchronize()
+        o = out.float().cpu().numpy().astype(np.float64)
+        check_output(o, ref["out"][0][0], w.dtype, ("repeat", rep))
+        outs.append(o)
+    assert kvp.kvp_debug_last_plan(store, 1)[3] > 8          # the call was split
+    for o in outs[1:]:
+        assert np.array_equal(o, outs[0])
+
+
 def test_zz_report_worst_relative_rms(gpu_device):
     """Prints the largest relative rms error the tests above saw (run with -s to see it)."""
     print("worst relative rms error:", WORST_REL_RMS)
