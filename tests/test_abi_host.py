@@ -167,13 +167,34 @@ def _attn_plan(s):
     return kind, bm, groups, items, slots, need
 
 
+def _random_prefill_cases(n):
+    """Seeded random batch geometries: ragged contexts (some empty), ragged query counts (some
+    zero), head groupings 1 / 4 / 7, both attention kernels."""
+    rng = np.random.default_rng(4242)
+    out = []
+    for _ in range(n):
+        n_kv = int(rng.choice([1, 2, 4, 8]))
+        grp = int(rng.choice([1, 4, 7]))
+        n_req = int(rng.integers(1, 9))
+        big = rng.random() < 0.3
+        ctx = [int(x) for x in rng.integers(0, 40000 if big else 3000, size=n_req)]
+        n_q = [int(x) for x in rng.integers(0, 300, size=n_req)]
+        if sum(n_q) == 0:
+            n_q[0] = 1
+        c = dict(n_q_heads=n_kv * grp, n_kv_heads=n_kv, ctx=ctx, n_q=n_q, max_positions=1 << 17)
+        if rng.random() < 0.25:
+            c.update(head_dim=64, dtype="f32")
+        out.append(c)
+    return out
+
+
 @pytest.mark.parametrize("cfg", [
     dict(n_q_heads=32, n_kv_heads=8, ctx=[8192], n_q=[32]),
     dict(n_q_heads=28, n_kv_heads=4, ctx=[6720], n_q=[64]),
     dict(n_q_heads=32, n_kv_heads=8, ctx=[16896] * 8, n_q=[128] * 8),
     dict(n_q_heads=32, n_kv_heads=8, ctx=[0, 5, 1000, 77], n_q=[16, 0, 255, 1]),
     dict(n_q_heads=4, n_kv_heads=2, ctx=[144], n_q=[16], head_dim=64, dtype="f32"),
-])
+] + _random_prefill_cases(24))
 def test_prefill_plan_covers_every_row_and_kv_exactly_once(cfg):
     cfg = dict(cfg)
     ctx, n_q = cfg.pop("ctx"), cfg.pop("n_q")
