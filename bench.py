@@ -39,6 +39,7 @@ def make_workload(name):
     return {
         "llama_8k": lambda: W.llama_8k(),
         "llama_8k_decode": lambda: W.llama_8k_decode(),
+        "llama_8k_pruned": lambda: W.llama_8k_pruned(),                     # packets pruned offline, per layer (Sec. 5.4)
         "llama_k5": lambda: W.llama_k5(),
         "qwen_k20": lambda: W.qwen_k20(),
         "llama_long_b8": lambda: W.llama_long_b8(n_layers=4),
@@ -56,6 +57,8 @@ def cpu_baseline(w, sample_layers):
     import oracle
     f = oracle.inv_freq(w.rope_base, w.head_dim)
     rq = w.requests[0]
+    if w.prune is not None:
+        return cpu_baseline_pruned(w, sample_layers, f)
     pk, pv = [], []
     for p in rq.packet_ids:
         k, v = w.packet_kv(p, layers=sample_layers)
@@ -79,6 +82,36 @@ def cpu_baseline(w, sample_layers):
                    (t2 - t1) * 1e6 / sample_layers))
 
 
+def cpu_baseline_pruned(w, sample_layers, f):
+    """The same for a pruned workload: the oracle composes and attends layer by layer."""
+    import numpy as np
+    import kvp_workloads as W
+    import oracle
+    rq = w.requests[0]
+    spans = [int(w.packet_lens[p]) for p in rq.packet_ids]
+    kv = [tuple(W.to_numpy(x) for x in w.packet_kv(p, layers=sample_layers)) for p in rq.packet_ids]
+    ins = []
+    for l in range(sample_layers):
+        keep = [w.kept_rows(p, l) for p in rq.packet_ids]
+        ins.append(([np.ascontiguousarray(k[l][:, s_]) for (k, _), s_ in zip(kv, keep)],
+                    [np.ascontiguousarray(v[l][:, s_]) for (_, v), s_ in zip(kv, keep)],
+                    tuple(W.to_numpy(x) for x in w.query(0, l))))
+    t_asm = t_pre = 0.0
+    for ks, vs, (q, kn, vn) in ins:
+        t0 = time.perf_counter()
+        ko, vo, rows, pos_end = oracle.assemble_layer_spans(w.dtype, ks, vs, spans, f, rq.base_pos,
+                                                            t_cap=sum(k.shape[1] for k in ks) + rq.n_q)
+        t1 = time.perf_counter()
+        oracle.query_prefill_at(w.dtype, q, kn, vn, f, rows, pos_end, ko, vo)
+        t2 = time.perf_counter()
+        t_asm += t1 - t0
+        t_pre += t2 - t1
+    return dict(value=(t_asm + t_pre) * 1e6 / sample_layers, unit="us/layer", cores=oracle.num_threads(),
+                kind="oracle",
+                sample="request 0, %d of %d layers of %s (assemble %.0f us/layer, prefill %.0f us/layer)"
+                % (sample_layers, w.n_layers, w.name, t_asm * 1e6 / sample_layers, t_pre * 1e6 / sample_layers))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -99,6 +132,8 @@ def main():
                          "memory, read over PCIe at every assembly (the paper's tier; reported apart)")
     ap.add_argument("--pipeline", action="store_true",
                     help="assemble layer by layer on a second stream, under the previous layer's prefill")
+    ap.add_argument("--layout", default="", choices=["", "contiguous", "paged"],
+                    help="cache layout (default: the workload's own); paged uses 16-row blocks in a seeded random order")
     ap.add_argument("--per-request", action="store_true",
                     help="batched workloads: also time every request alone (p50 / p99 latency)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -126,7 +161,13 @@ def main():
     w.name = args.workload
     if args.layers > 0:
         w.n_layers = min(w.n_layers, args.layers)
+    if args.layout:
+        w.paged = args.layout == "paged"
     n_req = len(w.requests)
+    if w.prune is not None and args.path == "packets":
+        print("bench.py: the in-place path reads whole packets only; run %s with --path cache" % w.name,
+              file=sys.stderr)
+        sys.exit(2)
     store = build_store(w, kvp, dev, packets=list(range(len(w.packet_lens)))
                         if len(w.packet_lens) <= 256 and args.store == "device" else None, arena=args.store,
                         progress=lambda i, n: print("store: packet %d of %d" % (i, n), file=sys.stderr, flush=True))
@@ -219,12 +260,15 @@ def main():
 
     # algorithmic bytes / flops
     tok_bytes = w.kv_bytes_per_token_layer()
-    T = sum(c - rq.base_pos for c, rq in zip(ctx, w.requests))
-    asm_bytes = 2.0 * T * tok_bytes * w.n_layers                      # read + write every K/V row
-    pre_bytes = sum((c + rq.n_q) * tok_bytes for c, rq in zip(ctx, w.requests))       # per layer
+    # rows[l][r]: context rows of request r in layer l (the same in every layer unless pruned)
+    rows = [[w.layer_rows(r, l) for r in range(n_req)] for l in range(w.n_layers if w.prune else 1)]
+    if not w.prune:
+        rows = rows * w.n_layers
+    asm_bytes = 2.0 * tok_bytes * sum(c - rq.base_pos for rl in rows for c, rq in zip(rl, w.requests))  # read + write every K/V row
+    pre_bytes = sum((c + rq.n_q) * tok_bytes for rl in rows for c, rq in zip(rl, w.requests)) / w.n_layers   # per layer
     pre_flops = sum(4.0 * rq.n_q * c * w.n_q_heads * w.head_dim
                     + 2.0 * rq.n_q * rq.n_q * w.n_q_heads * w.head_dim
-                    for c, rq in zip(ctx, w.requests))                                 # per layer
+                    for rl in rows for c, rq in zip(rl, w.requests)) / w.n_layers                           # per layer
     if pipelined:  # the two overlap: only the whole step is observable
         asm_ms, pre_ms = ms_per_step, ms_per_step
     asm_gbs = asm_bytes / (max(asm_ms, 1e-6) * 1e-3) / 1e9
@@ -275,7 +319,7 @@ def main():
                            "unit": "GB/s", "frac": store_bytes / (ms_per_step * 1e-3) / 1e9 / PCIE_PEAK_GBS,
                            "traffic": None, "bytes_per_step": store_bytes}
     total_rows = sum(ctx) + tot_q
-    res["tokens_per_s"] = total_rows * w.n_layers / (ms_per_step * 1e-3) / w.n_layers  # context + query rows per second
+    res["tokens_per_s"] = total_rows / (ms_per_step * 1e-3)  # context + query positions per second
     if n_req > 1 and args.per_request:
         # every request issued alone, back to back (closed loop): wall-clock latency of its
         # kvp_assemble + kvp_query_prefill over the workload's layers

@@ -117,6 +117,7 @@ class Workload:
     requests: list = field(default_factory=list)
     paged: bool = False
     block_size: int = 16
+    prune: tuple = None       # (lo, hi): every (packet, layer) loses a seeded fraction in [lo, hi] of its rows
 
     @property
     def torch_dtype(self):
@@ -129,6 +130,24 @@ class Workload:
     def ctx_len(self, r):
         rq = self.requests[r]
         return rq.base_pos + int(sum(int(self.packet_lens[p]) for p in rq.packet_ids))
+
+    def kept_rows(self, pid, layer):
+        """Sorted rows of packet ``pid`` that a pruning pass kept in ``layer`` (a different,
+        unstructured subset per layer), or None when the workload is not pruned."""
+        if self.prune is None:
+            return None
+        n = int(self.packet_lens[pid])
+        rng = np.random.default_rng([self.seed, 7, int(pid), int(layer)])
+        n_keep = n - int(round(n * rng.uniform(*self.prune)))
+        return np.sort(rng.choice(n, size=n_keep, replace=False))
+
+    def layer_rows(self, r, layer):
+        """Rows of request ``r``'s context in ``layer`` of the composed cache (= ctx_len(r)
+        unless the workload is pruned)."""
+        if self.prune is None:
+            return self.ctx_len(r)
+        rq = self.requests[r]
+        return rq.base_pos + int(sum(len(self.kept_rows(p, layer)) for p in rq.packet_ids))
 
     def kv_bytes_per_token_layer(self):
         return 2 * self.n_kv_heads * self.head_dim * self.elem_bytes
@@ -221,6 +240,14 @@ def llama_8k(seed=1008, n_layers=32, n_packets=64, n_q=32, name="llama_8k"):
     ids = [int(x) for x in rng.choice(n_packets, size=16, replace=False)]
     return Workload(name, "bf16", n_layers, 32, 8, 128, 5.0e5, 8, 8, seed, 0.5, lens,
                     [Request(ids, n_q)])
+
+
+def llama_8k_pruned(seed=1009, n_layers=32, n_packets=64, rates=(0.1, 0.5)):
+    """The headline point with every packet pruned offline: each (packet, layer) keeps its own
+    random subset of rows, 10 % to 50 % removed (the range of compression rates of Sec. 5.4)."""
+    w = llama_8k(seed, n_layers, n_packets, name="llama_8k_pruned")
+    w.prune = tuple(rates)
+    return w
 
 
 def llama_8k_decode(seed=1008, n_layers=32, n_packets=64):

@@ -44,23 +44,52 @@ __device__ __forceinline__ uint4 pack(const float (&x)[8])
 
 constexpr int ASM_THREADS = 256;
 
-// Tile descriptor of this workgroup: from the device tile list, or derived from the packet
-// list carried in the kernel arguments (wave-uniform scalar scan).
-__device__ __forceinline__ AsmTile fetch_tile(const AsmArgs &a)
+// The tile of this workgroup: which rows of which segment, from where, to where.
+struct Tile {
+    int64_t k_off, v_ahead;  // elements: first K row of the tile; the V row is v_ahead further on
+    int n_tok, dst_row, pos, req, layer, head;
+};
+
+__device__ __forceinline__ Tile fetch_tile(const AsmArgs &a, int d)
 {
     const int b = (int)blockIdx.x;
-    if (a.tiles) return a.tiles[b];
-    int j = 0;
-    while (j + 1 < a.n_inline && a.inline_pk[j + 1].tile0 <= b) ++j;
-    const AsmPacket p = a.inline_pk[j];
-    AsmTile t;
-    t.src_base = p.src_base;
-    t.stride = p.stride;
-    t.tok0 = (b - p.tile0) * a.tile_rows;
-    t.n_tok = p.n_pkt - t.tok0 < a.tile_rows ? p.n_pkt - t.tok0 : a.tile_rows;
-    t.dst_row = p.pos + t.tok0;
-    t.pos = p.pos;
-    t.req = p.req;
+    AsmSeg g;
+    if (a.segs) {
+        // wave-uniform: scan the pivots in the arguments, then bisect one stretch of the list
+        int i = 0;
+        while (i + 1 < a.n_pivots && a.pivot[i + 1] <= b) ++i;
+        int lo = i * a.pivot_step;
+        int hi = lo + a.pivot_step < a.n_segs ? lo + a.pivot_step - 1 : a.n_segs - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (a.segs[mid].tile0 <= b) lo = mid;
+            else hi = mid - 1;
+        }
+        g = a.segs[lo];
+    } else {
+        int j = 0;
+        while (j + 1 < a.n_segs && a.inline_seg[j + 1].tile0 <= b) ++j;
+        g = a.inline_seg[j];
+    }
+    Tile t;
+    const int tok0 = (b - g.tile0) * a.tile_rows;
+    t.n_tok = g.n_rows - tok0 < a.tile_rows ? g.n_rows - tok0 : a.tile_rows;
+    t.dst_row = g.dst_row + tok0;
+    t.pos = g.pos;
+    t.req = g.req;
+    const int lh = (int)blockIdx.y;
+    const bool own_layer = g.stride < 0;  // compressed packet: the blob is laid out layer by layer
+    const int stride = own_layer ? -g.stride : g.stride;
+    t.v_ahead = (int64_t)(own_layer ? 1 : a.n_layers_total) * a.n_kv * stride * d;
+    if (a.layered) {
+        t.layer = g.layer;
+        t.head = lh;
+        t.k_off = g.src_base + ((int64_t)t.head * stride + tok0) * d;
+    } else {
+        t.layer = a.layer_begin + lh / a.n_kv;
+        t.head = lh % a.n_kv;
+        t.k_off = g.src_base + (((int64_t)t.layer * a.n_kv + t.head) * stride + tok0) * d;
+    }
     return t;
 }
 
@@ -98,19 +127,11 @@ __global__ __launch_bounds__(ASM_THREADS) void assemble_vec_kernel(AsmArgs a)
     constexpr int VPASS = (ROWS + VROWS - 1) / VROWS;
     static_assert(CPR >= 1 && ASM_THREADS % CPR == 0 && KPASS >= 1 && VPASS >= 1, "shape");
 
-    const AsmTile tile = fetch_tile(a);
-    const int lh = (int)blockIdx.y;
-    const int layer = a.layer_begin + lh / a.n_kv;
-    const int head = lh % a.n_kv;
+    const Tile tile = fetch_tile(a, D);
     const int tid = threadIdx.x;
-
-    const T *arena = (const T *)a.arena;
-    // stride < 0: a compressed packet, src_base is this layer's own [K: Hkv x rows][V: Hkv x rows]
-    const bool per_layer = tile.stride < 0;
-    const int stride = per_layer ? -tile.stride : tile.stride;
-    const int64_t blob = (int64_t)(per_layer ? 1 : a.n_layers_total) * a.n_kv * stride * D;
-    const T *ksrc = arena + tile.src_base + (((int64_t)(per_layer ? 0 : layer) * a.n_kv + head) * stride + tile.tok0) * D;
-    const T *vsrc = ksrc + blob;
+    const int layer = tile.layer, head = tile.head;
+    const T *ksrc = (const T *)a.arena + tile.k_off;
+    const T *vsrc = ksrc + tile.v_ahead;
     T *kdst = (T *)a.cache.k;
     T *vdst = (T *)a.cache.v;
 
@@ -172,17 +193,11 @@ __global__ __launch_bounds__(ASM_THREADS) void assemble_vec_kernel(AsmArgs a)
 template <typename T>
 __global__ __launch_bounds__(ASM_THREADS) void assemble_scalar_kernel(AsmArgs a)
 {
-    const AsmTile tile = fetch_tile(a);
-    const int lh = (int)blockIdx.y;
-    const int layer = a.layer_begin + lh / a.n_kv;
-    const int head = lh % a.n_kv;
     const int d = a.d, half = d / 2;
-    const T *arena = (const T *)a.arena;
-    const bool per_layer = tile.stride < 0;  // compressed packet: see the vector kernel
-    const int stride = per_layer ? -tile.stride : tile.stride;
-    const int64_t blob = (int64_t)(per_layer ? 1 : a.n_layers_total) * a.n_kv * stride * d;
-    const T *ksrc = arena + tile.src_base + (((int64_t)(per_layer ? 0 : layer) * a.n_kv + head) * stride + tile.tok0) * d;
-    const T *vsrc = ksrc + blob;
+    const Tile tile = fetch_tile(a, d);
+    const int layer = tile.layer, head = tile.head;
+    const T *ksrc = (const T *)a.arena + tile.k_off;
+    const T *vsrc = ksrc + tile.v_ahead;
     T *kdst = (T *)a.cache.k;
     T *vdst = (T *)a.cache.v;
     const float2 *cs = a.cs + (int64_t)tile.pos * half;
@@ -230,6 +245,26 @@ int launch_assemble(int dtype, const AsmArgs &a, int n_layers_launch, void *stre
         else if (a.d == 256) launch_vec<float, 256>(a, grid, st, nt);
         else hipLaunchKernelGGL((assemble_scalar_kernel<float>), grid, block, 0, st, a);
     }
+    return (int)hipGetLastError();
+}
+
+// A call's plan goes from its pinned host buffer to its device twin through this kernel
+// (the device reads host memory directly): next to the launches that follow it on the stream
+// it costs a few microseconds, where a copy-engine transfer and its hand-over to the compute
+// queue cost some twenty.
+__global__ __launch_bounds__(256) void plan_upload_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, int n16)
+{
+    const int i = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (i < n16) dst[i] = src[i];
+}
+
+int launch_plan_upload(const void *host, void *dev, uint64_t bytes, void *stream)
+{
+    const uint64_t n16 = (bytes + 15) / 16;  // plan buffers are sized in multiples of 4 KB
+    if (n16 == 0) return 0;
+    if (n16 > 0x7fffffffull || (((uintptr_t)host | (uintptr_t)dev) & 15)) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(plan_upload_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       (const uint4 *)host, (uint4 *)dev, (int)n16);
     return (int)hipGetLastError();
 }
 

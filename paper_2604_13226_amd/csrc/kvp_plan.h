@@ -5,19 +5,27 @@
 
 namespace kvp {
 
-// One tile of the gather: up to ASM_TILE_ROWS consecutive rows of one retrieved packet.
-// The same tile list serves every (layer, kv head): blockIdx.y selects those.
-struct AsmTile {
-    int64_t src_base;  // element offset of the packet's K blob in the arena
-    int32_t stride;    // rows between consecutive (layer, head) slices of the blob; negative: a compressed
-                       // packet, src_base is one layer's own part and -stride its rows in that layer
-    int32_t tok0;      // first packet row of this tile
-    int32_t n_tok;     // rows in this tile
-    int32_t dst_row;   // cache row (absolute position) of tok0
+// The gather's plan is a list of segments: runs of rows of one retrieved packet that land in
+// consecutive cache rows.  A workgroup takes one tile (up to AsmArgs::tile_rows rows) of one
+// segment and finds it from blockIdx.x by the segments' cumulative tile counts.
+//  - Whole packets: a segment is a packet, the same list serves every (layer, kv head), and
+//    blockIdx.y selects those.
+//  - Layered lists (requests with compressed packets, Sec. 5.4): the rows differ from layer to
+//    layer, so a segment is one packet's rows in one layer and blockIdx.y selects the kv head.
+struct AsmSeg {
+    int64_t src_base;  // element offset in the arena: whole packets: the packet's K blob;
+                       // layered: the first K row of kv head 0 in `layer`
+    int32_t stride;    // rows between consecutive (layer, head) slices of the blob; negative (layered
+                       // only): a compressed packet, -stride = the rows its layer kept, V follows that layer's K
+    int32_t n_rows;    // rows of the segment (> 0)
+    int32_t dst_row;   // cache row of the segment's first row
     int32_t pos;       // Delta_j: rotation offset of the packet (Eq. 1)
     int32_t req;       // request index
+    int32_t layer;     // layered lists only
+    int32_t tile0;     // index of the segment's first tile
+    int32_t pad;
 };
-static_assert(sizeof(AsmTile) == 32, "AsmTile is 32 bytes");
+static_assert(sizeof(AsmSeg) == 40, "AsmSeg is 40 bytes");
 
 constexpr int ASM_TILE_ROWS_MAX = 64;  // tiles hold 16, 32 or 64 rows
 
@@ -29,30 +37,26 @@ struct CacheView {
     int32_t layout, t_cap, n_blocks, block_shift, max_blocks;
 };
 
-// Small requests carry their packet list inside the kernel arguments (no plan upload):
-// the kernel finds its tile's packet by a scan over the cumulative tile counts.
-struct AsmPacket {
-    int64_t src_base;  // element offset of the packet's K blob in the arena
-    int32_t n_pkt;     // rows of the packet
-    int32_t stride;    // rows between consecutive (layer, head) slices of the blob; negative: a compressed
-                       // packet, src_base is one layer's own part and -stride its rows in that layer
-    int32_t pos;       // Delta_j = cache row of the packet's first row
-    int32_t req;
-    int32_t tile0;     // index of the packet's first tile
-    int32_t pad;
-};
-constexpr int ASM_INLINE_PACKETS = 96;
+// Short lists ride in the kernel arguments (nothing is uploaded) and are scanned linearly.
+// Longer ones are uploaded; the arguments then carry the first tile of every pivot_step-th
+// segment, so the search is a scan of at most ASM_PIVOTS argument words and a bisection of
+// pivot_step list entries.
+constexpr int ASM_INLINE_SEGS = 80;
+constexpr int ASM_PIVOTS = 32;
 
 struct AsmArgs {
     const void *arena;
-    const float2 *cs;      // [max_positions][d/2] (cos, sin)
-    const AsmTile *tiles;  // device tile list, or nullptr: use `inline_pk`
+    const float2 *cs;    // [max_positions][d/2] (cos, sin)
+    const AsmSeg *segs;  // device list, or nullptr: use `inline_seg`
     CacheView cache;
     int32_t n_tiles, layer_begin, n_layers_total, n_kv, d;
     int32_t tile_rows, nontemporal;
-    int32_t n_inline;
-    AsmPacket inline_pk[ASM_INLINE_PACKETS];
+    int32_t layered;  // segments name their own layer; blockIdx.y = kv head
+    int32_t n_segs, n_pivots, pivot_step;
+    int32_t pivot[ASM_PIVOTS];
+    AsmSeg inline_seg[ASM_INLINE_SEGS];
 };
+static_assert(sizeof(AsmArgs) <= 4096, "kernel arguments are limited to 4 KB");
 
 // ---- query prefill -------------------------------------------------------------
 struct ReqMeta {
@@ -136,6 +140,7 @@ struct AppendArgs {
 
 // launchers (defined next to their kernels)
 int launch_assemble(int dtype, const AsmArgs &a, int n_layers_launch, void *stream);
+int launch_plan_upload(const void *host, void *dev, uint64_t bytes, void *stream);  // host: pinned, device-mapped
 int launch_append(int dtype, const AppendArgs &a, void *stream);
 int launch_attention(int dtype, const AttnArgs &a, int kernel_kind, void *stream);
 int launch_combine(int dtype, const AttnArgs &a, void *stream);

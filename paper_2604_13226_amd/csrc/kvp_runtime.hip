@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <deque>
 #include <string>
 #include <thread>
 #include <unordered_map>
@@ -35,17 +36,67 @@ struct PacketRec {
     bool compressed() const { return !rows.empty(); }
 };
 
-// Ring of pinned-host / device twin buffers that carry one call's plan each.  A slot is
-// reused only after the work that read it has finished (event recorded behind it).
+// A pinned-host / device twin buffer that carries one call's plan.  It is rewritten only
+// after the work that read it has finished (event recorded behind that work).
+struct PlanSlot {
+    char *host = nullptr;
+    char *dev = nullptr;
+    uint64_t cap = 0;
+    hipEvent_t ev = nullptr;
+    bool pending = false;
+
+    int ensure(uint64_t bytes, bool dry)
+    {
+        if (dry) {
+            if (cap < bytes) {
+                free(host);
+                host = (char *)malloc(bytes);
+                cap = bytes;
+            }
+            return 0;
+        }
+        if (pending) {
+            hipError_t e = hipEventSynchronize(ev);
+            if (e != hipSuccess) return (int)e;
+            pending = false;
+        }
+        if (!ev) {
+            hipError_t e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+            if (e != hipSuccess) return (int)e;
+        }
+        if (cap < bytes) {
+            uint64_t want = std::max<uint64_t>(align_up(bytes, 4096), 1 << 16);
+            if (host) (void)hipHostFree(host);
+            if (dev) (void)hipFree(dev);
+            host = dev = nullptr;
+            cap = 0;
+            hipError_t e = hipHostMalloc((void **)&host, want, hipHostMallocDefault);
+            if (e != hipSuccess) return (int)e;
+            e = hipMalloc((void **)&dev, want);
+            if (e != hipSuccess) return (int)e;
+            cap = want;
+        }
+        return 0;
+    }
+    void release(bool dry)
+    {
+        if (dry) {
+            free(host);
+        } else {
+            if (pending) (void)hipEventSynchronize(ev);
+            if (host) (void)hipHostFree(host);
+            if (dev) (void)hipFree(dev);
+            if (ev) (void)hipEventDestroy(ev);
+        }
+        *this = PlanSlot();
+    }
+};
+
+// Ring of plan buffers for calls whose plan changes every time.
 struct PlanRing {
     static constexpr int SLOTS = 8;
-    struct Slot {
-        char *host = nullptr;
-        char *dev = nullptr;
-        uint64_t cap = 0;
-        hipEvent_t ev = nullptr;
-        bool pending = false;
-    } slot[SLOTS];
+    typedef PlanSlot Slot;
+    Slot slot[SLOTS];
     int next = 0;
     bool dry = false;
 
@@ -53,52 +104,12 @@ struct PlanRing {
     {
         Slot &s = slot[next];
         next = (next + 1) % SLOTS;
-        if (dry) {
-            if (s.cap < bytes) {
-                free(s.host);
-                s.host = (char *)malloc(bytes);
-                s.cap = bytes;
-            }
-            *out = &s;
-            return 0;
-        }
-        if (s.pending) {
-            hipError_t e = hipEventSynchronize(s.ev);
-            if (e != hipSuccess) return (int)e;
-            s.pending = false;
-        }
-        if (!s.ev) {
-            hipError_t e = hipEventCreateWithFlags(&s.ev, hipEventDisableTiming);
-            if (e != hipSuccess) return (int)e;
-        }
-        if (s.cap < bytes) {
-            uint64_t cap = std::max<uint64_t>(align_up(bytes, 4096), 1 << 16);
-            if (s.host) (void)hipHostFree(s.host);
-            if (s.dev) (void)hipFree(s.dev);
-            s.host = s.dev = nullptr;
-            s.cap = 0;
-            hipError_t e = hipHostMalloc((void **)&s.host, cap, hipHostMallocDefault);
-            if (e != hipSuccess) return (int)e;
-            e = hipMalloc((void **)&s.dev, cap);
-            if (e != hipSuccess) return (int)e;
-            s.cap = cap;
-        }
         *out = &s;
-        return 0;
+        return s.ensure(bytes, dry);
     }
     void release()
     {
-        for (auto &s : slot) {
-            if (dry) {
-                free(s.host);
-            } else {
-                if (s.pending) (void)hipEventSynchronize(s.ev);
-                if (s.host) (void)hipHostFree(s.host);
-                if (s.dev) (void)hipFree(s.dev);
-                if (s.ev) (void)hipEventDestroy(s.ev);
-            }
-            s = Slot();
-        }
+        for (auto &s : slot) s.release(dry);
     }
 };
 
@@ -115,14 +126,19 @@ struct kvp_store {
     void *arena_dev = nullptr;  // the arena as the kernels address it
     bool arena_host = false;    // the arena is pinned host memory mapped into the device (read over PCIe)
     PlanRing ring;          // plans of kvp_assemble
-    PlanRing ring_prefill;  // plans of kvp_query_prefill
+    PlanRing ring_prefill;  // plans of kvp_prefill_packets
     // The prefill plan depends only on the request geometry (context lengths, query
     // offsets, block table), which is the same for every layer of a forward pass: the
-    // uploaded plan is kept and reused while that geometry does not change.
+    // uploaded plan is kept and reused while that geometry does not change.  With compressed
+    // packets every layer has its own row counts, hence its own plan: kvp_query_prefill keeps
+    // a set of plans (one more than the layers, at least PlanRing::SLOTS), each in a buffer
+    // of its own, replaced least recently used first.
     struct PrefillCached {
         bool valid = false;
         std::vector<int32_t> sig;
-        PlanRing::Slot *slot = nullptr;
+        uint64_t sig_hash = 0, last_use = 0;
+        PlanSlot own;               // kvp_query_prefill: the entry's own buffer
+        PlanSlot *slot = nullptr;   // the buffer the plan is in
         void *stream = nullptr;
         const ReqMeta *reqs_dev = nullptr;
         const int32_t *row_req_dev = nullptr, *bt_dev = nullptr;
@@ -132,15 +148,20 @@ struct kvp_store {
         int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0, part_stride = 1, max_group_rows = 0;
         bool any_split = false;
         uint64_t need = 0;
-    } pf, pk;  // pf: kvp_query_prefill, pk: kvp_prefill_packets
+    } pk;                           // kvp_prefill_packets
+    std::deque<PrefillCached> pf_set;  // kvp_query_prefill
+    uint64_t pf_clock = 0;
     std::vector<int32_t> sig_scratch;
     std::string err;
-    std::vector<int64_t> dbg_asm, dbg_attn;
+    std::vector<AsmSeg> dbg_segs;  // the last gather plan (kvp_debug_last_plan)
+    bool dbg_layered = false;
+    std::vector<int64_t> dbg_attn;
     bool dry = false;
     int n_cu = 256;
     int force_generic = 0;
     int target_items = 0;  // 0: three quarters of the CU count (measured optimum at 8K context)
     int asm_tile_rows = 32, asm_nontemporal = 0;
+    int plan_copy_engine = 0;  // test knob: plans go up with hipMemcpyAsync instead of the upload kernel
     int force_bm = 0;  // test knob: row-block size of the MFMA attention kernel
     int force_split_in_wg = -1;  // test knob: 0 / 1 forces the 4-wave / 8-wave-in-two-groups shape of 128-row blocks
     size_t esize = 2;
@@ -278,16 +299,102 @@ struct PlanWriter {
     }
 };
 
+// Sends a plan from its slot's host buffer to the device twin, in stream order.
+int upload_plan(kvp_store *s, PlanSlot *slot, uint64_t bytes, void *hip_stream)
+{
+    if (s->plan_copy_engine) {
+        HIP_TRY(s, hipMemcpyAsync(slot->dev, slot->host, bytes, hipMemcpyHostToDevice, (hipStream_t)hip_stream));
+        return KVP_OK;
+    }
+    int e = launch_plan_upload(slot->host, slot->dev, bytes, hip_stream);
+    if (e) return hip_fail(s, (hipError_t)e, "plan upload");
+    return KVP_OK;
+}
+
+// Tiles of `rows` rows at the store's tile size.
+int tiles_of(const kvp_store *s, int rows) { return (rows + s->asm_tile_rows - 1) / s->asm_tile_rows; }
+
+// Uploads a gather plan (segment list, block table) if it does not fit the kernel arguments,
+// and launches the gather: grid = (tiles, layers x kv heads), or (tiles, kv heads) for a
+// layered list.
+int run_gather(kvp_store *s, const std::vector<AsmSeg> &segs, int64_t n_tiles, bool layered, int layer_begin,
+               int n_layers_launch, const kvp_cache_t *cache, const CacheCheck &cc, int n_req,
+               const std::vector<int> &first_blk, const std::vector<int> &n_blk, void *hip_stream)
+{
+    const kvp_config_t &g = s->cfg;
+    if (n_tiles > 0x7fffffff) return fail(s, KVP_E_CAPACITY, "%lld gather tiles in one call", (long long)n_tiles);
+    int bt_stride = 0;
+    for (int r = 0; r < n_req; ++r) bt_stride = std::max(bt_stride, n_blk[r]);
+    const bool inline_plan = (int)segs.size() <= ASM_INLINE_SEGS && cache->layout == KVP_CONTIG;
+    const AsmSeg *segs_dev = nullptr;
+    const int32_t *bt_dev = nullptr;
+    PlanRing::Slot *slot = nullptr;
+    uint64_t upload = 0;
+    if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
+    if (!inline_plan) {
+        const uint64_t bytes = align_up(segs.size() * sizeof(AsmSeg), 64) + (uint64_t)n_req * bt_stride * 4 + 256;
+        int hrc = s->ring.acquire(bytes, &slot);
+        if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
+        PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
+        AsmSeg *sh = w.put<AsmSeg>(segs.size(), &segs_dev);
+        if (!segs.empty()) memcpy(sh, segs.data(), segs.size() * sizeof(AsmSeg));
+        if (cache->layout == KVP_PAGED && bt_stride > 0) {
+            int32_t *bh = w.put<int32_t>((uint64_t)n_req * bt_stride, &bt_dev);
+            int rc = compact_block_table(s, cache, n_req, first_blk, n_blk, bt_stride, bh);
+            if (rc) return rc;
+        }
+        upload = w.off;
+    }
+    s->dbg_segs = segs;
+    s->dbg_layered = layered;
+    if (s->dry || n_tiles == 0 || n_layers_launch <= 0) return KVP_OK;
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    AsmArgs a;
+    a.arena = s->arena_dev;
+    a.cs = s->cs_dev;
+    a.segs = nullptr;
+    a.n_segs = (int)segs.size();
+    a.n_pivots = 0;
+    a.pivot_step = 1;
+    a.layered = layered ? 1 : 0;
+    if (inline_plan) {
+        for (size_t i = 0; i < segs.size(); ++i) a.inline_seg[i] = segs[i];
+    } else {
+        int urc = upload_plan(s, slot, upload, hip_stream);
+        if (urc) return urc;
+        a.segs = segs_dev;
+        a.pivot_step = ((int)segs.size() + ASM_PIVOTS - 1) / ASM_PIVOTS;
+        for (int i = 0; i * a.pivot_step < (int)segs.size(); ++i) a.pivot[a.n_pivots++] = segs[(size_t)i * a.pivot_step].tile0;
+    }
+    a.cache = make_view(s, cache, cc.shift, bt_dev, bt_stride);
+    a.n_tiles = (int)n_tiles;
+    a.tile_rows = s->asm_tile_rows;
+    a.nontemporal = s->asm_nontemporal;
+    a.layer_begin = layer_begin;
+    a.n_layers_total = g.n_layers;
+    a.n_kv = g.n_kv_heads;
+    a.d = g.head_dim;
+    int e = launch_assemble(g.dtype, a, layered ? 1 : n_layers_launch, hip_stream);
+    if (e) return hip_fail(s, (hipError_t)e, "assemble launch");
+    if (slot) {
+        HIP_TRY(s, hipEventRecord(slot->ev, st));
+        slot->pending = true;
+    }
+    return KVP_OK;
+}
+
 // kvp_assemble for requests with compressed packets (Sec. 5.4): positions advance by the
-// packets' spans, rows by what each layer kept, so every layer has its own tile list and its
-// own launch (one plan upload for all of them).
+// packets' spans, rows by what each layer kept, so every (packet, layer) is a segment of its
+// own, and one launch covers (tile, kv head).
 int assemble_compressed(kvp_store *s, const kvp_request_t *reqs, int n_req, int layer_begin, int layer_end,
                         kvp_cache_t *cache, const CacheCheck &cc, void *hip_stream)
 {
     const kvp_config_t &g = s->cfg;
     if (!cache->ctx_rows) return fail(s, KVP_E_INVAL, "compressed packets need kvp_cache_t.ctx_rows");
     const int n_l = layer_end - layer_begin;
-    std::vector<std::vector<AsmTile>> tiles(std::max(n_l, 0));
+    std::vector<AsmSeg> segs;
+    int64_t n_tiles = 0;
     std::vector<int> pos_end(n_req), first_blk(n_req, 0), n_blk(n_req, 0);
     std::vector<int64_t> rows_end((size_t)n_req * std::max(n_l, 1), 0);
     for (int r = 0; r < n_req; ++r) {
@@ -304,18 +411,20 @@ int assemble_compressed(kvp_store *s, const kvp_request_t *reqs, int n_req, int 
             for (int li = 0; li < n_l; ++li) {
                 const int l = layer_begin + li;
                 const int n = p.compressed() ? p.rows[l] : p.n_tokens;
-                for (int t0 = 0; t0 < n; t0 += s->asm_tile_rows) {
-                    AsmTile t;
-                    // a negative stride marks a blob laid out layer by layer
-                    t.src_base = p.compressed() ? p.layer_off[l] : p.elem_off;
-                    t.stride = p.compressed() ? -std::max(n, 1) : p.stride;
-                    t.tok0 = t0;
-                    t.n_tok = std::min(s->asm_tile_rows, n - t0);
-                    t.dst_row = (int32_t)row[li] + t0;
-                    t.pos = (int32_t)pos;
-                    t.req = r;
-                    tiles[li].push_back(t);
-                }
+                if (n == 0) continue;
+                AsmSeg t;
+                // first K row of head 0 in this layer; a negative stride marks a blob laid out layer by layer
+                t.src_base = p.compressed() ? p.layer_off[l] : p.elem_off + (int64_t)l * g.n_kv_heads * p.stride * g.head_dim;
+                t.stride = p.compressed() ? -n : p.stride;
+                t.n_rows = n;
+                t.dst_row = (int32_t)row[li];
+                t.pos = (int32_t)pos;
+                t.req = r;
+                t.layer = l;
+                t.tile0 = (int32_t)n_tiles;
+                t.pad = 0;
+                segs.push_back(t);
+                n_tiles += tiles_of(s, n);
                 row[li] += n;
             }
             pos += p.n_tokens;
@@ -331,66 +440,8 @@ int assemble_compressed(kvp_store *s, const kvp_request_t *reqs, int n_req, int 
             n_blk[r] = (int)((max_rows - 1) >> cc.shift) + 1;
         }
     }
-    int bt_stride = 0;
-    for (int r = 0; r < n_req; ++r) bt_stride = std::max(bt_stride, n_blk[r]);
-    uint64_t n_tiles_total = 0;
-    for (auto &v : tiles) n_tiles_total += v.size();
-
-    s->dbg_asm.clear();
-    s->dbg_asm.push_back((int64_t)n_tiles_total);
-    for (auto &v : tiles)
-        for (const AsmTile &t : v) {
-            int64_t rowv[8] = {t.src_base, t.stride, t.tok0, t.n_tok, t.dst_row, t.pos, t.req, 0};
-            s->dbg_asm.insert(s->dbg_asm.end(), rowv, rowv + 8);
-        }
-
-    if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
-    if (n_tiles_total > 0) {
-        const uint64_t bytes = align_up(n_tiles_total * sizeof(AsmTile), 64) + (uint64_t)n_req * bt_stride * 4 + 256;
-        PlanRing::Slot *slot = nullptr;
-        int hrc = s->ring.acquire(bytes, &slot);
-        if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
-        PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
-        const AsmTile *tiles_dev = nullptr;
-        const int32_t *bt_dev = nullptr;
-        AsmTile *th = w.put<AsmTile>(n_tiles_total, &tiles_dev);
-        uint64_t at = 0;
-        std::vector<uint64_t> first(n_l);
-        for (int li = 0; li < n_l; ++li) {
-            first[li] = at;
-            if (!tiles[li].empty()) memcpy(th + at, tiles[li].data(), tiles[li].size() * sizeof(AsmTile));
-            at += tiles[li].size();
-        }
-        if (cache->layout == KVP_PAGED && bt_stride > 0) {
-            int32_t *bh = w.put<int32_t>((uint64_t)n_req * bt_stride, &bt_dev);
-            int rc = compact_block_table(s, cache, n_req, first_blk, n_blk, bt_stride, bh);
-            if (rc) return rc;
-        }
-        if (!s->dry) {
-            hipStream_t st = (hipStream_t)hip_stream;
-            HIP_TRY(s, hipMemcpyAsync(slot->dev, slot->host, w.off, hipMemcpyHostToDevice, st));
-            for (int li = 0; li < n_l; ++li) {
-                if (tiles[li].empty()) continue;
-                AsmArgs a;
-                a.arena = s->arena_dev;
-                a.cs = s->cs_dev;
-                a.tiles = tiles_dev + first[li];
-                a.n_inline = 0;
-                a.cache = make_view(s, cache, cc.shift, bt_dev, bt_stride);
-                a.n_tiles = (int)tiles[li].size();
-                a.tile_rows = s->asm_tile_rows;
-                a.nontemporal = s->asm_nontemporal;
-                a.layer_begin = layer_begin + li;
-                a.n_layers_total = g.n_layers;
-                a.n_kv = g.n_kv_heads;
-                a.d = g.head_dim;
-                int e = launch_assemble(g.dtype, a, 1, hip_stream);
-                if (e) return hip_fail(s, (hipError_t)e, "assemble launch");
-            }
-            HIP_TRY(s, hipEventRecord(slot->ev, st));
-            slot->pending = true;
-        }
-    }
+    int rc = run_gather(s, segs, n_tiles, true, layer_begin, n_l, cache, cc, n_req, first_blk, n_blk, hip_stream);
+    if (rc) return rc;
     for (int r = 0; r < n_req; ++r) {
         cache->ctx_len[r] = pos_end[r];
         for (int li = 0; li < n_l; ++li)
@@ -452,6 +503,7 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
     if (tr && (atoi(tr) == 16 || atoi(tr) == 32 || atoi(tr) == 64)) s->asm_tile_rows = atoi(tr);
     const char *nt = getenv("KVP_ASM_NONTEMPORAL");
     if (nt) s->asm_nontemporal = nt[0] == '1';
+    if (const char *pc = getenv("KVP_PLAN_COPY_ENGINE")) s->plan_copy_engine = pc[0] == '1';
     if (const char *fb = getenv("KVP_ATTN_BM")) s->force_bm = atoi(fb);
     if (const char *fd = getenv("KVP_ATTN_SPLIT_IN_WG")) s->force_split_in_wg = atoi(fd) != 0;
     const char *ti = getenv("KVP_ATTN_TARGET_ITEMS");  // test knob: how finely split-KV cuts
@@ -500,10 +552,12 @@ int kvp_store_destroy(kvp_store_t *s)
         (void)hipSetDevice(s->cfg.device);
         s->ring.release();
         s->ring_prefill.release();
+        for (auto &e : s->pf_set) e.own.release(false);
         if (s->cs_dev) (void)hipFree(s->cs_dev);
     } else {
         s->ring.release();
         s->ring_prefill.release();
+        for (auto &e : s->pf_set) e.own.release(true);
     }
     delete s;
     return KVP_OK;
@@ -628,13 +682,12 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
         }
     }
 
-    // offsets Delta_j (Sec. 4.2.1 step 4: realign, then concatenate) and gather tiles
-    std::vector<AsmTile> tiles;
-    std::vector<AsmPacket> packets;
+    // offsets Delta_j (Sec. 4.2.1 step 4: realign, then concatenate): one segment per packet
+    std::vector<AsmSeg> segs;
+    int64_t n_tiles = 0;
     std::vector<int> ctx(n_req), first_blk(n_req, 0), n_blk(n_req, 0);
     for (int r = 0; r < n_req; ++r) {
         const kvp_request_t &q = reqs[r];
-        if (q.k < 0 || (q.k > 0 && !q.packet_ids)) return fail(s, KVP_E_INVAL, "request %d: bad packet list", r);
         if (q.base_pos < 0) return fail(s, KVP_E_INVAL, "request %d: base_pos %d < 0", r, q.base_pos);
         int64_t pos = q.base_pos;
         for (int j = 0; j < q.k; ++j) {
@@ -643,18 +696,8 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
             const PacketRec &p = it->second;
             if (pos + p.n_tokens > g.max_positions)
                 return fail(s, KVP_E_CAPACITY, "request %d: context exceeds max_positions %d", r, g.max_positions);
-            packets.push_back(AsmPacket{p.elem_off, p.n_tokens, p.stride, (int32_t)pos, r, (int32_t)tiles.size(), 0});
-            for (int t0 = 0; t0 < p.n_tokens; t0 += s->asm_tile_rows) {
-                AsmTile t;
-                t.src_base = p.elem_off;
-                t.stride = p.stride;
-                t.tok0 = t0;
-                t.n_tok = std::min(s->asm_tile_rows, p.n_tokens - t0);
-                t.dst_row = (int32_t)pos + t0;
-                t.pos = (int32_t)pos;
-                t.req = r;
-                tiles.push_back(t);
-            }
+            segs.push_back(AsmSeg{p.elem_off, p.stride, p.n_tokens, (int32_t)pos, (int32_t)pos, r, 0, (int32_t)n_tiles, 0});
+            n_tiles += tiles_of(s, p.n_tokens);
             pos += p.n_tokens;
         }
         if (pos > cc.cap_rows) return fail(s, KVP_E_CAPACITY, "request %d: %lld rows do not fit the cache (%lld)", r, (long long)pos, (long long)cc.cap_rows);
@@ -664,69 +707,8 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
             n_blk[r] = (int)((pos - 1) >> cc.shift) + 1;
         }
     }
-    int bt_stride = 0;
-    for (int r = 0; r < n_req; ++r) bt_stride = std::max(bt_stride, n_blk[r]);
-
-    const int n_layers_launch = layer_end - layer_begin;
-    // Few packets and no block table: the packet list rides in the kernel arguments and
-    // nothing is uploaded.  Otherwise the tile list (and block table) go through a plan slot.
-    const bool inline_plan = (int)packets.size() <= ASM_INLINE_PACKETS && cache->layout == KVP_CONTIG;
-    const AsmTile *tiles_dev = nullptr;
-    const int32_t *bt_dev = nullptr;
-    PlanRing::Slot *slot = nullptr;
-    uint64_t upload = 0;
-    if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
-    if (!inline_plan) {
-        const uint64_t bytes = align_up(tiles.size() * sizeof(AsmTile), 64) + (uint64_t)n_req * bt_stride * 4 + 256;
-        int hrc = s->ring.acquire(bytes, &slot);
-        if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
-        PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
-        AsmTile *th = w.put<AsmTile>(tiles.size(), &tiles_dev);
-        if (!tiles.empty()) memcpy(th, tiles.data(), tiles.size() * sizeof(AsmTile));
-        if (cache->layout == KVP_PAGED && bt_stride > 0) {
-            int32_t *bh = w.put<int32_t>((uint64_t)n_req * bt_stride, &bt_dev);
-            rc = compact_block_table(s, cache, n_req, first_blk, n_blk, bt_stride, bh);
-            if (rc) return rc;
-        }
-        upload = w.off;
-    }
-
-    s->dbg_asm.clear();
-    s->dbg_asm.push_back((int64_t)tiles.size());
-    for (const AsmTile &t : tiles) {
-        int64_t row[8] = {t.src_base, t.stride, t.tok0, t.n_tok, t.dst_row, t.pos, t.req, 0};
-        s->dbg_asm.insert(s->dbg_asm.end(), row, row + 8);
-    }
-
-    if (!s->dry && !tiles.empty() && n_layers_launch > 0) {
-        hipStream_t st = (hipStream_t)hip_stream;
-        AsmArgs a;
-        a.arena = s->arena_dev;
-        a.cs = s->cs_dev;
-        a.tiles = nullptr;
-        a.n_inline = 0;
-        if (inline_plan) {
-            a.n_inline = (int)packets.size();
-            for (size_t i = 0; i < packets.size(); ++i) a.inline_pk[i] = packets[i];
-        } else {
-            HIP_TRY(s, hipMemcpyAsync(slot->dev, slot->host, upload, hipMemcpyHostToDevice, st));
-            a.tiles = tiles_dev;
-        }
-        a.cache = make_view(s, cache, cc.shift, bt_dev, bt_stride);
-        a.n_tiles = (int)tiles.size();
-        a.tile_rows = s->asm_tile_rows;
-        a.nontemporal = s->asm_nontemporal;
-        a.layer_begin = layer_begin;
-        a.n_layers_total = g.n_layers;
-        a.n_kv = g.n_kv_heads;
-        a.d = g.head_dim;
-        int e = launch_assemble(g.dtype, a, n_layers_launch, hip_stream);
-        if (e) return hip_fail(s, (hipError_t)e, "assemble launch");
-        if (slot) {
-            HIP_TRY(s, hipEventRecord(slot->ev, st));
-            slot->pending = true;
-        }
-    }
+    rc = run_gather(s, segs, n_tiles, false, layer_begin, layer_end - layer_begin, cache, cc, n_req, first_blk, n_blk, hip_stream);
+    if (rc) return rc;
     for (int r = 0; r < n_req; ++r) {
         cache->ctx_len[r] = ctx[r];
         if (cache->ctx_rows)
@@ -989,8 +971,23 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
             const int32_t *row = cache->block_table + (int64_t)r * cache->max_blocks_per_req;
             sig.insert(sig.end(), row, row + n_blk[r]);
         }
-    kvp_store::PrefillCached &pf = s->pf;
-    const bool hit = pf.valid && pf.stream == hip_stream && pf.sig == sig;
+    uint64_t sig_hash = 1469598103934665603ull;
+    for (int32_t x : sig) sig_hash = (sig_hash ^ (uint32_t)x) * 1099511628211ull;
+    kvp_store::PrefillCached *found = nullptr, *victim = nullptr;
+    for (auto &e : s->pf_set) {
+        if (e.valid && e.sig_hash == sig_hash && e.stream == hip_stream && e.sig == sig) {
+            found = &e;
+            break;
+        }
+        if (!victim || (!e.valid && victim->valid) || (e.valid == victim->valid && e.last_use < victim->last_use)) victim = &e;
+    }
+    const bool hit = found != nullptr;
+    if (!hit && (!victim || (victim->valid && (int)s->pf_set.size() < std::max(PlanRing::SLOTS, g.n_layers + 1)))) {
+        s->pf_set.emplace_back();
+        victim = &s->pf_set.back();
+    }
+    kvp_store::PrefillCached &pf = hit ? *found : *victim;
+    pf.last_use = ++s->pf_clock;
     const uint64_t qrb = q_rot_bytes(s, tot_q);
     if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
 
@@ -1000,11 +997,10 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         const uint64_t need = qrb + (uint64_t)p.n_slots * p.bm * (g.head_dim + 2) * sizeof(float);
         const uint64_t bytes = p.reqs.size() * sizeof(ReqMeta) + p.row_req.size() * 4 + p.groups.size() * sizeof(AttnGroup) +
                                p.items.size() * sizeof(AttnItem) + (uint64_t)n_req * bt_stride * 4 + 6 * 64;
-        PlanRing::Slot *slot = nullptr;
-        int hrc = s->ring_prefill.acquire(bytes, &slot);
+        pf.valid = false;  // the entry's buffer is rewritten below
+        PlanSlot *slot = &pf.own;
+        int hrc = slot->ensure(bytes, s->dry);
         if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
-        pf.valid = false;  // the slot may be the cached one; it is rewritten below either way
-        if (s->pk.slot == slot) s->pk.valid = false;  // the two caches share one ring
         PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
         ReqMeta *rh = w.put<ReqMeta>(p.reqs.size(), &pf.reqs_dev);
         if (!p.reqs.empty()) memcpy(rh, p.reqs.data(), p.reqs.size() * sizeof(ReqMeta));
@@ -1043,6 +1039,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         pf.max_group_rows = p.max_group_rows;
         pf.need = need;
         pf.sig = sig;
+        pf.sig_hash = sig_hash;
         pf.stream = hip_stream;
         // validated below before the upload makes the entry usable
         if (tot_q > 0) {
@@ -1052,7 +1049,8 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
                 return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)need);
         }
         if (s->dry || tot_q == 0) return KVP_OK;
-        HIP_TRY(s, hipMemcpyAsync(slot->dev, slot->host, w.off, hipMemcpyHostToDevice, (hipStream_t)hip_stream));
+        rc = upload_plan(s, slot, w.off, hip_stream);
+        if (rc) return rc;
         pf.valid = true;
     } else if (tot_q > 0) {
         if (!s->dry && !workspace) return fail(s, KVP_E_INVAL, "workspace is null");
@@ -1253,7 +1251,6 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         int hrc = s->ring_prefill.acquire(bytes, &slot);
         if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
         pk.valid = false;
-        if (s->pf.slot == slot) s->pf.valid = false;  // the two caches share one ring
         PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
         ReqMeta *rh = w.put<ReqMeta>(metas.size(), &pk.reqs_dev);
         if (!metas.empty()) memcpy(rh, metas.data(), metas.size() * sizeof(ReqMeta));
@@ -1296,7 +1293,8 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
             return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)need);
         if (s->dry || tot_q == 0) return KVP_OK;
         if (need > 0 && (!workspace || ((uintptr_t)workspace & (ALIGN - 1)))) return fail(s, KVP_E_INVAL, "workspace is null or not 256-byte aligned");
-        HIP_TRY(s, hipMemcpyAsync(slot->dev, slot->host, w.off, hipMemcpyHostToDevice, (hipStream_t)hip_stream));
+        int urc = upload_plan(s, slot, w.off, hip_stream);
+        if (urc) return urc;
         pk.valid = true;
     } else if (tot_q > 0) {
         if (workspace_bytes < pk.need)
@@ -1347,7 +1345,20 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
 int64_t kvp_debug_last_plan(const kvp_store_t *s, int32_t which, int64_t *out, int64_t cap)
 {
     if (!s) return KVP_E_INVAL;
-    const std::vector<int64_t> &v = which == 0 ? s->dbg_asm : s->dbg_attn;
+    std::vector<int64_t> tiles;
+    if (which == 0) {
+        // the gather's tiles, as the kernel derives them from the segment list:
+        // src_base, stride, first row in the segment, rows, cache row, Delta, request, layer (layered lists)
+        tiles.push_back(0);
+        for (const AsmSeg &g : s->dbg_segs)
+            for (int t0 = 0; t0 < g.n_rows; t0 += s->asm_tile_rows) {
+                int64_t row[8] = {g.src_base, g.stride, t0, std::min(s->asm_tile_rows, g.n_rows - t0), g.dst_row + t0,
+                                  g.pos, g.req, s->dbg_layered ? g.layer : -1};
+                tiles.insert(tiles.end(), row, row + 8);
+                ++tiles[0];
+            }
+    }
+    const std::vector<int64_t> &v = which == 0 ? tiles : s->dbg_attn;
     for (int64_t i = 0; i < (int64_t)v.size() && i < cap && out; ++i) out[i] = v[i];
     return (int64_t)v.size();
 }

@@ -31,7 +31,13 @@ def build_store(w, kvp, device="cuda:0", packets=None, max_positions=None, extra
                                  w.n_trailer, device=0, arena=arena)
     for i, p in enumerate(packets):
         k, v = w.packet_kv(p, device=device)
-        kvp.kvp_store_put(store, p, k, v)
+        if w.prune is None:
+            kvp.kvp_store_put(store, p, k, v)
+        else:
+            keep = [torch.as_tensor(w.kept_rows(p, l), device=device) for l in range(w.n_layers)]
+            kvp.kvp_store_put_compressed(store, p, int(w.packet_lens[p]),
+                                         [k[l][:, keep[l]].contiguous() for l in range(w.n_layers)],
+                                         [v[l][:, keep[l]].contiguous() for l in range(w.n_layers)])
         if progress is not None and i % 32 == 31:
             progress(i + 1, len(packets))
     torch.cuda.synchronize()
@@ -42,7 +48,8 @@ def make_cache(w, kvp, store, device="cuda:0", block_order="random", t_slack=5):
     n_req = len(w.requests)
     rows = [w.ctx_len(r) + w.requests[r].n_q for r in range(n_req)]
     if not w.paged:
-        return kvp.Cache.contiguous(store, n_req, max(rows + [1]) + t_slack, device)
+        c = kvp.Cache.contiguous(store, n_req, max(rows + [1]) + t_slack, device)
+        return c.with_ctx_rows(w.n_layers) if w.prune is not None else c
     bs = w.block_size
     nblk = [(x + bs - 1) // bs for x in rows]
     total = sum(nblk) + 3
@@ -53,7 +60,8 @@ def make_cache(w, kvp, store, device="cuda:0", block_order="random", t_slack=5):
     for r in range(n_req):
         table[r, :nblk[r]] = pool[at:at + nblk[r]]
         at += nblk[r]
-    return kvp.Cache.paged(store, n_req, total, table, bs, device)
+    c = kvp.Cache.paged(store, n_req, total, table, bs, device)
+    return c.with_ctx_rows(w.n_layers) if w.prune is not None else c
 
 
 def run_workload(w, layers=None, device="cuda:0", flags=0, block_order="random", store=None,

@@ -339,6 +339,12 @@ def test_compressed_packets_plan_rows_and_positions():
     # tiles of compressed packets carry a negative stride (their blob is laid out layer by layer)
     neg = t[t[:, 1] < 0]
     assert len(neg) and set(-neg[:, 1]) <= {100, 37, 1, 70, 65}
+    # each tile names its layer; per (request, layer) the tiles cover the packet rows exactly once
+    for r, base in ((0, 5), (1, 0)):
+        for l in range(3):
+            mine = t[(t[:, 6] == r) & (t[:, 7] == l)]
+            rows = sorted(x for _, _, _, n, dst, *_ in mine for x in range(dst, dst + n))
+            assert rows == list(range(base, int(cache.ctx_rows[r][l])))
     # a layer range writes only its own entries
     cache2 = kvp.Cache.dry(1, t_cap=400).with_ctx_rows(3)
     cache2.ctx_rows[:] = -1

@@ -557,6 +557,50 @@ def test_compressed_packets_match_oracle(gpu_device, dtype, paged):
             check_output(outs[layer][q_off[r]:q_off[r + 1]], ref, w.dtype, ("compressed", r, layer))
 
 
+def test_pruned_headline_workload(gpu_device):
+    """The benchmark's pruned workload (Sec. 5.4, 10-50 % of every packet's rows removed, another
+    subset in every layer) at its full context, six layers of it (96 segments: the gather plan is
+    uploaded and searched, not carried in the kernel arguments): one assembly launch over all
+    layers, rows of every layer bit-exact, attention within tolerance."""
+    import paper_2604_13226_amd as kvp
+    import oracle
+    w = W.llama_8k_pruned(n_layers=6, n_packets=16)
+    rq = w.requests[0]
+    f = oracle.inv_freq(w.rope_base, w.head_dim)
+    store = build_store(w, kvp)
+    cache = make_cache(w, kvp, store)
+    kvp.kvp_assemble(store, [(rq.packet_ids, 0)], cache)
+    assert int(cache.ctx_len[0]) == w.ctx_len(0)
+    n_q = rq.n_q
+    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, 1, n_q, w.ctx_len(0) + n_q))
+    spans = [int(w.packet_lens[p]) for p in rq.packet_ids]
+    kv = [tuple(W.to_numpy(x) for x in w.packet_kv(p)) for p in rq.packet_ids]
+    first_pass = []
+    for layer in range(w.n_layers):
+        q, kn, vn = w.query(0, layer, "cuda")
+        out = torch.full_like(q, float("nan"))
+        kvp.kvp_query_prefill(store, cache, layer, q, kn, vn, [0, n_q], ws, out)
+        torch.cuda.synchronize()
+        keep = [w.kept_rows(p, layer) for p in rq.packet_ids]
+        ks = [np.ascontiguousarray(k[layer][:, s]) for (k, _), s in zip(kv, keep)]
+        vs = [np.ascontiguousarray(v[layer][:, s]) for (_, v), s in zip(kv, keep)]
+        Ko, Vo, rows, pos_end = oracle.assemble_layer_spans(w.dtype, ks, vs, spans, f, 0, t_cap=w.layer_rows(0, layer) + n_q)
+        assert rows == w.layer_rows(0, layer) == int(cache.ctx_rows[0][layer]) and pos_end == w.ctx_len(0)
+        ref = oracle.query_prefill_at(w.dtype, *(W.to_numpy(x) for x in (q, kn, vn)), f, rows, pos_end, Ko, Vo)
+        kg, vg = (W.to_numpy(x) for x in cache.logical(0, layer, rows + n_q))
+        assert np.array_equal(kg, Ko[:, :rows + n_q]), (layer, "K")
+        assert np.array_equal(vg, Vo[:, :rows + n_q]), (layer, "V")
+        check_output(out.float().cpu().numpy().astype(np.float64), ref, w.dtype, ("pruned 8k", layer))
+        first_pass.append(out)
+    # every layer has its own plan; a second pass finds them again and gives the same bits
+    for layer in range(w.n_layers):
+        q, kn, vn = w.query(0, layer, "cuda")
+        out = torch.full_like(q, float("nan"))
+        kvp.kvp_query_prefill(store, cache, layer, q, kn, vn, [0, n_q], ws, out)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), first_pass[layer].view(torch.int16)), layer
+
+
 def test_repeated_calls_reuse_the_plan_and_give_the_same_bits(gpu_device):
     """The same geometry layer after layer reuses the uploaded plan: six calls in a row match the
     oracle and each other bit for bit (same items, same merge order)."""
