@@ -134,6 +134,8 @@ def main():
                     help="assemble layer by layer on a second stream, under the previous layer's prefill")
     ap.add_argument("--layout", default="", choices=["", "contiguous", "paged"],
                     help="cache layout (default: the workload's own); paged uses 16-row blocks in a seeded random order")
+    ap.add_argument("--shared-header", action="store_true",
+                    help="store the header rows once (kvp_store_put_header) and every packet without them")
     ap.add_argument("--per-request", action="store_true",
                     help="batched workloads: also time every request alone (p50 / p99 latency)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -163,6 +165,7 @@ def main():
         w.n_layers = min(w.n_layers, args.layers)
     if args.layout:
         w.paged = args.layout == "paged"
+    w.shared_header = bool(args.shared_header)
     n_req = len(w.requests)
     if w.prune is not None and args.path == "packets":
         print("bench.py: the in-place path reads whole packets only; run %s with --path cache" % w.name,
@@ -291,7 +294,8 @@ def main():
                    % (w.name, w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, n_req,
                       ctx[:4], [rq.n_q for rq in w.requests[:4]]),
                    "layout": "paged" if w.paged else "contiguous", "path": args.path,
-                   "store": args.store, "pipelined": bool(pipelined)},
+                   "store": args.store, "pipelined": bool(pipelined), "shared_header": bool(args.shared_header),
+                   "store_bytes_used": kvp.kvp_store_bytes_used(store)},
         "roofline": {"bound": "hbm", "kernel": "assemble_vec_kernel (all layers, one launch)",
                      "achieved": asm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": asm_gbs / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),

@@ -127,6 +127,28 @@ int kvp_store_put(kvp_store_t *store, int64_t packet_id, int32_t n_tokens, const
 int kvp_store_put_compressed(kvp_store_t *store, int64_t packet_id, int32_t span, const int32_t *n_rows,
                              const void *k, const void *v, int32_t src_on_device, void *hip_stream);
 
+/*
+ * Sec. 4.1: the adapters are global, shared by all documents, and the header comes first in
+ * Eq. 2; under causal attention its K and V at local positions 0..n_header-1 are therefore the
+ * same in every packet.  A store may hold them once:
+ *   kvp_store_put_header : k, v [n_layers][n_kv_heads][n_header][head_dim] (n_header of the
+ *                          config, >= 1), K rotated at local positions 0..n_header-1; once per
+ *                          store (KVP_E_EXISTS after that).
+ *   kvp_store_put_body   : a packet without its header rows.  n_tokens is its full length, header
+ *                          included (the positions it occupies); k, v hold its rows n_header ..
+ *                          n_tokens-1 as [n_layers][n_kv_heads][n_tokens - n_header][head_dim],
+ *                          K rotated at those local positions.  Needs the header to be stored and
+ *                          n_tokens > n_header (KVP_E_INVAL otherwise).
+ * kvp_assemble and kvp_prefill_packets read the header rows of such a packet from the shared
+ * copy and rotate them by the packet's own Delta_j; results are those of the whole packet
+ * stored with kvp_store_put.  Whole and header-less packets may be mixed in a store and in a
+ * request.  Other arguments, copies and errors as kvp_store_put.
+ */
+int kvp_store_put_header(kvp_store_t *store, const void *k, const void *v, int32_t src_on_device,
+                         void *hip_stream);
+int kvp_store_put_body(kvp_store_t *store, int64_t packet_id, int32_t n_tokens, const void *k,
+                       const void *v, int32_t src_on_device, void *hip_stream);
+
 /* Rows of a stored packet (for a compressed packet: the positions it occupies), or
  * KVP_E_NOTFOUND. */
 int32_t kvp_store_packet_len(const kvp_store_t *store, int64_t packet_id);

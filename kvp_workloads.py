@@ -71,7 +71,7 @@ def normal_table(dtype, device="cpu"):
     return _TABLES[key]
 
 
-TENSOR_K, TENSOR_V, TENSOR_Q, TENSOR_KNEW, TENSOR_VNEW = 1, 2, 3, 4, 5
+TENSOR_K, TENSOR_V, TENSOR_Q, TENSOR_KNEW, TENSOR_VNEW, TENSOR_HEADER_K, TENSOR_HEADER_V = 1, 2, 3, 4, 5, 6, 7
 
 
 def normal_tensor(shape, seed, tensor_id, packet=0, scale=1.0, dtype=torch.bfloat16,
@@ -118,6 +118,7 @@ class Workload:
     paged: bool = False
     block_size: int = 16
     prune: tuple = None       # (lo, hi): every (packet, layer) loses a seeded fraction in [lo, hi] of its rows
+    shared_header: bool = False  # the first n_header rows are the same in every packet (global adapters, Sec. 4.1)
 
     @property
     def torch_dtype(self):
@@ -159,6 +160,18 @@ class Workload:
         shape = (n_l, self.n_kv_heads, int(self.packet_lens[pid]), self.head_dim)
         k = normal_tensor(shape, self.seed, TENSOR_K, pid, self.kv_scale, self.torch_dtype, device)
         v = normal_tensor(shape, self.seed, TENSOR_V, pid, self.kv_scale, self.torch_dtype, device)
+        if self.shared_header:
+            n_h = min(self.n_header, shape[2])
+            hk, hv = self.header_kv(device, n_l)
+            k[:, :, :n_h], v[:, :, :n_h] = hk[:, :, :n_h], hv[:, :, :n_h]
+        return k, v
+
+    def header_kv(self, device="cpu", layers=None):
+        """(K, V) of the header rows all packets share: [n_layers][Hkv][n_header][d]."""
+        n_l = self.n_layers if layers is None else layers
+        shape = (n_l, self.n_kv_heads, self.n_header, self.head_dim)
+        k = normal_tensor(shape, self.seed, TENSOR_HEADER_K, 0, self.kv_scale, self.torch_dtype, device)
+        v = normal_tensor(shape, self.seed, TENSOR_HEADER_V, 0, self.kv_scale, self.torch_dtype, device)
         return k, v
 
     def query(self, r, layer, device="cpu"):

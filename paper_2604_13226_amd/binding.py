@@ -45,6 +45,8 @@ EXPORTS = {
     "kvp_store_destroy": (_i32, [_vp]),
     "kvp_store_put": (_i32, [_vp, _i64, _i32, _vp, _vp, _i32, _vp]),
     "kvp_store_put_compressed": (_i32, [_vp, _i64, _i32, _vp, _vp, _vp, _i32, _vp]),
+    "kvp_store_put_header": (_i32, [_vp, _vp, _vp, _i32, _vp]),
+    "kvp_store_put_body": (_i32, [_vp, _i64, _i32, _vp, _vp, _i32, _vp]),
     "kvp_store_packet_len": (_i32, [_vp, _i64]),
     "kvp_store_packet_rows": (_i32, [_vp, _i64, _i32]),
     "kvp_store_bytes_used": (_u64, [_vp]),
@@ -197,6 +199,33 @@ def kvp_store_put_compressed(store, packet_id, span, k_layers, v_layers, stream=
                                          kk.data_ptr(), vv.data_ptr(), 1 if kk.is_cuda else 0, _stream(stream))
     if kk.is_cuda:
         torch.cuda.synchronize()  # kk, vv are temporaries
+    _check(store.handle, rc)
+
+
+def kvp_store_put_header(store, k=None, v=None, stream=None):
+    """The header rows every packet starts with, stored once: k, v [n_layers][n_kv_heads][n_header][head_dim]."""
+    if store.dry:
+        return _check(store.handle, load().kvp_store_put_header(store.handle, None, None, 0, None))
+    c = store.cfg
+    assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
+    assert k.dtype == store.torch_dtype and v.dtype == store.torch_dtype and v.is_cuda == k.is_cuda
+    assert tuple(k.shape) == (c.n_layers, c.n_kv_heads, c.n_header, c.head_dim)
+    rc = load().kvp_store_put_header(store.handle, k.data_ptr(), v.data_ptr(), 1 if k.is_cuda else 0, _stream(stream))
+    _check(store.handle, rc)
+
+
+def kvp_store_put_body(store, packet_id, k, v, stream=None, n_tokens=None):
+    """A packet without its header rows: k, v [n_layers][n_kv_heads][n_tokens - n_header][head_dim]
+    (rows n_header.. of the packet); n_tokens, header included, is derived from the shape."""
+    if store.dry:
+        rc = load().kvp_store_put_body(store.handle, int(packet_id), int(n_tokens), None, None, 0, None)
+        return _check(store.handle, rc)
+    c = store.cfg
+    assert k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
+    assert k.dtype == store.torch_dtype and v.dtype == store.torch_dtype and v.is_cuda == k.is_cuda
+    assert tuple(k.shape[:2]) == (c.n_layers, c.n_kv_heads) and k.shape[3] == c.head_dim
+    rc = load().kvp_store_put_body(store.handle, int(packet_id), int(k.shape[2]) + c.n_header, k.data_ptr(),
+                                   v.data_ptr(), 1 if k.is_cuda else 0, _stream(stream))
     _check(store.handle, rc)
 
 

@@ -33,7 +33,11 @@ struct PacketRec {
     // part of the blob ([K: Hkv x rows][V: Hkv x rows], layer after layer)
     std::vector<int32_t> rows;
     std::vector<int64_t> layer_off;
+    // packets stored without their header rows: the first head_rows positions come from the
+    // store's shared header blob, the blob at elem_off holds the n_tokens - head_rows others
+    int32_t head_rows = 0;
     bool compressed() const { return !rows.empty(); }
+    int body_rows() const { return n_tokens - head_rows; }
 };
 
 // A pinned-host / device twin buffer that carries one call's plan.  It is rewritten only
@@ -125,6 +129,7 @@ struct kvp_store {
     float2 *cs_dev = nullptr;
     void *arena_dev = nullptr;  // the arena as the kernels address it
     bool arena_host = false;    // the arena is pinned host memory mapped into the device (read over PCIe)
+    PacketRec header;       // the header rows stored once (kvp_store_put_header); n_tokens 0: none
     PlanRing ring;          // plans of kvp_assemble
     PlanRing ring_prefill;  // plans of kvp_prefill_packets
     // The prefill plan depends only on the request geometry (context lengths, query
@@ -410,22 +415,20 @@ int assemble_compressed(kvp_store *s, const kvp_request_t *reqs, int n_req, int 
                 return fail(s, KVP_E_CAPACITY, "request %d: context exceeds max_positions %d", r, g.max_positions);
             for (int li = 0; li < n_l; ++li) {
                 const int l = layer_begin + li;
-                const int n = p.compressed() ? p.rows[l] : p.n_tokens;
-                if (n == 0) continue;
-                AsmSeg t;
-                // first K row of head 0 in this layer; a negative stride marks a blob laid out layer by layer
-                t.src_base = p.compressed() ? p.layer_off[l] : p.elem_off + (int64_t)l * g.n_kv_heads * p.stride * g.head_dim;
-                t.stride = p.compressed() ? -n : p.stride;
-                t.n_rows = n;
-                t.dst_row = (int32_t)row[li];
-                t.pos = (int32_t)pos;
-                t.req = r;
-                t.layer = l;
-                t.tile0 = (int32_t)n_tiles;
-                t.pad = 0;
-                segs.push_back(t);
-                n_tiles += tiles_of(s, n);
-                row[li] += n;
+                // src: first K row of head 0 in this layer; a negative stride marks a blob laid out layer by layer
+                auto emit = [&](int64_t src, int stride, int n) {
+                    if (n == 0) return;
+                    segs.push_back(AsmSeg{src, stride, n, (int32_t)row[li], (int32_t)pos, r, l, (int32_t)n_tiles, 0});
+                    n_tiles += tiles_of(s, n);
+                    row[li] += n;
+                };
+                const int64_t slices = (int64_t)l * g.n_kv_heads * g.head_dim;  // x stride = elements before layer l
+                if (p.compressed()) {
+                    emit(p.layer_off[l], -p.rows[l], p.rows[l]);
+                } else {
+                    if (p.head_rows) emit(s->header.elem_off + slices * s->header.stride, s->header.stride, p.head_rows);
+                    emit(p.elem_off + slices * p.stride, p.stride, p.body_rows());
+                }
             }
             pos += p.n_tokens;
         }
@@ -563,20 +566,19 @@ int kvp_store_destroy(kvp_store_t *s)
     return KVP_OK;
 }
 
-int kvp_store_put(kvp_store_t *s, int64_t packet_id, int32_t n_tokens, const void *k, const void *v,
-                  int32_t src_on_device, void *hip_stream)
+}  // extern "C"
+
+namespace {
+
+// Copies K, V [n_layers][n_kv_heads][rows][head_dim] into a new blob of the arena.
+int put_blob(kvp_store *s, int rows, const void *k, const void *v, int src_on_device, void *hip_stream, PacketRec &rec)
 {
-    if (!s) return KVP_E_INVAL;
-    if (packet_id < 0) return fail(s, KVP_E_INVAL, "packet id %lld < 0", (long long)packet_id);
-    if (n_tokens < 1) return fail(s, KVP_E_INVAL, "n_tokens %d < 1", n_tokens);
-    if (!s->dry && (!k || !v)) return fail(s, KVP_E_INVAL, "k or v is null");
-    if (s->dir.count(packet_id)) return fail(s, KVP_E_EXISTS, "packet %lld already stored", (long long)packet_id);
     const kvp_config_t &g = s->cfg;
     const uint64_t row_bytes = (uint64_t)g.head_dim * s->esize;
-    const int stride = n_tokens + slice_pad_rows(n_tokens);
+    const int stride = rows + slice_pad_rows(rows);
     const uint64_t n_slices = (uint64_t)g.n_layers * g.n_kv_heads;
     const uint64_t half_bytes = n_slices * stride * row_bytes;
-    const uint64_t need = align_up(2 * half_bytes + blob_pad_rows(n_tokens) * row_bytes);
+    const uint64_t need = align_up(2 * half_bytes + blob_pad_rows(rows) * row_bytes);
     if (s->used_bytes + need > g.arena_bytes)
         return fail(s, KVP_E_NOSPACE, "arena full: %llu used + %llu needed > %llu", (unsigned long long)s->used_bytes,
                     (unsigned long long)need, (unsigned long long)g.arena_bytes);
@@ -585,13 +587,66 @@ int kvp_store_put(kvp_store_t *s, int64_t packet_id, int32_t n_tokens, const voi
         char *dst = (char *)g.arena + s->used_bytes;
         hipMemcpyKind kind = s->arena_host ? hipMemcpyDefault : src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
         hipStream_t st = (hipStream_t)hip_stream;
-        const uint64_t slice_bytes = (uint64_t)n_tokens * row_bytes;
+        const uint64_t slice_bytes = (uint64_t)rows * row_bytes;
         HIP_TRY(s, hipMemcpy2DAsync(dst, stride * row_bytes, k, slice_bytes, slice_bytes, n_slices, kind, st));
         HIP_TRY(s, hipMemcpy2DAsync(dst + half_bytes, stride * row_bytes, v, slice_bytes, slice_bytes, n_slices, kind, st));
         if (!src_on_device) HIP_TRY(s, hipStreamSynchronize(st));  // host buffers may be reused on return
     }
-    s->dir[packet_id] = PacketRec{(int64_t)(s->used_bytes / s->esize), n_tokens, stride, {}, {}};
+    rec.elem_off = (int64_t)(s->used_bytes / s->esize);
+    rec.stride = stride;
     s->used_bytes += need;
+    return KVP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int kvp_store_put(kvp_store_t *s, int64_t packet_id, int32_t n_tokens, const void *k, const void *v,
+                  int32_t src_on_device, void *hip_stream)
+{
+    if (!s) return KVP_E_INVAL;
+    if (packet_id < 0) return fail(s, KVP_E_INVAL, "packet id %lld < 0", (long long)packet_id);
+    if (n_tokens < 1) return fail(s, KVP_E_INVAL, "n_tokens %d < 1", n_tokens);
+    if (!s->dry && (!k || !v)) return fail(s, KVP_E_INVAL, "k or v is null");
+    if (s->dir.count(packet_id)) return fail(s, KVP_E_EXISTS, "packet %lld already stored", (long long)packet_id);
+    PacketRec rec;
+    rec.n_tokens = n_tokens;
+    int rc = put_blob(s, n_tokens, k, v, src_on_device, hip_stream, rec);
+    if (rc) return rc;
+    s->dir[packet_id] = rec;
+    return KVP_OK;
+}
+
+int kvp_store_put_header(kvp_store_t *s, const void *k, const void *v, int32_t src_on_device, void *hip_stream)
+{
+    if (!s) return KVP_E_INVAL;
+    if (s->cfg.n_header < 1) return fail(s, KVP_E_INVAL, "the store was created with n_header = %d", s->cfg.n_header);
+    if (!s->dry && (!k || !v)) return fail(s, KVP_E_INVAL, "k or v is null");
+    if (s->header.n_tokens) return fail(s, KVP_E_EXISTS, "the header is already stored");
+    PacketRec rec;
+    int rc = put_blob(s, s->cfg.n_header, k, v, src_on_device, hip_stream, rec);
+    if (rc) return rc;
+    rec.n_tokens = s->cfg.n_header;
+    s->header = rec;
+    return KVP_OK;
+}
+
+int kvp_store_put_body(kvp_store_t *s, int64_t packet_id, int32_t n_tokens, const void *k, const void *v,
+                       int32_t src_on_device, void *hip_stream)
+{
+    if (!s) return KVP_E_INVAL;
+    if (packet_id < 0) return fail(s, KVP_E_INVAL, "packet id %lld < 0", (long long)packet_id);
+    if (!s->header.n_tokens) return fail(s, KVP_E_INVAL, "no header stored (kvp_store_put_header)");
+    if (n_tokens <= s->cfg.n_header) return fail(s, KVP_E_INVAL, "n_tokens %d does not exceed the %d header rows", n_tokens, s->cfg.n_header);
+    if (!s->dry && (!k || !v)) return fail(s, KVP_E_INVAL, "k or v is null");
+    if (s->dir.count(packet_id)) return fail(s, KVP_E_EXISTS, "packet %lld already stored", (long long)packet_id);
+    PacketRec rec;
+    rec.n_tokens = n_tokens;
+    rec.head_rows = s->cfg.n_header;
+    int rc = put_blob(s, n_tokens - s->cfg.n_header, k, v, src_on_device, hip_stream, rec);
+    if (rc) return rc;
+    s->dir[packet_id] = rec;
     return KVP_OK;
 }
 
@@ -620,7 +675,9 @@ int kvp_store_put_compressed(kvp_store_t *s, int64_t packet_id, int32_t span, co
     if (s->dir.count(packet_id)) return fail(s, KVP_E_EXISTS, "packet %lld already stored", (long long)packet_id);
     const kvp_config_t &g = s->cfg;
     const uint64_t row_bytes = (uint64_t)g.head_dim * s->esize;
-    PacketRec rec{(int64_t)(s->used_bytes / s->esize), span, span, {}, {}};
+    PacketRec rec;
+    rec.elem_off = (int64_t)(s->used_bytes / s->esize);
+    rec.n_tokens = rec.stride = span;
     uint64_t total_rows = 0;
     for (int l = 0; l < g.n_layers; ++l) {
         if (n_rows[l] < 0 || n_rows[l] > span) return fail(s, KVP_E_INVAL, "layer %d keeps %d rows of a span of %d", l, n_rows[l], span);
@@ -696,8 +753,12 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
             const PacketRec &p = it->second;
             if (pos + p.n_tokens > g.max_positions)
                 return fail(s, KVP_E_CAPACITY, "request %d: context exceeds max_positions %d", r, g.max_positions);
-            segs.push_back(AsmSeg{p.elem_off, p.stride, p.n_tokens, (int32_t)pos, (int32_t)pos, r, 0, (int32_t)n_tiles, 0});
-            n_tiles += tiles_of(s, p.n_tokens);
+            if (p.head_rows) {  // the header rows come from the shared copy, at the packet's own Delta
+                segs.push_back(AsmSeg{s->header.elem_off, s->header.stride, p.head_rows, (int32_t)pos, (int32_t)pos, r, 0, (int32_t)n_tiles, 0});
+                n_tiles += tiles_of(s, p.head_rows);
+            }
+            segs.push_back(AsmSeg{p.elem_off, p.stride, p.body_rows(), (int32_t)pos + p.head_rows, (int32_t)pos, r, 0, (int32_t)n_tiles, 0});
+            n_tiles += tiles_of(s, p.body_rows());
             pos += p.n_tokens;
         }
         if (pos > cc.cap_rows) return fail(s, KVP_E_CAPACITY, "request %d: %lld rows do not fit the cache (%lld)", r, (long long)pos, (long long)cc.cap_rows);
@@ -1182,8 +1243,11 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
                 if (itp == s->dir.end()) return fail(s, KVP_E_NOTFOUND, "request %d: packet %lld not in the store", r, (long long)rq.packet_ids[j]);
                 const PacketRec &p = itp->second;
                 if (p.compressed()) return fail(s, KVP_E_INVAL, "request %d: packet %lld is compressed; kvp_prefill_packets reads uncompressed packets only", r, (long long)rq.packet_ids[j]);
-                for (int r0 = 0; r0 < p.n_tokens; r0 += 64)
-                    tiles.push_back(AttnTile{p.elem_off, p.stride, r0, std::min(64, p.n_tokens - r0), (int32_t)pos, 0, 0});
+                // (a packet stored without its header rows: those come from the shared copy, as a tile of their own)
+                for (int r0 = 0; r0 < p.head_rows; r0 += 64)
+                    tiles.push_back(AttnTile{s->header.elem_off, s->header.stride, r0, std::min(64, p.head_rows - r0), (int32_t)pos, 0, 0});
+                for (int r0 = 0; r0 < p.body_rows(); r0 += 64)
+                    tiles.push_back(AttnTile{p.elem_off, p.stride, r0, std::min(64, p.body_rows() - r0), (int32_t)pos, 0, 0});
                 pos += p.n_tokens;
             }
             if (pos + n_q > g.max_positions) return fail(s, KVP_E_CAPACITY, "request %d: %lld rows exceed max_positions %d", r, (long long)(pos + n_q), g.max_positions);

@@ -24,14 +24,20 @@ def build_store(w, kvp, device="cuda:0", packets=None, max_positions=None, extra
     packets = needed_packets(w) if packets is None else packets
     arena_bytes = sum(kvp.packet_bytes(w.n_layers, w.n_kv_heads, w.head_dim, w.dtype, int(w.packet_lens[p]))
                       for p in packets) + extra_bytes
+    if w.shared_header:
+        arena_bytes += kvp.packet_bytes(w.n_layers, w.n_kv_heads, w.head_dim, w.dtype, w.n_header)
     if max_positions is None:
         max_positions = max([w.ctx_len(r) + w.requests[r].n_q for r in range(len(w.requests))] + [1]) + 64
     store = kvp.kvp_store_create(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype,
                                  w.rope_base, max_positions, max(arena_bytes, 256), w.n_header,
                                  w.n_trailer, device=0, arena=arena)
+    if w.shared_header:
+        kvp.kvp_store_put_header(store, *w.header_kv(device))
     for i, p in enumerate(packets):
         k, v = w.packet_kv(p, device=device)
-        if w.prune is None:
+        if w.shared_header and k.shape[2] > w.n_header:    # the header rows are in the store already
+            kvp.kvp_store_put_body(store, p, k[:, :, w.n_header:].contiguous(), v[:, :, w.n_header:].contiguous())
+        elif w.prune is None:
             kvp.kvp_store_put(store, p, k, v)
         else:
             keep = [torch.as_tensor(w.kept_rows(p, l), device=device) for l in range(w.n_layers)]

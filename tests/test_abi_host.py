@@ -359,6 +359,58 @@ def test_compressed_packets_plan_rows_and_positions():
     assert ends[0] == cache.ctx_rows[0][1] + 4 and ends[1] == 40 + 3
 
 
+def test_shared_header_plan_and_errors():
+    """Sec. 4.1 (global adapters): header rows stored once; header-less packets get them back."""
+    s = dry_store(n_layers=2, n_header=8)
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_store_put_body(s, 0, None, None, n_tokens=100)          # no header yet
+    assert e.value.code == kvp.KVP_E_INVAL
+    kvp.kvp_store_put_header(s)
+    used_header = kvp.kvp_store_bytes_used(s)
+    assert used_header == kvp.packet_bytes(2, 2, 128, "bf16", 8)
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_store_put_header(s)
+    assert e.value.code == kvp.KVP_E_EXISTS
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_store_put_body(s, 0, None, None, n_tokens=8)            # nothing but the header
+    assert e.value.code == kvp.KVP_E_INVAL
+    kvp.kvp_store_put_body(s, 0, None, None, n_tokens=100)
+    assert kvp.kvp_store_bytes_used(s) == used_header + kvp.packet_bytes(2, 2, 128, "bf16", 92)
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_store_put_body(s, 0, None, None, n_tokens=50)
+    assert e.value.code == kvp.KVP_E_EXISTS
+    kvp.kvp_store_put(s, 1, None, None, n_tokens=40)                    # a whole packet next to it
+    assert kvp.kvp_store_packet_len(s, 0) == 100 and kvp.kvp_store_packet_rows(s, 0, 1) == 100
+    cache = kvp.Cache.dry(1, t_cap=300)
+    kvp.kvp_assemble(s, [([0, 1, 0], 3)], cache)
+    assert cache.ctx_len[0] == 3 + 100 + 40 + 100
+    t = _tiles(s)
+    covered = np.zeros(243, int)
+    for src, stride, tok0, n_tok, dst, pos, _, _ in t:
+        covered[dst:dst + n_tok] += 1
+        assert pos in (3, 103, 143)
+        if stride == 8:          # a header tile: from the shared blob, at the packet's first rows
+            assert src * 2 < used_header and dst == pos and n_tok == 8 and pos in (3, 143)
+        elif stride == 92:       # body rows land behind the header rows
+            assert dst == pos + 8 + tok0
+        else:
+            assert stride == 40 and dst == pos + tok0
+    assert np.all(covered[3:] == 1) and not covered[:3].any()
+    assert sum(1 for row in t if row[1] == 8) == 2
+    # the in-place path: a header tile of 8 rows, then the body tiles, all at the packet's Delta
+    kvp.kvp_prefill_packets(s, [([0, 1], 0)], 0, None, None, None, np.array([0, 4], np.int32), None, None, None)
+    p = kvp.kvp_debug_last_plan(s, 1)
+    ng, ni = int(p[2]), int(p[3])
+    rest = p[6 + 6 * ng + 4 * ni:]
+    tiles = rest[1:].reshape(int(rest[0]), 6)
+    assert [tuple(int(v) for v in x[1:]) for x in tiles] == [
+        (8, 0, 8, 0, 0), (92, 0, 64, 0, 0), (92, 64, 28, 0, 0), (40, 0, 40, 100, 0), (0, 0, 4, 0, 1)]
+    # a store without header rows has nothing to share
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_store_put_header(dry_store(n_header=0))
+    assert e.value.code == kvp.KVP_E_INVAL
+
+
 def test_compressed_packets_errors():
     s = dry_store(n_layers=2)
     with pytest.raises(kvp.KvpError) as e:

@@ -601,6 +601,53 @@ def test_pruned_headline_workload(gpu_device):
         assert torch.equal(out.view(torch.int16), first_pass[layer].view(torch.int16)), layer
 
 
+@pytest.mark.parametrize("case", ["bf16", "bf16 paged", "f32", "mixed with compressed"])
+def test_shared_header_store_matches_whole_packets(gpu_device, case):
+    """Sec. 4.1: the header is global, so its rows are the same in every packet and the store may
+    hold them once (kvp_store_put_header / kvp_store_put_body).  The oracle composes the whole
+    packets; the library reads the header rows from the shared copy: cache rows bit-exact,
+    attention within tolerance, on both the assembled and the in-place path."""
+    import paper_2604_13226_amd as kvp
+    if case == "f32":
+        w = W.random_small(91, dtype="f32", d=64, n_q_heads=4, n_kv_heads=2, n_layers=2, n_packets=5, k=4, n_q=6,
+                           max_len=50, n_req=2, base_pos=3)
+        w.n_header, w.n_trailer = 3, 2
+        w.packet_lens[0] = 2                        # shorter than the header: stored whole
+    else:
+        w = W.llama_long_b8(n_layers=2, n_packets=6, batch=3, k=4, n_q=40)
+        w.packet_lens[:] = [70, 9, 64, 129, 300, 8]   # 9: one body row; 8: header only, stored whole
+        w.requests[1].packet_ids = [2, 2, 5, 1]
+        w.requests[2].n_q = 3
+        w.paged = case == "bf16 paged"
+    w.shared_header = True
+    ref = oracle_workload(w)
+    if case != "mixed with compressed":
+        compare(w, run_workload(w), ref)
+        if w.dtype == "bf16" and not w.paged:
+            layers = list(range(w.n_layers))
+            outs, tails = _run_packets(w, layers)
+            _check_packets(w, layers, outs, tails, ref)
+        return
+    # a compressed packet in the request sends the call down the layer-by-layer route, where the
+    # header-less packets get a header segment per layer; keeping every row of the compressed
+    # packet makes the whole-packet oracle the reference
+    store = build_store(w, kvp, packets=[0, 1, 2, 3, 5], extra_bytes=1 << 24)
+    k4, v4 = w.packet_kv(4, "cuda")
+    kvp.kvp_store_put_compressed(store, 4, 300, [k4[l].contiguous() for l in range(w.n_layers)],
+                                 [v4[l].contiguous() for l in range(w.n_layers)])
+    w.requests[0].packet_ids = [3, 4, 0, 1]
+    ref = oracle_workload(w)
+    cache = make_cache(w, kvp, store).with_ctx_rows(w.n_layers)
+    kvp.kvp_assemble(store, [(rq.packet_ids, rq.base_pos) for rq in w.requests], cache)
+    for r in range(len(w.requests)):
+        for layer in range(w.n_layers):
+            ctx = w.ctx_len(r)
+            assert int(cache.ctx_rows[r][layer]) == ctx == int(cache.ctx_len[r])
+            k, v = cache.logical(r, layer, ctx)
+            assert np.array_equal(W.to_numpy(k), ref["k"][r][layer][:, :ctx]), (r, layer, "K")
+            assert np.array_equal(W.to_numpy(v), ref["v"][r][layer][:, :ctx]), (r, layer, "V")
+
+
 def test_repeated_calls_reuse_the_plan_and_give_the_same_bits(gpu_device):
     """The same geometry layer after layer reuses the uploaded plan: six calls in a row match the
     oracle and each other bit for bit (same items, same merge order)."""
