@@ -134,6 +134,8 @@ def main():
                     help="assemble layer by layer on a second stream, under the previous layer's prefill")
     ap.add_argument("--layout", default="", choices=["", "contiguous", "paged"],
                     help="cache layout (default: the workload's own); paged uses 16-row blocks in a seeded random order")
+    ap.add_argument("--block-order", default="random", choices=["random", "sequential"],
+                    help="paged layout: how the pool's blocks are dealt to the requests")
     ap.add_argument("--shared-header", action="store_true",
                     help="store the header rows once (kvp_store_put_header) and every packet without them")
     ap.add_argument("--per-request", action="store_true",
@@ -174,7 +176,7 @@ def main():
     store = build_store(w, kvp, dev, packets=list(range(len(w.packet_lens)))
                         if len(w.packet_lens) <= 256 and args.store == "device" else None, arena=args.store,
                         progress=lambda i, n: print("store: packet %d of %d" % (i, n), file=sys.stderr, flush=True))
-    cache = make_cache(w, kvp, store, dev, t_slack=0)
+    cache = make_cache(w, kvp, store, dev, block_order=args.block_order, t_slack=0)
     reqs = [(rq.packet_ids, rq.base_pos) for rq in w.requests]
     q_off = np.zeros(n_req + 1, np.int32)
     for r in range(n_req):
@@ -293,7 +295,7 @@ def main():
         "config": {"workload": "%s: %d layers, Hq %d / Hkv %d, d %d, %d request(s), ctx %s, n_q %s"
                    % (w.name, w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, n_req,
                       ctx[:4], [rq.n_q for rq in w.requests[:4]]),
-                   "layout": "paged" if w.paged else "contiguous", "path": args.path,
+                   "layout": ("paged, %s block order" % args.block_order) if w.paged else "contiguous", "path": args.path,
                    "store": args.store, "pipelined": bool(pipelined), "shared_header": bool(args.shared_header),
                    "store_bytes_used": kvp.kvp_store_bytes_used(store)},
         "roofline": {"bound": "hbm", "kernel": "assemble_vec_kernel (all layers, one launch)",

@@ -227,12 +227,6 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
     // ordinary global loads (its in-flight count is what the waits below rely on)
     int *blk_ids = (int *)(lds + STAGES * STAGE_BYTES);
     const int blk0 = SRC == SRC_PAGED ? (it.kv_begin >> a.cache.block_shift) : 0;
-    if (SRC == SRC_PAGED) {
-        const int nb = (kv_last >> a.cache.block_shift) - blk0 + 1;
-        for (int i = tid; i < nb; i += NT)
-            blk_ids[i] = a.cache.block_table[(int64_t)it.req * a.cache.max_blocks + blk0 + i];
-        __syncthreads();
-    }
     // contiguous layout: wave-uniform byte address of the item's first K / V row
     const int64_t contig_off = SRC == SRC_CONTIG
                                    ? (int64_t)it.req * a.cache.req_stride + (int64_t)a.layer * a.cache.layer_stride +
@@ -251,6 +245,14 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
     const int k_chunk = slot_chunk ^ ((4 * wave + slot_row) & 15);  // logical chunk fetched
     const int v_chunk = slot_chunk ^ (4 * slot_row);
     const int last_tile_rows = it.kv_end - it.kv_begin - (n_tiles - 1) * BN;  // 1..64 (cache modes)
+    // paged layout: the LDS word with the block id of load instruction i of tile tj.  The 4 rows
+    // of one instruction lie in one block (blocks hold a multiple of 4 rows, items start at a
+    // multiple of 64), clamped rows included, so the word is the same for the whole wave.
+    auto blk_word = [&](int tj, int i) -> int {
+        const int max_r = tj == n_tiles - 1 ? last_tile_rows - 1 : BN - 1;
+        const int rb = 4 * (NW * i + wave) < max_r ? 4 * (NW * i + wave) : max_r;
+        return blk_ids[((it.kv_begin + tj * BN + rb) >> a.cache.block_shift) - blk0];
+    };
     auto issue = [&](int tj) {
         const uint32_t st = lds_base + (uint32_t)((tj % STAGES) * STAGE_BYTES);
         if (SRC == SRC_PACKETS) {
@@ -292,12 +294,14 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
                 load_to_lds_16(kt, (uint32_t)(r * ROW_BYTES + 16 * k_chunk), dst);
                 load_to_lds_16(vt, (uint32_t)(r * ROW_BYTES + 16 * v_chunk), dst + TILE_BYTES);
             } else {
-                const int kv = it.kv_begin + tj * BN + r;
-                const int b = blk_ids[(kv >> a.cache.block_shift) - blk0];
-                const int slot = kv & ((1 << a.cache.block_shift) - 1);
-                const int64_t off = paged_base + ((((int64_t)b * a.n_kv + it.kv_head) << a.cache.block_shift) + slot) * D;
-                load_to_lds_16(kc + off + 8 * k_chunk, dst);
-                load_to_lds_16(vc + off + 8 * v_chunk, dst + TILE_BYTES);
+                // the block id is wave-uniform: the address is a scalar base plus a 32-bit lane offset
+                const int b = __builtin_amdgcn_readfirstlane(blk_word(tj, i));
+                const int64_t blk_off = paged_base + (((int64_t)b * a.n_kv + it.kv_head) << a.cache.block_shift) * D;
+                const int slot = (it.kv_begin + tj * BN + r) & ((1 << a.cache.block_shift) - 1);
+                const char *kt = uniform_ptr((const char *)(kc + blk_off));
+                const char *vt = uniform_ptr((const char *)(vc + blk_off));
+                load_to_lds_16(kt, (uint32_t)(slot * ROW_BYTES + 16 * k_chunk), dst);
+                load_to_lds_16(vt, (uint32_t)(slot * ROW_BYTES + 16 * v_chunk), dst + TILE_BYTES);
             }
         }
     };
@@ -383,6 +387,12 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
     int cur_delta = SRC == SRC_PACKETS && n_tiles > 0 ? a.tiles[it.kv_begin].pos : 0;
     KVP_STAMP(1);
     q_issue(cur_delta);  // first, so that the query arrives ahead of the tiles
+    if (SRC == SRC_PAGED) {  // the block ids travel while the query does
+        const int nb = (kv_last >> a.cache.block_shift) - blk0 + 1;
+        for (int i = tid; i < nb; i += NT)
+            blk_ids[i] = a.cache.block_table[(int64_t)it.req * a.cache.max_blocks + blk0 + i];
+        __syncthreads();
+    }
     // a first tile that cannot contain query rows can start its trip right away
     const bool early0 = n_tiles > 0 && (SRC == SRC_PACKETS ? a.tiles[it.kv_begin].kind == 0 : it.kv_begin + BN <= it.ctx_len);
     if (early0) issue(0);
