@@ -200,7 +200,7 @@ enum { SRC_CONTIG = 0, SRC_PAGED = 1, SRC_PACKETS = 2 };
 //                         (an in-workgroup split-KV that halves the serial chain of a
 //                         latency-bound item) and merge their (m, l, O) through LDS.
 template <int STAGES, int SRC, int NW, int KS>
-__global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
+__device__ __forceinline__ void attention_body(const AttnArgs &a)
 {
     constexpr int RW = NW / KS;    // waves per group
     constexpr int BM = 32 * RW;
@@ -714,7 +714,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
         }
     }
     if (it.part_slot >= 0) {
-        float *pp = a.partials + (int64_t)it.part_slot * BM * (D + 2);
+        // a slot holds a.bm rows (the launch's largest row block; BM <= a.bm), then m and l of each
+        float *pp = a.partials + (int64_t)it.part_slot * a.bm * (D + 2);
         if (KS == 1) {
             // The split's unnormalised O rows go through LDS so that they leave as whole 512-byte
             // rows (two per store instruction) instead of 32-byte pieces: each wave parks its
@@ -746,26 +747,53 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
                 }
         }
         if (row_ok && h == 0) {
-            pp[BM * D + rr] = m_ref;
-            pp[BM * D + BM + rr] = l_i;
+            pp[a.bm * D + rr] = m_ref;
+            pp[a.bm * D + a.bm + rr] = l_i;
         }
     }
     KVP_STAMP(31);
+}
+
+template <int STAGES, int SRC, int NW, int KS>
+__global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
+{
+    attention_body<STAGES, SRC, NW, KS>(a);
+}
+
+// 8 waves, 4 stages, the row block chosen item by item: 256 packed rows, or (AttnItem::half_block)
+// at most 128 rows handled by two wave groups that take alternate tiles.  A launch of 256-row
+// blocks uses it when some groups -- the last rows of a request -- fill at most half a block:
+// such an item then holds its compute unit for half the time.
+template <int SRC>
+__global__ __launch_bounds__(512, 2) void attention_mfma_mixed_kernel(AttnArgs a)
+{
+    if (a.items[blockIdx.x].half_block) attention_body<4, SRC, 8, 2>(a);
+    else attention_body<4, SRC, 8, 1>(a);
+}
+
+template <typename K> static int launch_kernel(K kernel, bool &attr_set, int lds_bytes, int threads, const AttnArgs &a, void *stream)
+{
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return (int)e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kernel, dim3(a.n_items), dim3(threads), lds_bytes, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
 }
 
 template <int SRC, int NW, int KS, int STAGES> static int launch_variant(const AttnArgs &a, void *stream)
 {
     constexpr int lds_bytes = STAGES * STAGE_BYTES + (SRC == SRC_PAGED ? MAX_BLOCK_IDS * 4 : 0);
     static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)attention_mfma_kernel<STAGES, SRC, NW, KS>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return (int)e;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL((attention_mfma_kernel<STAGES, SRC, NW, KS>), dim3(a.n_items), dim3(64 * NW), lds_bytes,
-                       (hipStream_t)stream, a);
-    return (int)hipGetLastError();
+    return launch_kernel(attention_mfma_kernel<STAGES, SRC, NW, KS>, attr_set, lds_bytes, 64 * NW, a, stream);
+}
+
+template <int SRC> static int launch_mixed(const AttnArgs &a, void *stream)
+{
+    constexpr int lds_bytes = 4 * STAGE_BYTES + (SRC == SRC_PAGED ? MAX_BLOCK_IDS * 4 : 0);
+    static bool attr_set = false;
+    return launch_kernel(attention_mfma_mixed_kernel<SRC>, attr_set, lds_bytes, 512, a, stream);
 }
 
 template <int NW, int KS, int STAGES> static int launch_nw(const AttnArgs &a, void *stream)
@@ -775,12 +803,17 @@ template <int NW, int KS, int STAGES> static int launch_nw(const AttnArgs &a, vo
                                : launch_variant<SRC_CONTIG, NW, KS, STAGES>(a, stream);
 }
 
-// a.bm selects the row block: 256 packed rows (8 waves) or 128.  128-row blocks run as 4 waves
+// a.bm selects the row block: 256 packed rows (8 waves; a.mixed: with half blocks among them,
+// see above) or 128.  128-row blocks run as 4 waves
 // with two tile stages (two workgroups per CU), or -- a.split_in_wg, chosen when the launch
 // has at most one item per CU -- as 8 waves in two groups that take alternate tiles.
 int launch_attention_mfma(const AttnArgs &a, void *stream)
 {
     if (a.d != D || (a.bm != 128 && a.bm != 256)) return (int)hipErrorInvalidValue;
+    if (a.bm == 256 && a.mixed) {
+        if (a.tiles) return (int)hipErrorInvalidValue;  // the in-place path plans 128-row blocks only
+        return a.cache.layout != 0 ? launch_mixed<SRC_PAGED>(a, stream) : launch_mixed<SRC_CONTIG>(a, stream);
+    }
     if (a.bm == 256) return launch_nw<8, 1, 4>(a, stream);
     return a.split_in_wg ? launch_nw<8, 2, 4>(a, stream) : launch_nw<4, 1, 2>(a, stream);
 }

@@ -82,7 +82,8 @@ struct AttnItem {
     int32_t part_slot;                       // partial slot to write, or -1: write `out` directly
     int32_t n_q;                             // query rows of the request
     int32_t pos0;                            // position of query row 0 (rows and positions differ with compressed packets)
-    int32_t pad[3];
+    int32_t half_block;                      // MFMA kernel, launches of 256-row blocks: this group has at most 128 rows
+    int32_t pad[2];
 };
 static_assert(sizeof(AttnItem) == 64, "AttnItem is 64 bytes");
 
@@ -118,6 +119,7 @@ struct AttnArgs {
     void *out;        // [tot_q][Hq][d]
     int32_t n_items, n_groups, layer, n_q_heads, n_kv, d, bm, g;
     int32_t split_in_wg;  // MFMA kernel, 128-row blocks: two wave groups take alternate tiles
+    int32_t mixed;        // MFMA kernel, 256-row blocks: some items are half blocks (AttnItem::half_block)
     int32_t part_stride;  // partial slots per group
     int32_t max_group_rows;  // largest n_rows among the groups that are split (the combine grid covers no more)
     float scale_log2e;  // log2(e) / sqrt(d)

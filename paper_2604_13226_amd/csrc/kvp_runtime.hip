@@ -151,7 +151,7 @@ struct kvp_store {
         const AttnItem *items_dev = nullptr;
         const AttnTile *tiles_dev = nullptr;
         int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0, part_stride = 1, max_group_rows = 0;
-        bool any_split = false;
+        bool any_split = false, mixed = false;
         uint64_t need = 0;
     } pk;                           // kvp_prefill_packets
     std::deque<PrefillCached> pf_set;  // kvp_query_prefill
@@ -166,6 +166,7 @@ struct kvp_store {
     int force_generic = 0;
     int target_items = 0;  // 0: three quarters of the CU count (measured optimum at 8K context)
     int asm_tile_rows = 32, asm_nontemporal = 0;
+    int mixed_blocks = 1;  // test knob (KVP_ATTN_MIXED=0): no half blocks in launches of 256-row blocks
     int plan_copy_engine = 0;  // test knob: plans go up with hipMemcpyAsync instead of the upload kernel
     int force_bm = 0;  // test knob: row-block size of the MFMA attention kernel
     int force_split_in_wg = -1;  // test knob: 0 / 1 forces the 4-wave / 8-wave-in-two-groups shape of 128-row blocks
@@ -507,6 +508,7 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
     const char *nt = getenv("KVP_ASM_NONTEMPORAL");
     if (nt) s->asm_nontemporal = nt[0] == '1';
     if (const char *pc = getenv("KVP_PLAN_COPY_ENGINE")) s->plan_copy_engine = pc[0] == '1';
+    if (const char *mb = getenv("KVP_ATTN_MIXED")) s->mixed_blocks = mb[0] != '0';
     if (const char *fb = getenv("KVP_ATTN_BM")) s->force_bm = atoi(fb);
     if (const char *fd = getenv("KVP_ATTN_SPLIT_IN_WG")) s->force_split_in_wg = atoi(fd) != 0;
     const char *ti = getenv("KVP_ATTN_TARGET_ITEMS");  // test knob: how finely split-KV cuts
@@ -797,10 +799,13 @@ void assign_part_slots(std::vector<AttnGroup> &groups, std::vector<AttnItem> &it
 // blocks) are therefore placed 8 apart, next to each other in launch order: they run on
 // one XCD at about the same time and all but the first find the tiles in its L2.  Cohorts
 // of unequal size are padded with null items (n_rows = 0: the workgroup exits at once).
+// Cohorts go out longest first (kv rows x query rows of their largest member): workgroups
+// start in index order as compute units fall free, so the long items of a ragged batch start
+// early and the short ones fill the end of the launch.
 void xcd_order(std::vector<AttnItem> &items)
 {
     constexpr int XCDS = 8;
-    struct Cohort { int64_t key; std::vector<int> members; };
+    struct Cohort { int64_t key; std::vector<int> members; int64_t work = 0; };
     std::vector<Cohort> cohorts;
     std::unordered_map<int64_t, int> index;
     bool shared = false;
@@ -811,14 +816,22 @@ void xcd_order(std::vector<AttnItem> &items)
         if (f == index.end()) {
             index[key] = (int)cohorts.size();
             cohorts.push_back(Cohort{key, {i}});
+            f = index.find(key);
         } else {
             cohorts[f->second].members.push_back(i);
             shared = true;
         }
+        Cohort &c = cohorts[f->second];
+        c.work = std::max(c.work, (int64_t)(it.kv_end - it.kv_begin) * it.n_rows);
     }
-    if (!shared) return;
+    std::stable_sort(cohorts.begin(), cohorts.end(), [](const Cohort &x, const Cohort &y) { return x.work > y.work; });
     std::vector<AttnItem> out;
     out.reserve(items.size() + 64);
+    if (!shared) {
+        for (const Cohort &c : cohorts) out.push_back(items[c.members[0]]);
+        items.swap(out);
+        return;
+    }
     AttnItem null_item{};
     null_item.group = -1;
     for (size_t c0 = 0; c0 < cohorts.size(); c0 += XCDS) {
@@ -844,6 +857,7 @@ struct PrefillPlan {
     std::vector<AttnItem> items;
     int n_slots = 0, part_stride = 1, max_group_rows = 0;
     bool any_split = false;
+    bool mixed = false;  // MFMA kernel, 256-row blocks: some groups are half blocks
 };
 
 constexpr int MFMA_BM = 128;
@@ -920,6 +934,10 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
                 gp.kv_head = h;
                 gp.m0 = m0;
                 gp.n_rows = std::min(p.bm, M - m0);
+                // a block of 256 of which at most half is filled (the last rows of a request)
+                // runs as a half block: same compute unit, half the time
+                const bool half_block = mfma && p.bm == 2 * MFMA_BM && gp.n_rows <= MFMA_BM && s->mixed_blocks;
+                if (half_block) p.mixed = true;
                 const int t_last = (m0 + gp.n_rows - 1) / gq;
                 const int vis = rq.ctx_len + t_last + 1;
                 gp.n_splits = (vis + split_len - 1) / split_len;
@@ -937,6 +955,7 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
                     it.split = sp;
                     it.kv_begin = sp * split_len;
                     it.kv_end = std::min(vis, (sp + 1) * split_len);
+                    it.half_block = half_block ? 1 : 0;
                     it.req = r;
                     it.kv_head = h;
                     it.m0 = m0;
@@ -1096,6 +1115,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         pf.bt_stride = bt_stride;
         pf.tot_q = tot_q;
         pf.any_split = p.any_split;
+        pf.mixed = p.mixed;
         pf.part_stride = p.part_stride;
         pf.max_group_rows = p.max_group_rows;
         pf.need = need;
@@ -1171,6 +1191,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     at.d = g.head_dim;
     at.bm = pf.bm;
     at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : 0;
+    at.mixed = pf.mixed ? 1 : 0;
     at.part_stride = pf.part_stride;
     at.max_group_rows = pf.max_group_rows;
     at.g = g.n_q_heads / g.n_kv_heads;
@@ -1391,6 +1412,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     at.d = g.head_dim;
     at.bm = pk.bm;
     at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : 0;
+    at.mixed = 0;
     at.part_stride = pk.part_stride;
     at.max_group_rows = pk.max_group_rows;
     at.g = g.n_q_heads / g.n_kv_heads;

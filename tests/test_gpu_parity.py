@@ -233,6 +233,31 @@ def test_split_invariance(gpu_device):
         compare(w, got, ref)
 
 
+@pytest.mark.parametrize("paged", [False, True])
+@pytest.mark.parametrize("target", [None, "3000"])
+def test_half_blocks_in_a_launch_of_256_row_blocks(gpu_device, paged, target):
+    """A request with 4 n_q >= 256 packed rows makes the launch use 256-row blocks; groups of at
+    most 128 rows (the last rows of a request, or a whole small request) then run as half blocks
+    inside the same launch -- unsplit and, with many work items asked for, split over KV with
+    partial slots of the launch's 256-row layout."""
+    w = W.llama_long_b8(n_layers=1, n_packets=6, batch=4, k=3, n_q=89)      # 356 rows: 256 + 100
+    w.packet_lens[:] = [700, 130, 64, 529, 300, 63]
+    w.requests[1].n_q = 114                                                # 456 rows: 256 + 200 (a full block)
+    w.requests[2].n_q = 20                                                 # 80 rows: one half block
+    w.requests[3].n_q = 64                                                 # 256 rows exactly
+    w.paged = paged
+    if target:
+        os.environ["KVP_ATTN_TARGET_ITEMS"] = target
+    try:
+        got = run_workload(w)
+    finally:
+        os.environ.pop("KVP_ATTN_TARGET_ITEMS", None)
+    import paper_2604_13226_amd as kvp
+    plan = kvp.kvp_debug_last_plan(got["store"], 1)
+    assert plan[1] == 256                                                   # the launch's row block
+    compare(w, got, oracle_workload(w))
+
+
 def test_generic_kernel_on_bf16_model_shape(gpu_device):
     w = W.llama_k5(n_layers=1, n_packets=8)
     w.requests[0].packet_ids = w.requests[0].packet_ids[:2]
