@@ -151,7 +151,7 @@ struct kvp_store {
         const AttnItem *items_dev = nullptr;
         const AttnTile *tiles_dev = nullptr;
         int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0, part_stride = 1, max_group_rows = 0;
-        bool any_split = false, mixed = false;
+        bool any_split = false, mixed = false, split_in_wg = false;
         uint64_t need = 0;
     } pk;                           // kvp_prefill_packets
     std::deque<PrefillCached> pf_set;  // kvp_query_prefill
@@ -858,21 +858,30 @@ struct PrefillPlan {
     int n_slots = 0, part_stride = 1, max_group_rows = 0;
     bool any_split = false;
     bool mixed = false;  // MFMA kernel, 256-row blocks: some groups are half blocks
+    bool split_in_wg = false;  // MFMA kernel, 128-row blocks: 8 waves in two groups on alternate tiles
 };
 
 constexpr int MFMA_BM = 128;
 constexpr int GENERIC_BM = 8;
 constexpr int MAX_SPLITS = 64;
 
+// Many tiles per compute unit to stream with 128-row blocks (long contexts, few query rows:
+// HBM-bound): such launches take one 8-wave workgroup per CU whose two wave groups work on
+// alternate tiles, four tile stages deep -- bytes in flight are what counts there (measured on 8
+// requests of 16.9K context: 32 query rows 158 us with 192 four-wave items, 133 us with 512,
+// 126 us this way; one query row 119 -> 111 us).
+bool streams_many_tiles(const kvp_store *s, int64_t tiles, int bm)
+{
+    return bm == 128 && tiles >= 16 * (int64_t)s->n_cu;
+}
+
 // Work items a launch should have.  Three quarters of the CU count when the call reads little
 // (one 8K request: every extra split costs partial traffic and the items are latency-bound
-// anyway); two per CU -- the 128-row kernel's occupancy -- once there are many tiles per CU to
-// stream, where bytes in flight are what counts (measured: 8 requests of 16.9K context with 32
-// query rows, 158 -> 133 us per layer).
+// anyway); one per CU for the streaming shape above.
 int target_items(const kvp_store *s, int64_t tiles = 0, int bm = 0)
 {
     if (s->target_items > 0) return s->target_items;
-    if (bm == 128 && tiles >= 16 * (int64_t)s->n_cu) return 2 * s->n_cu;
+    if (streams_many_tiles(s, tiles, bm)) return s->n_cu;
     return s->n_cu * 3 / 4;
 }
 
@@ -918,6 +927,7 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
         tiles += (int64_t)g.n_kv_heads * (((int64_t)p.reqs[r].n_q * gq + p.bm - 1) / p.bm) * ((p.reqs[r].ctx_len + p.reqs[r].n_q + 63) / 64);
     int want = (int)std::min<int64_t>(MAX_SPLITS, (target_items(s, tiles, mfma ? p.bm : 0) + n_groups - 1) / n_groups);
     if (want < 1) want = 1;
+    p.split_in_wg = mfma && streams_many_tiles(s, tiles, p.bm);
     for (int r = 0; r < n_req; ++r) {
         const ReqMeta &rq = p.reqs[r];
         if (rq.n_q == 0) continue;
@@ -1116,6 +1126,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         pf.tot_q = tot_q;
         pf.any_split = p.any_split;
         pf.mixed = p.mixed;
+        pf.split_in_wg = p.split_in_wg;
         pf.part_stride = p.part_stride;
         pf.max_group_rows = p.max_group_rows;
         pf.need = need;
@@ -1190,7 +1201,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     at.n_kv = g.n_kv_heads;
     at.d = g.head_dim;
     at.bm = pf.bm;
-    at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : 0;
+    at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : (pf.split_in_wg ? 1 : 0);
     at.mixed = pf.mixed ? 1 : 0;
     at.part_stride = pf.part_stride;
     at.max_group_rows = pf.max_group_rows;

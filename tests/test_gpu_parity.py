@@ -443,6 +443,44 @@ def test_full_size_long_context_batch_sampled(gpu_device):
     _compare_sampled(w, got, oracle_workload(w, requests=sample), sample, [0])
 
 
+@pytest.mark.parametrize("n_q", [32, 1])
+def test_full_size_long_context_few_query_rows_sampled(gpu_device, n_q):
+    """The long-context batch with 32 query rows, and one decode step over it: HBM-bound launches
+    that stream many tiles per compute unit, which the planner gives to 8-wave workgroups whose
+    two wave groups take alternate tiles (merged through LDS) with one work item per CU."""
+    import paper_2604_13226_amd as kvp
+    w = W.llama_long_b8(n_layers=1, n_q=n_q)
+    sample = [1, 6]
+    got = run_workload(w)
+    plan = kvp.kvp_debug_last_plan(got["store"], 1)
+    assert plan[1] == 128 and 200 <= plan[3] <= 264                        # 128-row blocks, about one item per CU
+    _compare_sampled(w, got, oracle_workload(w, requests=sample), sample, [0])
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_two_wave_groups_on_alternate_tiles(gpu_device, paged):
+    """The 8-wave shape of 128-row blocks forced on small ragged requests: odd and even tile
+    counts, a single tile, items split over KV and unsplit, query rows inside the last tile."""
+    w = W.llama_long_b8(n_layers=2, n_packets=6, batch=4, k=3, n_q=30)
+    w.packet_lens[:] = [700, 130, 64, 529, 300, 63]
+    w.requests[1].packet_ids = [2]                 # one tile of context
+    w.requests[1].n_q = 5
+    w.requests[2].packet_ids = []                  # no context at all
+    w.requests[3].n_q = 1
+    w.paged = paged
+    ref = oracle_workload(w)
+    for target in (None, "2000"):
+        os.environ["KVP_ATTN_SPLIT_IN_WG"] = "1"
+        if target:
+            os.environ["KVP_ATTN_TARGET_ITEMS"] = target
+        try:
+            got = run_workload(w)
+        finally:
+            os.environ.pop("KVP_ATTN_SPLIT_IN_WG", None)
+            os.environ.pop("KVP_ATTN_TARGET_ITEMS", None)
+        compare(w, got, ref)
+
+
 def test_full_size_serving_mix_sampled(gpu_device):
     """Config 5 (64 requests, paged cache, block 16, Zipf retrieval) on one layer: the oracle
     checks four of the 64 requests, among them the longest and the shortest context."""
