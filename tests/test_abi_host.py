@@ -238,6 +238,39 @@ def test_prefill_plan_covers_every_row_and_kv_exactly_once(cfg):
     assert bound >= need
 
 
+def test_paged_items_stay_within_the_block_id_limit(monkeypatch):
+    """Paged layout: an item keeps its block ids in LDS, at most 2047 of them, so a long context
+    is cut further than the work-item target asks for."""
+    monkeypatch.setenv("KVP_ATTN_TARGET_ITEMS", "1")
+    s = dry_store(n_q_heads=8, n_kv_heads=2, max_positions=1 << 17)
+    ctx, n_q = [70000, 40000, 100], [8, 40, 3]
+    n_blk = [(c + q + 15) // 16 for c, q in zip(ctx, n_q)]
+    table = np.zeros((3, max(n_blk)), np.int32)
+    at = 0
+    for r in range(3):
+        table[r, :n_blk[r]] = np.arange(at, at + n_blk[r])
+        at += n_blk[r]
+    cache = kvp.Cache.dry(3, layout=kvp.KVP_PAGED, n_blocks=at, block_table=table, block_size=16)
+    cache.ctx_len[:3] = ctx
+    q_off = np.concatenate([[0], np.cumsum(n_q)]).astype(np.int32)
+    kvp.kvp_query_prefill(s, cache, 0, None, None, None, q_off, None, None)
+    kind, bm, groups, items, slots, need = _attn_plan(s)
+    assert kind == 1
+    per_group = {}
+    for g_, sp, b, e in items:
+        if g_ < 0:                                             # padding of the launch order
+            continue
+        assert 0 < e - b <= 2047 * 16 and b % 64 == 0
+        assert (e - 1) // 16 - b // 16 + 1 <= 2047             # block ids of the item
+        per_group.setdefault(int(g_), []).append((int(b), int(e)))
+    for gi, (r, h, m0, n_rows, part0, n_splits) in enumerate(groups):
+        rng = sorted(per_group[gi])
+        assert rng[0][0] == 0 and all(e0 == b1 for (_, e0), (b1, _) in zip(rng, rng[1:]))
+        assert rng[-1][1] == ctx[r] + (m0 + n_rows - 1) // 4 + 1
+        assert len(rng) == {0: 3, 1: 2, 2: 1}[int(r)]           # 70008 -> 3 ranges, 40040 -> 2, 103 -> 1
+    assert kvp.kvp_prefill_workspace_bytes(s, 3, int(q_off[-1]), 70008) >= need
+
+
 def test_prefill_errors():
     s = dry_store(max_positions=1000)
     cache = kvp.Cache.dry(1, t_cap=100)

@@ -481,6 +481,25 @@ def test_two_wave_groups_on_alternate_tiles(gpu_device, paged):
         compare(w, got, ref)
 
 
+def test_paged_context_longer_than_one_items_block_ids(gpu_device):
+    """A paged context of 34 K rows with one work item asked for: the item limit of 2047 block
+    ids forces two kv ranges, merged by the combine kernel."""
+    w = W.llama_long_b8(n_layers=1, n_packets=4, batch=1, k=4, n_q=6)
+    w.n_q_heads, w.n_kv_heads = 8, 2
+    w.packet_lens[:] = [16000, 9000, 8990, 40]
+    w.requests[0].packet_ids = [0, 1, 2, 3]
+    w.paged = True
+    os.environ["KVP_ATTN_TARGET_ITEMS"] = "1"
+    try:
+        got = run_workload(w)
+    finally:
+        os.environ.pop("KVP_ATTN_TARGET_ITEMS", None)
+    import paper_2604_13226_amd as kvp
+    plan = kvp.kvp_debug_last_plan(got["store"], 1)
+    assert plan[3] == 2 * 2                                   # two kv heads x two forced ranges
+    compare(w, got, oracle_workload(w))
+
+
 def test_full_size_serving_mix_sampled(gpu_device):
     """Config 5 (64 requests, paged cache, block 16, Zipf retrieval) on one layer: the oracle
     checks four of the 64 requests, among them the longest and the shortest context."""
