@@ -39,8 +39,10 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        build()
-        L = ctypes.CDLL(_LIB)
+        # KVP_ORACLE_LIB: tests/test_oracle_mutants.py points the pins at deliberately broken
+        # copies of the oracle to show that they notice; nothing else sets it.
+        path = os.environ.get("KVP_ORACLE_LIB") or build()
+        L = ctypes.CDLL(path)
         vp, i32, i64, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
         L.kvo_inv_freq.argtypes = [dbl, i32, vp]
         L.kvo_inv_freq.restype = None
