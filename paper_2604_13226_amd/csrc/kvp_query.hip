@@ -197,15 +197,19 @@ __global__ __launch_bounds__(256) void combine_wave_kernel(AttnArgs a)
     const int m = gp.m0 + rr;
     const int t = m / a.g, hq = gp.kv_head * a.g + m % a.g;
     T *op = (T *)a.out + ((int64_t)(gp.q_off + t) * a.n_q_heads + hq) * d;
+    // Every lane runs every trip of the loops below (the weights travel by lane shuffles, which
+    // need their source lanes active); `on` guards the loads and stores of lanes past the row.
     if ((d & 3) == 0) {
-        for (int e = 4 * li; e < d; e += 128) {
+        for (int e0 = 0; e0 < d; e0 += 128) {
+            const int e = e0 + 4 * li;
+            const bool on = e < d;
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
             int s_from = 0;
-            if (e == 4 * li) {  // the pieces already on their way
+            if (e0 == 0) {  // the pieces already on their way
 #pragma unroll
                 for (int i = 0; i < EARLY; ++i) {
                     const int sq = 2 * i + hf, sp = sq < ns ? sq : ns - 1;
-                    const float ws = __shfl(w, sp, 64);  // executed by all 64 lanes
+                    const float ws = __shfl(w, sp, 64);
                     if (sq < ns) { acc.x += v0[i].x * ws; acc.y += v0[i].y * ws; acc.z += v0[i].z * ws; acc.w += v0[i].w * ws; }
                 }
                 s_from = 2 * EARLY;
@@ -215,14 +219,14 @@ __global__ __launch_bounds__(256) void combine_wave_kernel(AttnArgs a)
                 const int sq = s2 + hf, sp = sq < ns ? sq : ns - 1;
                 float ws = __shfl(w, sp, 64);
                 if (sq >= ns) ws = 0.f;
-                const float4 v = *(const float4 *)(row + sp * slot + e);
+                const float4 v = on ? *(const float4 *)(row + sp * slot + e) : make_float4(0.f, 0.f, 0.f, 0.f);
                 acc.x += v.x * ws; acc.y += v.y * ws; acc.z += v.z * ws; acc.w += v.w * ws;
             }
             acc.x += __shfl_xor(acc.x, 32, 64);
             acc.y += __shfl_xor(acc.y, 32, 64);
             acc.z += __shfl_xor(acc.z, 32, 64);
             acc.w += __shfl_xor(acc.w, 32, 64);
-            if (hf == 0) {
+            if (hf == 0 && on) {
                 st_elem(op + e, acc.x * inv);
                 st_elem(op + e + 1, acc.y * inv);
                 st_elem(op + e + 2, acc.z * inv);
@@ -230,10 +234,15 @@ __global__ __launch_bounds__(256) void combine_wave_kernel(AttnArgs a)
             }
         }
     } else {
-        for (int e = lane; e < d; e += 64) {
+        for (int e0 = 0; e0 < d; e0 += 64) {
+            const int e = e0 + lane;
+            const bool on = e < d;
             float acc = 0.f;
-            for (int sp = 0; sp < ns; ++sp) acc += row[sp * slot + e] * __shfl(w, sp, 64);
-            st_elem(op + e, acc * inv);
+            for (int sp = 0; sp < ns; ++sp) {
+                const float ws = __shfl(w, sp, 64);
+                if (on) acc += row[sp * slot + e] * ws;
+            }
+            if (on) st_elem(op + e, acc * inv);
         }
     }
 }

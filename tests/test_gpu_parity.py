@@ -70,6 +70,39 @@ def test_small_ragged_shapes(gpu_device, case, dtype):
     compare(w, run_workload(w), oracle_workload(w))
 
 
+def _random_geometry(seed):
+    """A seeded random batch: 1-4 requests, ragged packets, ragged (some empty) queries, head
+    groupings 1 / 4 / 7, every head dim the vector gather takes, either dtype and layout, with or
+    without the shared header, sometimes a caller prefix below base_pos."""
+    rng = np.random.default_rng(seed)
+    dtype = "bf16" if rng.random() < 0.6 else "f32"
+    d = int(rng.choice([64, 128, 128, 128, 128, 256])) if dtype == "bf16" else int(rng.choice([8, 64, 128]))
+    n_kv = int(rng.choice([1, 2, 4]))
+    g = int(rng.choice([1, 4, 7]))
+    n_req = int(rng.integers(1, 5))
+    n_packets = int(rng.integers(2, 7))
+    big = dtype == "bf16" and d == 128 and rng.random() < 0.75          # the MFMA kernel with several row blocks
+    w = W.random_small(seed, dtype=dtype, d=d, n_q_heads=n_kv * g, n_kv_heads=n_kv, n_layers=int(rng.integers(1, 3)),
+                       n_packets=n_packets, k=1, n_q=1, max_len=int(rng.choice([9, 70, 300])), n_req=n_req)
+    for rq in w.requests:
+        rq.packet_ids = [int(x) for x in rng.integers(0, n_packets, size=int(rng.integers(0, 6)))]
+        rq.n_q = int(rng.integers(0, 150 if big else 12))
+        rq.base_pos = int(rng.integers(0, 40)) if rng.random() < 0.3 else 0
+    if all(rq.n_q == 0 for rq in w.requests):
+        w.requests[0].n_q = 3
+    w.paged = bool(rng.random() < 0.4)
+    w.block_size = int(rng.choice([16, 32, 64])) if big or dtype == "bf16" else int(rng.choice([4, 16]))
+    if rng.random() < 0.3:
+        w.n_header, w.shared_header = int(rng.choice([1, 4, 8])), True
+    return w
+
+
+@pytest.mark.parametrize("seed", range(300, 340))
+def test_random_geometries(gpu_device, seed):
+    w = _random_geometry(seed)
+    compare(w, run_workload(w), oracle_workload(w))
+
+
 @pytest.mark.parametrize("mk", [
     lambda: W.llama_k5(n_layers=2, n_packets=16),
     lambda: W.qwen_k20(n_layers=2, n_packets=40),
@@ -255,6 +288,27 @@ def test_half_blocks_in_a_launch_of_256_row_blocks(gpu_device, paged, target):
     import paper_2604_13226_amd as kvp
     plan = kvp.kvp_debug_last_plan(got["store"], 1)
     assert plan[1] == 256                                                   # the launch's row block
+    compare(w, got, oracle_workload(w))
+
+
+@pytest.mark.parametrize("dtype,d,ctx_rows", [("f32", 8, 600), ("f32", 2, 300), ("bf16", 64, 1300), ("f32", 24, 700),
+                                              ("bf16", 256, 900)])
+def test_many_splits_with_small_head_dims(gpu_device, dtype, d, ctx_rows):
+    """More kv ranges per group than a row has 16-byte chunks (or columns): the merge of the
+    splits hands the weights around by lane shuffles, which must not depend on how many lanes
+    a row of head_dim d keeps busy."""
+    w = W.random_small(71, dtype=dtype, d=d, n_q_heads=4, n_kv_heads=2, n_layers=1, n_packets=3, k=3, n_q=5, max_len=9)
+    w.packet_lens[:] = [ctx_rows // 2, ctx_rows // 3, ctx_rows - ctx_rows // 2 - ctx_rows // 3]
+    w.requests[0].packet_ids = [0, 1, 2]
+    os.environ["KVP_ATTN_TARGET_ITEMS"] = "4000"
+    try:
+        got = run_workload(w)
+    finally:
+        os.environ.pop("KVP_ATTN_TARGET_ITEMS", None)
+    import paper_2604_13226_amd as kvp
+    plan = kvp.kvp_debug_last_plan(got["store"], 1)
+    groups = plan[6:6 + 6 * int(plan[2])].reshape(int(plan[2]), 6)
+    assert groups[:, 5].max() == (ctx_rows + 5 + 63) // 64 > 4              # one range per 64 rows
     compare(w, got, oracle_workload(w))
 
 
