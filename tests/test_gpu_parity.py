@@ -737,6 +737,88 @@ def test_pruned_headline_workload(gpu_device):
         assert torch.equal(out.view(torch.int16), first_pass[layer].view(torch.int16)), layer
 
 
+def _check_pruned_workload(w, tag):
+    """A workload whose packets are all pruned (w.prune), any number of requests, base_pos 0:
+    one assembly over all layers, then every layer's prefill, against the oracle layer by layer."""
+    import paper_2604_13226_amd as kvp
+    import oracle
+    f = oracle.inv_freq(w.rope_base, w.head_dim)
+    n_req, L = len(w.requests), w.n_layers
+    store = build_store(w, kvp)
+    cache = make_cache(w, kvp, store)
+    kvp.kvp_assemble(store, [(rq.packet_ids, 0) for rq in w.requests], cache)
+    assert [int(x) for x in cache.ctx_len[:n_req]] == [w.ctx_len(r) for r in range(n_req)]
+    q_off = np.zeros(n_req + 1, np.int32)
+    for r in range(n_req):
+        q_off[r + 1] = q_off[r] + w.requests[r].n_q
+    rows_max = max(w.ctx_len(r) + w.requests[r].n_q for r in range(n_req))
+    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, n_req, int(q_off[-1]), rows_max))
+    for layer in range(L):
+        parts = [w.query(r, layer, "cuda") for r in range(n_req)]
+        q, kn, vn = (torch.cat([p_[i] for p_ in parts]).contiguous() for i in range(3))
+        out = torch.full_like(q, float("nan"))
+        kvp.kvp_query_prefill(store, cache, layer, q, kn, vn, q_off, ws, out)
+        torch.cuda.synchronize()
+        out = out.float().cpu().numpy().astype(np.float64)
+        for r, rq in enumerate(w.requests):
+            kv = [tuple(W.to_numpy(x) for x in w.packet_kv(p)) for p in rq.packet_ids]
+            keep = [w.kept_rows(p, layer) for p in rq.packet_ids]
+            ks = [np.ascontiguousarray(k[layer][:, s_]) for (k, _), s_ in zip(kv, keep)]
+            vs = [np.ascontiguousarray(v[layer][:, s_]) for (_, v), s_ in zip(kv, keep)]
+            spans = [int(w.packet_lens[p]) for p in rq.packet_ids]
+            rows_l = w.layer_rows(r, layer)
+            if ks:
+                Ko, Vo, rows, pos_end = oracle.assemble_layer_spans(w.dtype, ks, vs, spans, f, 0, t_cap=rows_l + rq.n_q)
+            else:                      # no packets: an empty layer for the query rows to go into
+                Ko = np.zeros((w.n_kv_heads, rq.n_q, w.head_dim), np.float32 if w.dtype == "f32" else np.uint16)
+                Vo, rows, pos_end = Ko.copy(), 0, 0
+            assert rows == rows_l == int(cache.ctx_rows[r][layer]) and pos_end == w.ctx_len(r)
+            if rq.n_q == 0 and not ks:
+                continue
+            ref = oracle.query_prefill_at(w.dtype, *(W.to_numpy(x) for x in parts[r]), f, rows, pos_end, Ko, Vo)
+            kg, vg = (W.to_numpy(x) for x in cache.logical(r, layer, rows + rq.n_q))
+            assert np.array_equal(kg, Ko[:, :rows + rq.n_q]), (tag, r, layer, "K")
+            assert np.array_equal(vg, Vo[:, :rows + rq.n_q]), (tag, r, layer, "V")
+            if rq.n_q:
+                check_output(out[q_off[r]:q_off[r + 1]], ref, w.dtype, (tag, r, layer))
+
+
+@pytest.mark.parametrize("seed", range(500, 516))
+def test_random_geometries_pruned(gpu_device, seed):
+    """Seeded random batches whose packets are all pruned, a different subset in every layer."""
+    w = _random_geometry(seed)
+    rng = np.random.default_rng(seed + 1)
+    for rq in w.requests:
+        rq.base_pos = 0
+    w.shared_header = False
+    w.n_layers = int(rng.integers(1, 4))
+    lo = float(rng.uniform(0.0, 0.6))
+    w.prune = (lo, min(1.0, lo + float(rng.uniform(0.0, 0.5))))
+    _check_pruned_workload(w, ("pruned", seed))
+
+
+@pytest.mark.parametrize("seed", range(400, 416))
+def test_random_geometries_in_place(gpu_device, seed):
+    """Seeded random bf16 batches through kvp_prefill_packets (attention in place, no cache)."""
+    rng = np.random.default_rng(seed)
+    n_req, n_packets = int(rng.integers(1, 5)), int(rng.integers(2, 7))
+    g = int(rng.choice([1, 4, 7]))
+    n_kv = int(rng.choice([1, 2, 4]))
+    w = W.random_small(seed, dtype="bf16", d=128, n_q_heads=n_kv * g, n_kv_heads=n_kv, n_layers=int(rng.integers(1, 3)),
+                       n_packets=n_packets, k=1, n_q=1, max_len=int(rng.choice([9, 70, 300, 700])), n_req=n_req)
+    for rq in w.requests:
+        rq.packet_ids = [int(x) for x in rng.integers(0, n_packets, size=int(rng.integers(0, 6)))]
+        rq.n_q = int(rng.integers(0, 150))
+    if all(rq.n_q == 0 for rq in w.requests):
+        w.requests[0].n_q = 3
+    if rng.random() < 0.4:
+        w.n_header, w.shared_header = int(rng.choice([1, 4, 8])), True
+    w.name = "in place %d" % seed
+    layers = list(range(w.n_layers))
+    outs, tails = _run_packets(w, layers)
+    _check_packets(w, layers, outs, tails, oracle_workload(w))
+
+
 @pytest.mark.parametrize("case", ["bf16", "bf16 paged", "f32", "mixed with compressed"])
 def test_shared_header_store_matches_whole_packets(gpu_device, case):
     """Sec. 4.1: the header is global, so its rows are the same in every packet and the store may
