@@ -312,6 +312,56 @@ def test_many_splits_with_small_head_dims(gpu_device, dtype, d, ctx_rows):
     compare(w, got, oracle_workload(w))
 
 
+def test_long_query_without_packets(gpu_device):
+    """No cached context at all (the baseline without packets) and 1500 query tokens: plain
+    causal self-attention over 24 tiles of query rows, 6000 packed rows per kv head."""
+    w = W.llama_long_b8(n_layers=1, n_packets=2, batch=2, k=1, n_q=1500)
+    w.n_q_heads, w.n_kv_heads = 8, 2
+    w.packet_lens[:] = [70, 64]
+    w.requests[0].packet_ids = []
+    w.requests[1].packet_ids = [1, 0]
+    w.requests[1].n_q = 700
+    compare(w, run_workload(w), oracle_workload(w))
+
+
+def test_side_stream_and_two_stores(gpu_device):
+    """The whole path on a stream other than the current one, with a second store of another
+    shape used in between (plans and their buffers belong to the store and the stream)."""
+    import paper_2604_13226_amd as kvp
+    wa = W.llama_k5(n_layers=2, n_packets=8)
+    wb = W.qwen_k20(n_layers=1, n_packets=24)
+    refs = [oracle_workload(wa), oracle_workload(wb)]
+    side = torch.cuda.Stream()
+    stores = [build_store(w, kvp) for w in (wa, wb)]
+    caches = [make_cache(w, kvp, st) for w, st in zip((wa, wb), stores)]
+    torch.cuda.synchronize()
+    outs = [dict(), dict()]
+    with torch.cuda.stream(side):
+        for i, (w, st, c) in enumerate(zip((wa, wb), stores, caches)):
+            kvp.kvp_assemble(st, [(rq.packet_ids, rq.base_pos) for rq in w.requests], c, stream=side)
+        wss = [kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(st, 1, w.requests[0].n_q, w.ctx_len(0) + w.requests[0].n_q))
+               for w, st in zip((wa, wb), stores)]
+        for layer in range(2):
+            for i, (w, st, c) in enumerate(zip((wa, wb), stores, caches)):      # the two stores take turns
+                if layer >= w.n_layers:
+                    continue
+                q, kn, vn = w.query(0, layer, "cuda")
+                out = torch.full_like(q, float("nan"))
+                kvp.kvp_query_prefill(st, c, layer, q, kn, vn, [0, w.requests[0].n_q], wss[i], out, stream=side)
+                outs[i][layer] = out
+    side.synchronize()
+    for i, w in enumerate((wa, wb)):
+        rows = w.ctx_len(0) + w.requests[0].n_q
+        for layer in range(w.n_layers):
+            k, v = caches[i].logical(0, layer, rows)
+            assert np.array_equal(W.to_numpy(k), refs[i]["k"][0][layer]), (w.name, layer, "K")
+            assert np.array_equal(W.to_numpy(v), refs[i]["v"][0][layer]), (w.name, layer, "V")
+            check_output(outs[i][layer].float().cpu().numpy().astype(np.float64), refs[i]["out"][0][layer], w.dtype,
+                         (w.name, "side stream", layer))
+    for st in stores:
+        kvp.kvp_store_destroy(st)
+
+
 def test_generic_kernel_on_bf16_model_shape(gpu_device):
     w = W.llama_k5(n_layers=1, n_packets=8)
     w.requests[0].packet_ids = w.requests[0].packet_ids[:2]
