@@ -108,24 +108,37 @@ __global__ __launch_bounds__(256) void attention_generic_kernel(AttnArgs a)
         float mx = -INFINITY, l = 0.f;
         int vis_end = rq.ctx_len + t + 1;  // causal among the query rows, full over the prefix
         int end = it.kv_end < vis_end ? it.kv_end : vis_end;
-        for (int u = it.kv_begin; u < end; ++u) {
-            int64_t off = cache_row_off(a.cache, gp.req, a.layer, gp.kv_head, u, a.n_kv, d);
-            float part = 0.f, v[4];
+        // UB rows per trip: all their K and V loads are issued before the first is used, so a
+        // trip costs one memory round trip instead of UB
+        constexpr int UB = 8;
+        for (int u0 = it.kv_begin; u0 < end; u0 += UB) {
+            float kk[UB][4], v[UB][4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                int e = lane + 64 * j;
-                float kk = e < d ? ld_elem(kc + off + e) : 0.f;
-                v[j] = e < d ? ld_elem(vc + off + e) : 0.f;
-                part += q[j] * kk;
+            for (int i = 0; i < UB; ++i) {
+                const int u = u0 + i < end ? u0 + i : end - 1;  // rows past the range repeat the last one (unused)
+                const int64_t off = cache_row_off(a.cache, gp.req, a.layer, gp.kv_head, u, a.n_kv, d);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int e = lane + 64 * j;
+                    kk[i][j] = e < d ? ld_elem(kc + off + e) : 0.f;
+                    v[i][j] = e < d ? ld_elem(vc + off + e) : 0.f;
+                }
             }
-            float sc = wave_sum(part) * a.scale_log2e;
-            float mn = fmaxf(mx, sc);
-            float alpha = exp2f(mx - mn);  // exp2f(-inf) = 0 on the first row
-            float p = exp2f(sc - mn);
-            l = l * alpha + p;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) o[j] = o[j] * alpha + p * v[j];
-            mx = mn;
+            for (int i = 0; i < UB; ++i) {
+                if (u0 + i >= end) break;  // wave-uniform
+                float part = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) part += q[j] * kk[i][j];
+                float sc = wave_sum(part) * a.scale_log2e;
+                float mn = fmaxf(mx, sc);
+                float alpha = exp2f(mx - mn);  // exp2f(-inf) = 0 on the first row
+                float p = exp2f(sc - mn);
+                l = l * alpha + p;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) o[j] = o[j] * alpha + p * v[i][j];
+                mx = mn;
+            }
         }
         if (gp.n_splits == 1) {
             T *op = (T *)a.out + ((int64_t)(rq.q_off + t) * a.n_q_heads + hq) * d;
