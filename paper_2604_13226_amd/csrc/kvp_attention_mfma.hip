@@ -811,7 +811,7 @@ int launch_attention_mfma(const AttnArgs &a, void *stream)
 {
     if (a.d != D || (a.bm != 128 && a.bm != 256)) return (int)hipErrorInvalidValue;
     if (a.bm == 256 && a.mixed) {
-        if (a.tiles) return (int)hipErrorInvalidValue;  // the in-place path plans 128-row blocks only
+        if (a.tiles) return launch_mixed<SRC_PACKETS>(a, stream);
         return a.cache.layout != 0 ? launch_mixed<SRC_PAGED>(a, stream) : launch_mixed<SRC_CONTIG>(a, stream);
     }
     if (a.bm == 256) return launch_nw<8, 1, 4>(a, stream);

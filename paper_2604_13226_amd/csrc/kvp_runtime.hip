@@ -1286,13 +1286,25 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
             n_pkt_tiles[r] = (int)tiles.size() - tile_begin[r];
             for (int r0 = 0; r0 < n_q; r0 += 64) tiles.push_back(AttnTile{0, 0, r0, std::min(64, n_q - r0), 0, 1, 0});
             metas[r] = ReqMeta{(int32_t)pos, q_offsets[r], n_q, (int32_t)pos};
-            n_groups_total += (int64_t)g.n_kv_heads * (((int64_t)n_q * gq + MFMA_BM - 1) / MFMA_BM);
+        }
+        // row block, work-item target and launch shape as for the cache path (plan_prefill)
+        int bm = MFMA_BM;
+        if (s->force_bm == MFMA_BM || s->force_bm == 2 * MFMA_BM) bm = s->force_bm;
+        else
+            for (int r = 0; r < n_req; ++r)
+                if ((int64_t)metas[r].n_q * gq >= 2 * MFMA_BM) bm = 2 * MFMA_BM;
+        int64_t n_tiles_total = 0;  // 64-row tiles all the items together will read
+        for (int r = 0; r < n_req; ++r) {
+            const int64_t blocks = (int64_t)g.n_kv_heads * (((int64_t)metas[r].n_q * gq + bm - 1) / bm);
+            n_groups_total += blocks;
+            n_tiles_total += blocks * (n_pkt_tiles[r] + (metas[r].n_q + 63) / 64);
         }
         std::vector<AttnGroup> groups;
         std::vector<AttnItem> items;
         int n_slots = 0, part_stride = 1, max_group_rows = 0;
-        bool any_split = false;
-        int want = n_groups_total ? (int)std::min<int64_t>(MAX_SPLITS, (target_items(s) + n_groups_total - 1) / n_groups_total) : 1;
+        bool any_split = false, mixed = false;
+        const bool split_in_wg = streams_many_tiles(s, n_tiles_total, bm);
+        int want = n_groups_total ? (int)std::min<int64_t>(MAX_SPLITS, (target_items(s, n_tiles_total, bm) + n_groups_total - 1) / n_groups_total) : 1;
         if (want < 1) want = 1;
         for (int r = 0; r < n_req; ++r) {
             const ReqMeta &rq = metas[r];
@@ -1301,12 +1313,14 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
             const int per_item = std::max(4, (n_t + want - 1) / want);  // at least 256 rows per item
             const int M = rq.n_q * gq;
             for (int h = 0; h < g.n_kv_heads; ++h)
-                for (int m0 = 0; m0 < M; m0 += MFMA_BM) {
+                for (int m0 = 0; m0 < M; m0 += bm) {
                     AttnGroup gp;
                     gp.req = r;
                     gp.kv_head = h;
                     gp.m0 = m0;
-                    gp.n_rows = std::min(MFMA_BM, M - m0);
+                    gp.n_rows = std::min(bm, M - m0);
+                    const bool half_block = bm == 2 * MFMA_BM && gp.n_rows <= MFMA_BM && s->mixed_blocks;
+                    if (half_block) mixed = true;
                     const int t_last = (m0 + gp.n_rows - 1) / gq;
                     const int vis_tiles = n_pkt_tiles[r] + t_last / 64 + 1;  // causal: later query tiles are invisible
                     gp.n_splits = (vis_tiles + per_item - 1) / per_item;
@@ -1324,6 +1338,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
                         it.split = sp;
                         it.kv_begin = tile_begin[r] + sp * per_item;
                         it.kv_end = tile_begin[r] + std::min(vis_tiles, (sp + 1) * per_item);
+                        it.half_block = half_block ? 1 : 0;
                         it.req = r;
                         it.kv_head = h;
                         it.m0 = m0;
@@ -1340,7 +1355,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         }
         assign_part_slots(groups, items, any_split ? part_stride : 0, n_slots);
         xcd_order(items);
-        const uint64_t need = (uint64_t)n_slots * MFMA_BM * (g.head_dim + 2) * sizeof(float);
+        const uint64_t need = (uint64_t)n_slots * bm * (g.head_dim + 2) * sizeof(float);
         const uint64_t bytes = metas.size() * sizeof(ReqMeta) + groups.size() * sizeof(AttnGroup) +
                                items.size() * sizeof(AttnItem) + tiles.size() * sizeof(AttnTile) + 6 * 64;
         PlanRing::Slot *slot = nullptr;
@@ -1358,7 +1373,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         if (!tiles.empty()) memcpy(th, tiles.data(), tiles.size() * sizeof(AttnTile));
 
         s->dbg_attn.clear();
-        int64_t head[6] = {2, MFMA_BM, (int64_t)groups.size(), (int64_t)items.size(), n_slots, (int64_t)need};
+        int64_t head[6] = {2, bm, (int64_t)groups.size(), (int64_t)items.size(), n_slots, (int64_t)need};
         s->dbg_attn.insert(s->dbg_attn.end(), head, head + 6);
         for (const AttnGroup &x : groups) {
             int64_t row[6] = {x.req, x.kv_head, x.m0, x.n_rows, x.part0, x.n_splits};
@@ -1375,7 +1390,9 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         }
         pk.slot = slot;
         pk.kind = ATTN_MFMA;
-        pk.bm = MFMA_BM;
+        pk.bm = bm;
+        pk.mixed = mixed;
+        pk.split_in_wg = split_in_wg;
         pk.n_items = (int)items.size();
         pk.n_groups = (int)groups.size();
         pk.tot_q = tot_q;
@@ -1422,8 +1439,8 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     at.n_kv = g.n_kv_heads;
     at.d = g.head_dim;
     at.bm = pk.bm;
-    at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : 0;
-    at.mixed = 0;
+    at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : (pk.split_in_wg ? 1 : 0);
+    at.mixed = pk.mixed ? 1 : 0;
     at.part_stride = pk.part_stride;
     at.max_group_rows = pk.max_group_rows;
     at.g = g.n_q_heads / g.n_kv_heads;

@@ -300,7 +300,7 @@ def test_packets_plan_tiles_and_items():
     kvp.kvp_prefill_packets(s, reqs, 0, None, None, None, q_off, None, None, None)
     p = kvp.kvp_debug_last_plan(s, 1)
     kind, bm, ng, ni, slots, need = (int(x) for x in p[:6])
-    assert kind == 2 and bm == 128
+    assert kind == 2 and bm == 256                            # 70 query rows x 4 heads per kv head
     groups = p[6:6 + 6 * ng].reshape(ng, 6)
     items = p[6 + 6 * ng:6 + 6 * ng + 4 * ni].reshape(ni, 4)
     rest = p[6 + 6 * ng + 4 * ni:]
