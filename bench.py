@@ -169,10 +169,6 @@ def main():
         w.paged = args.layout == "paged"
     w.shared_header = bool(args.shared_header)
     n_req = len(w.requests)
-    if w.prune is not None and args.path == "packets":
-        print("bench.py: the in-place path reads whole packets only; run %s with --path cache" % w.name,
-              file=sys.stderr)
-        sys.exit(2)
     store = build_store(w, kvp, dev, packets=list(range(len(w.packet_lens)))
                         if len(w.packet_lens) <= 256 and args.store == "device" else None, arena=args.store,
                         progress=lambda i, n: print("store: packet %d of %d" % (i, n), file=sys.stderr, flush=True))

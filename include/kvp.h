@@ -121,8 +121,8 @@ int kvp_store_put(kvp_store_t *store, int64_t packet_id, int32_t n_tokens, const
  * kept rows of a layer follow each other without gaps, so layers have different row counts
  * (kvp_cache_t.ctx_rows).
  * k, v: layer after layer, layer l as [n_kv_heads][n_rows[l]][head_dim].
- * Other arguments, copies and errors as kvp_store_put.  kvp_prefill_packets does not take
- * compressed packets (KVP_E_INVAL).
+ * Other arguments, copies and errors as kvp_store_put.  kvp_prefill_packets reads, for the
+ * layer it is called for, the rows that layer kept.
  */
 int kvp_store_put_compressed(kvp_store_t *store, int64_t packet_id, int32_t span, const int32_t *n_rows,
                              const void *k, const void *v, int32_t src_on_device, void *hip_stream);

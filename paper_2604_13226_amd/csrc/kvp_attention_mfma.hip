@@ -260,9 +260,13 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
             const char *kt, *vt;
             uint32_t row_bytes;
             if (td.kind == 0) {
-                const int64_t slice = ((int64_t)a.layer * a.n_kv + it.kv_head) * td.stride + td.row0;
+                // stride < 0: a compressed packet, src_base is this layer's own part of the blob
+                // ([K: Hkv x rows][V: Hkv x rows], rows = -stride)
+                const bool own_layer = td.stride < 0;
+                const int stride = own_layer ? -td.stride : td.stride;
+                const int64_t slice = ((int64_t)(own_layer ? 0 : a.layer) * a.n_kv + it.kv_head) * stride + td.row0;
                 kt = (const char *)((const bf16_t *)a.arena + td.src_base + slice * D);
-                vt = kt + (int64_t)a.n_layers_total * a.n_kv * td.stride * ROW_BYTES;
+                vt = kt + (int64_t)(own_layer ? 1 : a.n_layers_total) * a.n_kv * stride * ROW_BYTES;
                 row_bytes = ROW_BYTES;
             } else {
                 kt = (const char *)((const bf16_t *)a.k_tail + tail_off + (int64_t)td.row0 * a.n_kv * D);

@@ -91,7 +91,8 @@ static_assert(sizeof(AttnItem) == 64, "AttnItem is 64 bytes");
 // (kind 0) or of the request's own query rows (kind 1).
 struct AttnTile {
     int64_t src_base;  // kind 0: element offset of the packet's K blob in the arena
-    int32_t stride;    // kind 0: rows between (layer, head) slices of the blob
+    int32_t stride;    // kind 0: rows between (layer, head) slices of the blob; negative: a compressed packet,
+                       // src_base is the called layer's own part and -stride the rows that layer kept
     int32_t row0;      // first row: inside the packet (kind 0) / among the query rows (kind 1)
     int32_t n_rows;    // 1..64
     int32_t pos;       // Delta_j of the packet; 0 for query rows

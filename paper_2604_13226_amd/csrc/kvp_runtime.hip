@@ -131,13 +131,12 @@ struct kvp_store {
     bool arena_host = false;    // the arena is pinned host memory mapped into the device (read over PCIe)
     PacketRec header;       // the header rows stored once (kvp_store_put_header); n_tokens 0: none
     PlanRing ring;          // plans of kvp_assemble
-    PlanRing ring_prefill;  // plans of kvp_prefill_packets
     // The prefill plan depends only on the request geometry (context lengths, query
     // offsets, block table), which is the same for every layer of a forward pass: the
     // uploaded plan is kept and reused while that geometry does not change.  With compressed
     // packets every layer has its own row counts, hence its own plan: kvp_query_prefill keeps
     // a set of plans (one more than the layers, at least PlanRing::SLOTS), each in a buffer
-    // of its own, replaced least recently used first.
+    // of its own, replaced least recently used first; kvp_prefill_packets likewise.
     struct PrefillCached {
         bool valid = false;
         std::vector<int32_t> sig;
@@ -153,8 +152,9 @@ struct kvp_store {
         int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0, part_stride = 1, max_group_rows = 0;
         bool any_split = false, mixed = false, split_in_wg = false;
         uint64_t need = 0;
-    } pk;                           // kvp_prefill_packets
+    };
     std::deque<PrefillCached> pf_set;  // kvp_query_prefill
+    std::deque<PrefillCached> pk_set;  // kvp_prefill_packets
     uint64_t pf_clock = 0;
     std::vector<int32_t> sig_scratch;
     std::string err;
@@ -493,7 +493,6 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
     s->cfg = *cfg;
     s->dry = dry;
     s->ring.dry = dry;
-    s->ring_prefill.dry = dry;
     s->esize = cfg->dtype == KVP_BF16 ? 2 : 4;
     const int half = cfg->head_dim / 2;
     s->inv_freq.resize(half);
@@ -556,13 +555,13 @@ int kvp_store_destroy(kvp_store_t *s)
     if (!s->dry) {
         (void)hipSetDevice(s->cfg.device);
         s->ring.release();
-        s->ring_prefill.release();
         for (auto &e : s->pf_set) e.own.release(false);
+        for (auto &e : s->pk_set) e.own.release(false);
         if (s->cs_dev) (void)hipFree(s->cs_dev);
     } else {
         s->ring.release();
-        s->ring_prefill.release();
         for (auto &e : s->pf_set) e.own.release(true);
+        for (auto &e : s->pk_set) e.own.release(true);
     }
     delete s;
     return KVP_OK;
@@ -849,6 +848,31 @@ void xcd_order(std::vector<AttnItem> &items)
     items.swap(out);
 }
 
+// The kept plan with this signature on this stream, or the entry to build it in: a fresh one
+// while the set may grow, else an invalid one, else the least recently used.
+kvp_store::PrefillCached &find_plan(kvp_store *s, std::deque<kvp_store::PrefillCached> &set, const std::vector<int32_t> &sig,
+                                    void *stream, uint64_t &sig_hash, bool &hit)
+{
+    sig_hash = 1469598103934665603ull;
+    for (int32_t x : sig) sig_hash = (sig_hash ^ (uint32_t)x) * 1099511628211ull;
+    kvp_store::PrefillCached *victim = nullptr;
+    for (auto &e : set) {
+        if (e.valid && e.sig_hash == sig_hash && e.stream == stream && e.sig == sig) {
+            hit = true;
+            e.last_use = ++s->pf_clock;
+            return e;
+        }
+        if (!victim || (!e.valid && victim->valid) || (e.valid == victim->valid && e.last_use < victim->last_use)) victim = &e;
+    }
+    hit = false;
+    if (!victim || (victim->valid && (int)set.size() < std::max(PlanRing::SLOTS, s->cfg.n_layers + 1))) {
+        set.emplace_back();
+        victim = &set.back();
+    }
+    victim->last_use = ++s->pf_clock;
+    return *victim;
+}
+
 struct PrefillPlan {
     int kind = ATTN_GENERIC, bm = 8, bn = 64;
     std::vector<ReqMeta> reqs;
@@ -1061,23 +1085,9 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
             const int32_t *row = cache->block_table + (int64_t)r * cache->max_blocks_per_req;
             sig.insert(sig.end(), row, row + n_blk[r]);
         }
-    uint64_t sig_hash = 1469598103934665603ull;
-    for (int32_t x : sig) sig_hash = (sig_hash ^ (uint32_t)x) * 1099511628211ull;
-    kvp_store::PrefillCached *found = nullptr, *victim = nullptr;
-    for (auto &e : s->pf_set) {
-        if (e.valid && e.sig_hash == sig_hash && e.stream == hip_stream && e.sig == sig) {
-            found = &e;
-            break;
-        }
-        if (!victim || (!e.valid && victim->valid) || (e.valid == victim->valid && e.last_use < victim->last_use)) victim = &e;
-    }
-    const bool hit = found != nullptr;
-    if (!hit && (!victim || (victim->valid && (int)s->pf_set.size() < std::max(PlanRing::SLOTS, g.n_layers + 1)))) {
-        s->pf_set.emplace_back();
-        victim = &s->pf_set.back();
-    }
-    kvp_store::PrefillCached &pf = hit ? *found : *victim;
-    pf.last_use = ++s->pf_clock;
+    uint64_t sig_hash = 0;
+    bool hit = false;
+    kvp_store::PrefillCached &pf = find_plan(s, s->pf_set, sig, hip_stream, sig_hash, hit);
     const uint64_t qrb = q_rot_bytes(s, tot_q);
     if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
 
@@ -1237,6 +1247,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     std::vector<int32_t> &sig = s->sig_scratch;
     sig.clear();
     sig.push_back(n_req);
+    bool any_compressed = false;
     for (int r = 0; r < n_req; ++r) {
         const kvp_request_t &rq = reqs[r];
         if (rq.k < 0 || (rq.k > 0 && !rq.packet_ids)) return fail(s, KVP_E_INVAL, "request %d: bad packet list", r);
@@ -1247,16 +1258,21 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         for (int j = 0; j < rq.k; ++j) {
             sig.push_back((int32_t)(rq.packet_ids[j] & 0xFFFFFFFF));
             sig.push_back((int32_t)(rq.packet_ids[j] >> 32));
+            auto itp = s->dir.find(rq.packet_ids[j]);
+            if (itp == s->dir.end()) return fail(s, KVP_E_NOTFOUND, "request %d: packet %lld not in the store", r, (long long)rq.packet_ids[j]);
+            any_compressed |= itp->second.compressed();
         }
     }
+    sig.push_back(any_compressed ? layer : -1);  // compressed packets (Sec. 5.4): every layer has its own rows, hence its own tiles
     const int tot_q = q_offsets[n_req];
     if (tot_q > 0 && !s->dry) {
         if (!q || !k_new || !v_new || !out || !k_tail) return fail(s, KVP_E_INVAL, "q, k_new, v_new, k_tail or out is null");
         if (((uintptr_t)q | (uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)out | (uintptr_t)k_tail) & 15)
             return fail(s, KVP_E_INVAL, "q, k_new, v_new, k_tail, out must be 16-byte aligned");
     }
-    kvp_store::PrefillCached &pk = s->pk;
-    const bool hit = pk.valid && pk.stream == hip_stream && pk.sig == sig;
+    uint64_t sig_hash = 0;
+    bool hit = false;
+    kvp_store::PrefillCached &pk = find_plan(s, s->pk_set, sig, hip_stream, sig_hash, hit);
     if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
 
     if (!hit) {
@@ -1274,7 +1290,15 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
                 auto itp = s->dir.find(rq.packet_ids[j]);
                 if (itp == s->dir.end()) return fail(s, KVP_E_NOTFOUND, "request %d: packet %lld not in the store", r, (long long)rq.packet_ids[j]);
                 const PacketRec &p = itp->second;
-                if (p.compressed()) return fail(s, KVP_E_INVAL, "request %d: packet %lld is compressed; kvp_prefill_packets reads uncompressed packets only", r, (long long)rq.packet_ids[j]);
+                if (p.compressed()) {
+                    // this layer's kept rows, from its own part of the blob (negative stride: V follows
+                    // this layer's K); the packet still occupies its span of positions
+                    const int rows = p.rows[layer];
+                    for (int r0 = 0; r0 < rows; r0 += 64)
+                        tiles.push_back(AttnTile{p.layer_off[layer], -rows, r0, std::min(64, rows - r0), (int32_t)pos, 0, 0});
+                    pos += p.n_tokens;
+                    continue;
+                }
                 // (a packet stored without its header rows: those come from the shared copy, as a tile of their own)
                 for (int r0 = 0; r0 < p.head_rows; r0 += 64)
                     tiles.push_back(AttnTile{s->header.elem_off, s->header.stride, r0, std::min(64, p.head_rows - r0), (int32_t)pos, 0, 0});
@@ -1358,10 +1382,10 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         const uint64_t need = (uint64_t)n_slots * bm * (g.head_dim + 2) * sizeof(float);
         const uint64_t bytes = metas.size() * sizeof(ReqMeta) + groups.size() * sizeof(AttnGroup) +
                                items.size() * sizeof(AttnItem) + tiles.size() * sizeof(AttnTile) + 6 * 64;
-        PlanRing::Slot *slot = nullptr;
-        int hrc = s->ring_prefill.acquire(bytes, &slot);
+        pk.valid = false;  // the entry's buffer is rewritten below
+        PlanSlot *slot = &pk.own;
+        int hrc = slot->ensure(bytes, s->dry);
         if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
-        pk.valid = false;
         PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
         ReqMeta *rh = w.put<ReqMeta>(metas.size(), &pk.reqs_dev);
         if (!metas.empty()) memcpy(rh, metas.data(), metas.size() * sizeof(ReqMeta));
@@ -1401,6 +1425,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         pk.max_group_rows = max_group_rows;
         pk.need = need;
         pk.sig = sig;
+        pk.sig_hash = sig_hash;
         pk.stream = hip_stream;
         if (tot_q > 0 && workspace_bytes < need)
             return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)need);

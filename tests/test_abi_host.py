@@ -464,10 +464,18 @@ def test_compressed_packets_errors():
     with pytest.raises(kvp.KvpError) as e:
         kvp.kvp_assemble(s, [([0], 0)], cache)
     assert e.value.code == kvp.KVP_E_CAPACITY
-    # the in-place attention path reads uncompressed packets only
-    with pytest.raises(kvp.KvpError) as e:
-        kvp.kvp_prefill_packets(s, [([0], 0)], 0, None, None, None, np.array([0, 2], np.int32), None, None, None)
-    assert e.value.code == kvp.KVP_E_INVAL
+    # the in-place attention path tiles the rows the called layer kept (packet 0: 10 and 3 rows),
+    # at the positions of the spans
+    kvp.kvp_store_put(s, 5, None, None, n_tokens=70)
+    for layer, rows in ((0, 10), (1, 3)):
+        kvp.kvp_prefill_packets(s, [([0, 5, 0], 0)], layer, None, None, None, np.array([0, 2], np.int32), None, None, None)
+        p = kvp.kvp_debug_last_plan(s, 1)
+        ng, ni = int(p[2]), int(p[3])
+        rest = p[6 + 6 * ng + 4 * ni:]
+        tiles = rest[1:].reshape(int(rest[0]), 6)
+        assert [tuple(int(v) for v in x[1:]) for x in tiles] == [
+            (-rows, 0, rows, 0, 0), (70, 0, 64, 10, 0), (70, 64, 6, 10, 0), (-rows, 0, rows, 80, 0), (0, 0, 2, 0, 1)]
+        assert tiles[0][0] == tiles[3][0] and (layer == 0 or tiles[0][0] > 0)
     # rows of a layer cannot exceed the position
     cache = kvp.Cache.dry(1, t_cap=100).with_ctx_rows(2)
     cache.ctx_len[0] = 5

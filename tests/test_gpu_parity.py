@@ -847,6 +847,46 @@ def test_random_geometries_pruned(gpu_device, seed):
     _check_pruned_workload(w, ("pruned", seed))
 
 
+@pytest.mark.parametrize("seed", range(600, 612))
+def test_random_geometries_pruned_in_place(gpu_device, seed):
+    """Pruned packets read in place (kvp_prefill_packets): every layer tiles its own kept rows;
+    the oracle composes that layer from the kept rows and attends with the query at the position
+    after the spans."""
+    import oracle
+    rng = np.random.default_rng(seed)
+    n_req, n_packets = int(rng.integers(1, 4)), int(rng.integers(2, 6))
+    g, n_kv = int(rng.choice([1, 4])), int(rng.choice([1, 2]))
+    w = W.random_small(seed, dtype="bf16", d=128, n_q_heads=n_kv * g, n_kv_heads=n_kv, n_layers=int(rng.integers(1, 4)),
+                       n_packets=n_packets, k=1, n_q=1, max_len=int(rng.choice([9, 70, 300])), n_req=n_req)
+    for rq in w.requests:
+        rq.packet_ids = [int(x) for x in rng.integers(0, n_packets, size=int(rng.integers(0, 5)))]
+        rq.n_q = int(rng.integers(0, 100))
+    if all(rq.n_q == 0 for rq in w.requests):
+        w.requests[0].n_q = 3
+    lo = float(rng.uniform(0.0, 0.6))
+    w.prune = (lo, min(1.0, lo + float(rng.uniform(0.0, 0.5))))
+    layers = list(range(w.n_layers))
+    outs, tails = _run_packets(w, layers)
+    f = oracle.inv_freq(w.rope_base, w.head_dim)
+    for r, rq in enumerate(w.requests):
+        if rq.n_q == 0:
+            continue
+        kv = [tuple(W.to_numpy(x) for x in w.packet_kv(p)) for p in rq.packet_ids]
+        spans = [int(w.packet_lens[p]) for p in rq.packet_ids]
+        for layer in layers:
+            keep = [w.kept_rows(p, layer) for p in rq.packet_ids]
+            ks = [np.ascontiguousarray(k[layer][:, s_]) for (k, _), s_ in zip(kv, keep)]
+            vs = [np.ascontiguousarray(v[layer][:, s_]) for (_, v), s_ in zip(kv, keep)]
+            if ks:
+                Ko, Vo, rows, pos_end = oracle.assemble_layer_spans(w.dtype, ks, vs, spans, f, 0, t_cap=w.layer_rows(r, layer) + rq.n_q)
+            else:
+                Ko = np.zeros((w.n_kv_heads, rq.n_q, w.head_dim), np.uint16)
+                Vo, rows, pos_end = Ko.copy(), 0, 0
+            ref = oracle.query_prefill_at(w.dtype, *(W.to_numpy(x) for x in w.query(r, layer)), f, rows, pos_end, Ko, Vo)
+            check_output(outs[r][layer], ref, w.dtype, ("pruned in place", seed, r, layer))
+            assert np.array_equal(tails[r][layer], Ko[:, rows:rows + rq.n_q].transpose(1, 0, 2)), (seed, "k_tail", r, layer)
+
+
 @pytest.mark.parametrize("seed", range(400, 416))
 def test_random_geometries_in_place(gpu_device, seed):
     """Seeded random bf16 batches through kvp_prefill_packets (attention in place, no cache)."""
