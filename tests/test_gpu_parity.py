@@ -604,6 +604,16 @@ def test_paged_context_longer_than_one_items_block_ids(gpu_device):
     compare(w, got, oracle_workload(w))
 
 
+def test_context_of_128k_rows(gpu_device):
+    """The longest context the paper's models take (131 072 positions): 64 packets of 2048 rows,
+    32 query tokens, one layer.  Rotation angles at the far end, 2048 tiles, 32-way split."""
+    w = W.llama_8k(n_layers=1, n_packets=16)
+    w.packet_lens[:] = 2048
+    w.requests[0].packet_ids = [int(x) for x in np.random.default_rng(5).integers(0, 8, size=64)]
+    assert w.ctx_len(0) == 131072
+    compare(w, run_workload(w), oracle_workload(w))
+
+
 def test_full_size_serving_mix_sampled(gpu_device):
     """Config 5 (64 requests, paged cache, block 16, Zipf retrieval) on one layer: the oracle
     checks four of the 64 requests, among them the longest and the shortest context."""
