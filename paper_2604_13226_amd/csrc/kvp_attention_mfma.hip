@@ -202,8 +202,7 @@ enum { SRC_CONTIG = 0, SRC_PAGED = 1, SRC_PACKETS = 2 };
 template <int STAGES, int SRC, int NW, int KS>
 __device__ __forceinline__ void attention_body(const AttnArgs &a)
 {
-    constexpr int RW = NW / KS;    // waves per group
-    constexpr int BM = 32 * RW;
+    constexpr int RW = NW / KS;    // waves per group (a group owns 32 RW rows)
     constexpr int NT = 64 * NW;    // threads
     constexpr int NI = 16 / NW;    // K (and V) load instructions per wave per tile
     constexpr int PR = STAGES / KS - 1;  // rounds (of KS tiles) loaded ahead

@@ -222,11 +222,6 @@ void build_cos_sin(const std::vector<float> &inv_freq, int max_pos, std::vector<
     for (auto &t : th) t.join();
 }
 
-// Rows between consecutive (layer, head) slices of a packet blob.  No padding: skewing
-// equal-length packets by a few rows per slice / per blob was measured and changed nothing.
-int slice_pad_rows(int) { return 0; }
-int blob_pad_rows(int) { return 0; }
-
 struct CacheCheck {
     int shift = 0;
     int64_t cap_rows = 0;  // rows a request can hold
@@ -467,8 +462,7 @@ uint64_t kvp_packet_bytes(const kvp_config_t *cfg, int32_t n_tokens)
 {
     if (!cfg || n_tokens < 0) return 0;
     uint64_t es = cfg->dtype == KVP_BF16 ? 2 : 4;
-    const uint64_t stride = (uint64_t)n_tokens + slice_pad_rows(n_tokens);
-    return align_up((2ull * cfg->n_layers * cfg->n_kv_heads * stride + blob_pad_rows(n_tokens)) * cfg->head_dim * es);
+    return align_up(2ull * cfg->n_layers * cfg->n_kv_heads * (uint64_t)n_tokens * cfg->head_dim * es);
 }
 
 int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
@@ -576,10 +570,12 @@ int put_blob(kvp_store *s, int rows, const void *k, const void *v, int src_on_de
 {
     const kvp_config_t &g = s->cfg;
     const uint64_t row_bytes = (uint64_t)g.head_dim * s->esize;
-    const int stride = rows + slice_pad_rows(rows);
+    // (layer, head) slices follow each other without padding: skewing equal-length packets by a
+    // few rows per slice or per blob was measured and changed nothing
+    const int stride = rows;
     const uint64_t n_slices = (uint64_t)g.n_layers * g.n_kv_heads;
     const uint64_t half_bytes = n_slices * stride * row_bytes;
-    const uint64_t need = align_up(2 * half_bytes + blob_pad_rows(rows) * row_bytes);
+    const uint64_t need = align_up(2 * half_bytes);
     if (s->used_bytes + need > g.arena_bytes)
         return fail(s, KVP_E_NOSPACE, "arena full: %llu used + %llu needed > %llu", (unsigned long long)s->used_bytes,
                     (unsigned long long)need, (unsigned long long)g.arena_bytes);
