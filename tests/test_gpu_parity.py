@@ -103,6 +103,39 @@ def test_random_geometries(gpu_device, seed):
     compare(w, run_workload(w), oracle_workload(w))
 
 
+@pytest.mark.parametrize("seed", range(700, 748))
+def test_random_geometries_with_random_launch_shapes(gpu_device, seed):
+    """The same random batches with the planner's choices overridden at random: how finely
+    split-KV cuts, the row block, the two-group workgroup shape, half blocks on or off, the
+    gather's tile rows and the generic kernel.  Results must not depend on any of them."""
+    rng = np.random.default_rng(seed + 10000)
+    w = _random_geometry(seed)
+    env = {"KVP_ATTN_TARGET_ITEMS": str(int(rng.choice([1, 7, 64, 300, 4000]))),
+           "KVP_ASM_TILE_ROWS": str(int(rng.choice([16, 32, 64])))}
+    if rng.random() < 0.5:
+        env["KVP_ATTN_BM"] = str(int(rng.choice([128, 256])))
+    if rng.random() < 0.5:
+        env["KVP_ATTN_SPLIT_IN_WG"] = str(int(rng.integers(0, 2)))
+    if rng.random() < 0.3:
+        env["KVP_ATTN_MIXED"] = "0"
+    if rng.random() < 0.15:
+        env["KVP_FORCE_GENERIC_ATTENTION"] = "1"
+    if rng.random() < 0.2:
+        env["KVP_ASM_NONTEMPORAL"] = "1"
+    if rng.random() < 0.2:
+        env["KVP_PLAN_COPY_ENGINE"] = "1"
+    os.environ.update(env)
+    try:
+        got = run_workload(w)
+    finally:
+        for k in env:
+            os.environ.pop(k, None)
+    try:
+        compare(w, got, oracle_workload(w))
+    except AssertionError as e:
+        raise AssertionError("with %s: %s" % (env, e))
+
+
 @pytest.mark.parametrize("mk", [
     lambda: W.llama_k5(n_layers=2, n_packets=16),
     lambda: W.qwen_k20(n_layers=2, n_packets=40),
