@@ -132,6 +132,8 @@ def main():
                          "memory, read over PCIe at every assembly (the paper's tier; reported apart)")
     ap.add_argument("--pipeline", action="store_true",
                     help="assemble layer by layer on a second stream, under the previous layer's prefill")
+    ap.add_argument("--pipeline-group", type=int, default=1,
+                    help="with --pipeline: layers per assembly launch")
     ap.add_argument("--layout", default="", choices=["", "contiguous", "paged"],
                     help="cache layout (default: the workload's own); paged uses 16-row blocks in a seeded random order")
     ap.add_argument("--block-order", default="random", choices=["random", "sequential"],
@@ -208,11 +210,15 @@ def main():
         if ev:
             ev[0].record()
         if pipelined:
+            G = max(1, args.pipeline_group)
+            for l0 in range(0, w.n_layers, G):       # every group's assembly is queued on the side stream at once
+                l1 = min(w.n_layers, l0 + G)
+                side.wait_event(free[l1 - 1])
+                kvp.kvp_assemble(store, reqs, cache, l0, l1, stream=side)
+                ready[l0].record(side)
             for layer in range(w.n_layers):
-                side.wait_event(free[layer])
-                kvp.kvp_assemble(store, reqs, cache, layer, layer + 1, stream=side)
-                ready[layer].record(side)
-                main.wait_event(ready[layer])
+                if layer % G == 0:
+                    main.wait_event(ready[layer])
                 q, kn, vn = qkv[layer]
                 kvp.kvp_query_prefill(store, cache, layer, q, kn, vn, q_off, ws, out)
                 free[layer].record(main)
