@@ -308,6 +308,13 @@ def main():
                     "flops_per_layer": pre_flops, "achieved_GBs": pre_gbs,
                     "hbm_frac": pre_gbs / HBM_PEAK_GBS, "achieved_TFLOPs": pre_tflops,
                     "mfma_frac": pre_tflops / BF16_PEAK_TFLOPS},
+        # the per-layer launches (attention + combine) in the same terms as `roofline`: HBM-bound
+        # while the packed query rows per KV head stay below the chip's flop-per-byte balance
+        "roofline_prefill": ({"bound": "mfma", "kernel": "attention + combine, per layer", "achieved": pre_tflops,
+                              "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": pre_tflops / BF16_PEAK_TFLOPS, "traffic": None}
+                             if w.dtype == "bf16" and pre_flops / max(pre_bytes, 1.0) > BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS else
+                             {"bound": "hbm", "kernel": "attention + combine, per layer", "achieved": pre_gbs,
+                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pre_gbs / HBM_PEAK_GBS, "traffic": None}),
         "assemble_us_per_layer": asm_ms * 1e3 / w.n_layers,
         "step_us_per_layer": {"p50": float(np.percentile(step_ms, 50)) * 1e3 / w.n_layers,
                               "p99": float(np.percentile(step_ms, 99)) * 1e3 / w.n_layers,
