@@ -160,7 +160,14 @@ struct kvp_store {
     std::string err;
     std::vector<AsmSeg> dbg_segs;  // the last gather plan (kvp_debug_last_plan)
     bool dbg_layered = false;
-    std::vector<int64_t> dbg_attn;
+    // the last prefill plan, kept as built (kvp_debug_last_plan expands it on request)
+    struct DebugPlan {
+        int64_t head[6] = {0, 0, 0, 0, 0, 0};  // kind, bm, groups, items, slots, workspace bytes needed
+        std::vector<AttnGroup> groups;
+        std::vector<AttnItem> items;
+        std::vector<AttnTile> tiles;
+        bool has_tiles = false;
+    } dbg_plan;
     bool dry = false;
     int n_cu = 256;
     int force_generic = 0;
@@ -800,30 +807,36 @@ void assign_part_slots(std::vector<AttnGroup> &groups, std::vector<AttnItem> &it
 void xcd_order(std::vector<AttnItem> &items)
 {
     constexpr int XCDS = 8;
-    struct Cohort { int64_t key; std::vector<int> members; int64_t work = 0; };
-    std::vector<Cohort> cohorts;
-    std::unordered_map<int64_t, int> index;
-    bool shared = false;
-    for (int i = 0; i < (int)items.size(); ++i) {
+    const int n = (int)items.size();
+    // items by cohort key, original order inside a cohort
+    struct Ref { int64_t key; int idx; };
+    std::vector<Ref> refs(n);
+    for (int i = 0; i < n; ++i) {
         const AttnItem &it = items[i];
-        const int64_t key = ((int64_t)it.req << 40) ^ ((int64_t)it.kv_head << 28) ^ (int64_t)it.split;
-        auto f = index.find(key);
-        if (f == index.end()) {
-            index[key] = (int)cohorts.size();
-            cohorts.push_back(Cohort{key, {i}});
-            f = index.find(key);
-        } else {
-            cohorts[f->second].members.push_back(i);
-            shared = true;
-        }
-        Cohort &c = cohorts[f->second];
-        c.work = std::max(c.work, (int64_t)(it.kv_end - it.kv_begin) * it.n_rows);
+        refs[i] = Ref{((int64_t)it.req << 40) ^ ((int64_t)it.kv_head << 28) ^ (int64_t)it.split, i};
     }
-    std::stable_sort(cohorts.begin(), cohorts.end(), [](const Cohort &x, const Cohort &y) { return x.work > y.work; });
+    std::sort(refs.begin(), refs.end(), [](const Ref &x, const Ref &y) { return x.key != y.key ? x.key < y.key : x.idx < y.idx; });
+    struct Cohort { int first, count, order; int64_t work; };  // refs[first .. first + count); order = its first item's index
+    std::vector<Cohort> cohorts;
+    bool shared = false;
+    for (int i = 0; i < n;) {
+        int j = i;
+        int64_t work = 0;
+        for (; j < n && refs[j].key == refs[i].key; ++j) {
+            const AttnItem &it = items[refs[j].idx];
+            work = std::max(work, (int64_t)(it.kv_end - it.kv_begin) * it.n_rows);
+        }
+        cohorts.push_back(Cohort{i, j - i, refs[i].idx, work});
+        shared |= j - i > 1;
+        i = j;
+    }
+    // longest first; equal work keeps the planner's order
+    std::sort(cohorts.begin(), cohorts.end(),
+              [](const Cohort &x, const Cohort &y) { return x.work != y.work ? x.work > y.work : x.order < y.order; });
     std::vector<AttnItem> out;
     out.reserve(items.size() + 64);
     if (!shared) {
-        for (const Cohort &c : cohorts) out.push_back(items[c.members[0]]);
+        for (const Cohort &c : cohorts) out.push_back(items[refs[c.first].idx]);
         items.swap(out);
         return;
     }
@@ -831,12 +844,12 @@ void xcd_order(std::vector<AttnItem> &items)
     null_item.group = -1;
     for (size_t c0 = 0; c0 < cohorts.size(); c0 += XCDS) {
         const size_t c1 = std::min(cohorts.size(), c0 + XCDS);
-        size_t depth = 0;
-        for (size_t c = c0; c < c1; ++c) depth = std::max(depth, cohorts[c].members.size());
+        int depth = 0;
+        for (size_t c = c0; c < c1; ++c) depth = std::max(depth, cohorts[c].count);
         const bool last_block = c1 == cohorts.size();
-        for (size_t j = 0; j < depth; ++j)
+        for (int j = 0; j < depth; ++j)
             for (size_t c = c0; c < c0 + XCDS; ++c) {
-                if (c < c1 && j < cohorts[c].members.size()) out.push_back(items[cohorts[c].members[j]]);
+                if (c < c1 && j < cohorts[c].count) out.push_back(items[refs[cohorts[c].first + j].idx]);
                 else if (!(last_block && c >= c1 && j + 1 == depth)) out.push_back(null_item);
             }
     }
@@ -1112,22 +1125,20 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
             rc = compact_block_table(s, cache, n_req, first_blk, n_blk, bt_stride, bh);
             if (rc) return rc;
         }
-        s->dbg_attn.clear();
-        int64_t head[6] = {p.kind, p.bm, (int64_t)p.groups.size(), (int64_t)p.items.size(), p.n_slots, (int64_t)need};
-        s->dbg_attn.insert(s->dbg_attn.end(), head, head + 6);
-        for (const AttnGroup &x : p.groups) {
-            int64_t row[6] = {x.req, x.kv_head, x.m0, x.n_rows, x.part0, x.n_splits};
-            s->dbg_attn.insert(s->dbg_attn.end(), row, row + 6);
-        }
-        for (const AttnItem &x : p.items) {
-            int64_t row[4] = {x.group, x.split, x.kv_begin, x.kv_end};
-            s->dbg_attn.insert(s->dbg_attn.end(), row, row + 4);
+        {
+            kvp_store::DebugPlan &dp = s->dbg_plan;
+            const int64_t head[6] = {p.kind, p.bm, (int64_t)p.groups.size(), (int64_t)p.items.size(), p.n_slots, (int64_t)need};
+            memcpy(dp.head, head, sizeof head);
+            dp.groups.swap(p.groups);  // (already copied into the plan buffer above)
+            dp.items.swap(p.items);
+            dp.tiles.clear();
+            dp.has_tiles = false;
         }
         pf.slot = slot;
         pf.kind = p.kind;
         pf.bm = p.bm;
-        pf.n_items = (int)p.items.size();
-        pf.n_groups = (int)p.groups.size();
+        pf.n_items = (int)s->dbg_plan.head[3];  // (the vectors themselves have moved into dbg_plan)
+        pf.n_groups = (int)s->dbg_plan.head[2];
         pf.bt_stride = bt_stride;
         pf.tot_q = tot_q;
         pf.any_split = p.any_split;
@@ -1392,29 +1403,23 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         AttnTile *th = w.put<AttnTile>(tiles.size(), &pk.tiles_dev);
         if (!tiles.empty()) memcpy(th, tiles.data(), tiles.size() * sizeof(AttnTile));
 
-        s->dbg_attn.clear();
-        int64_t head[6] = {2, bm, (int64_t)groups.size(), (int64_t)items.size(), n_slots, (int64_t)need};
-        s->dbg_attn.insert(s->dbg_attn.end(), head, head + 6);
-        for (const AttnGroup &x : groups) {
-            int64_t row[6] = {x.req, x.kv_head, x.m0, x.n_rows, x.part0, x.n_splits};
-            s->dbg_attn.insert(s->dbg_attn.end(), row, row + 6);
-        }
-        for (const AttnItem &x : items) {
-            int64_t row[4] = {x.group, x.split, x.kv_begin, x.kv_end};
-            s->dbg_attn.insert(s->dbg_attn.end(), row, row + 4);
-        }
-        s->dbg_attn.push_back((int64_t)tiles.size());
-        for (const AttnTile &x : tiles) {
-            int64_t row[6] = {x.src_base, x.stride, x.row0, x.n_rows, x.pos, x.kind};
-            s->dbg_attn.insert(s->dbg_attn.end(), row, row + 6);
+        const int n_items_planned = (int)items.size(), n_groups_planned = (int)groups.size();
+        {
+            kvp_store::DebugPlan &dp = s->dbg_plan;
+            const int64_t head[6] = {2, bm, (int64_t)groups.size(), (int64_t)items.size(), n_slots, (int64_t)need};
+            memcpy(dp.head, head, sizeof head);
+            dp.groups.swap(groups);  // (already copied into the plan buffer above)
+            dp.items.swap(items);
+            dp.tiles.swap(tiles);
+            dp.has_tiles = true;
         }
         pk.slot = slot;
         pk.kind = ATTN_MFMA;
         pk.bm = bm;
         pk.mixed = mixed;
         pk.split_in_wg = split_in_wg;
-        pk.n_items = (int)items.size();
-        pk.n_groups = (int)groups.size();
+        pk.n_items = n_items_planned;
+        pk.n_groups = n_groups_planned;
         pk.tot_q = tot_q;
         pk.any_split = any_split;
         pk.part_stride = part_stride;
@@ -1493,7 +1498,28 @@ int64_t kvp_debug_last_plan(const kvp_store_t *s, int32_t which, int64_t *out, i
                 ++tiles[0];
             }
     }
-    const std::vector<int64_t> &v = which == 0 ? tiles : s->dbg_attn;
+    if (which != 0) {
+        // the last prefill plan: head, then groups (6 numbers each), items (4 each) and, for the
+        // in-place path, the tile count and the tiles (6 each)
+        const kvp_store::DebugPlan &dp = s->dbg_plan;
+        tiles.assign(dp.head, dp.head + 6);
+        for (const AttnGroup &x : dp.groups) {
+            int64_t row[6] = {x.req, x.kv_head, x.m0, x.n_rows, x.part0, x.n_splits};
+            tiles.insert(tiles.end(), row, row + 6);
+        }
+        for (const AttnItem &x : dp.items) {
+            int64_t row[4] = {x.group, x.split, x.kv_begin, x.kv_end};
+            tiles.insert(tiles.end(), row, row + 4);
+        }
+        if (dp.has_tiles) {
+            tiles.push_back((int64_t)dp.tiles.size());
+            for (const AttnTile &x : dp.tiles) {
+                int64_t row[6] = {x.src_base, x.stride, x.row0, x.n_rows, x.pos, x.kind};
+                tiles.insert(tiles.end(), row, row + 6);
+            }
+        }
+    }
+    const std::vector<int64_t> &v = tiles;
     for (int64_t i = 0; i < (int64_t)v.size() && i < cap && out; ++i) out[i] = v[i];
     return (int64_t)v.size();
 }
