@@ -121,6 +121,7 @@ struct AttnArgs {
     int32_t n_items, n_groups, layer, n_q_heads, n_kv, d, bm, g;
     int32_t split_in_wg;  // MFMA kernel, 128-row blocks: two wave groups take alternate tiles
     int32_t mixed;        // MFMA kernel, 256-row blocks: some items are half blocks (AttnItem::half_block)
+    int32_t nt_loads;     // MFMA kernel: no two work items read the same K/V rows, tiles are loaded with the streaming hint
     int32_t part_stride;  // partial slots per group
     int32_t max_group_rows;  // largest n_rows among the groups that are split (the combine grid covers no more)
     float scale_log2e;  // log2(e) / sqrt(d)

@@ -150,7 +150,7 @@ struct kvp_store {
         const AttnItem *items_dev = nullptr;
         const AttnTile *tiles_dev = nullptr;
         int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0, part_stride = 1, max_group_rows = 0;
-        bool any_split = false, mixed = false, split_in_wg = false;
+        bool any_split = false, mixed = false, split_in_wg = false, shared_rows = false;
         uint64_t need = 0;
     };
     std::deque<PrefillCached> pf_set;  // kvp_query_prefill
@@ -173,6 +173,7 @@ struct kvp_store {
     int force_generic = 0;
     int target_items = 0;  // 0: three quarters of the CU count (measured optimum at 8K context)
     int asm_tile_rows = 32, asm_nontemporal = 0;
+    int nt_loads = -1;  // test knob (KVP_ATTN_NT_LOADS=0/1): streaming hint on the attention kernel's tile loads
     int mixed_blocks = 1;  // test knob (KVP_ATTN_MIXED=0): no half blocks in launches of 256-row blocks
     int plan_copy_engine = 0;  // test knob: plans go up with hipMemcpyAsync instead of the upload kernel
     int force_bm = 0;  // test knob: row-block size of the MFMA attention kernel
@@ -509,6 +510,7 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
     if (nt) s->asm_nontemporal = nt[0] == '1';
     if (const char *pc = getenv("KVP_PLAN_COPY_ENGINE")) s->plan_copy_engine = pc[0] == '1';
     if (const char *mb = getenv("KVP_ATTN_MIXED")) s->mixed_blocks = mb[0] != '0';
+    if (const char *nl = getenv("KVP_ATTN_NT_LOADS")) s->nt_loads = nl[0] != '0';
     if (const char *fb = getenv("KVP_ATTN_BM")) s->force_bm = atoi(fb);
     if (const char *fd = getenv("KVP_ATTN_SPLIT_IN_WG")) s->force_split_in_wg = atoi(fd) != 0;
     const char *ti = getenv("KVP_ATTN_TARGET_ITEMS");  // test knob: how finely split-KV cuts
@@ -804,7 +806,7 @@ void assign_part_slots(std::vector<AttnGroup> &groups, std::vector<AttnItem> &it
 // Cohorts go out longest first (kv rows x query rows of their largest member): workgroups
 // start in index order as compute units fall free, so the long items of a ragged batch start
 // early and the short ones fill the end of the launch.
-void xcd_order(std::vector<AttnItem> &items)
+bool xcd_order(std::vector<AttnItem> &items)  // returns whether any two items share their K/V rows
 {
     constexpr int XCDS = 8;
     const int n = (int)items.size();
@@ -838,7 +840,7 @@ void xcd_order(std::vector<AttnItem> &items)
     if (!shared) {
         for (const Cohort &c : cohorts) out.push_back(items[refs[c.first].idx]);
         items.swap(out);
-        return;
+        return false;
     }
     AttnItem null_item{};
     null_item.group = -1;
@@ -855,6 +857,7 @@ void xcd_order(std::vector<AttnItem> &items)
     }
     while (!out.empty() && out.back().group < 0) out.pop_back();
     items.swap(out);
+    return true;
 }
 
 // The kept plan with this signature on this stream, or the entry to build it in: a fresh one
@@ -892,6 +895,8 @@ struct PrefillPlan {
     bool any_split = false;
     bool mixed = false;  // MFMA kernel, 256-row blocks: some groups are half blocks
     bool split_in_wg = false;  // MFMA kernel, 128-row blocks: 8 waves in two groups on alternate tiles
+    bool shared_rows = false;  // some work items read the same K/V rows (several row blocks per request and head),
+                               // or the launch is short: either way no streaming hint on the tile loads
 };
 
 constexpr int MFMA_BM = 128;
@@ -1014,7 +1019,7 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
             }
     }
     assign_part_slots(p.groups, p.items, p.any_split ? p.part_stride : 0, p.n_slots);
-    xcd_order(p.items);
+    p.shared_rows = xcd_order(p.items) || tiles < 16 * (int64_t)s->n_cu;  // (short launches: the hint measured slower)
 }
 
 uint64_t q_rot_bytes(const kvp_store *s, int64_t tot_q)
@@ -1144,6 +1149,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         pf.any_split = p.any_split;
         pf.mixed = p.mixed;
         pf.split_in_wg = p.split_in_wg;
+        pf.shared_rows = p.shared_rows;
         pf.part_stride = p.part_stride;
         pf.max_group_rows = p.max_group_rows;
         pf.need = need;
@@ -1220,6 +1226,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     at.bm = pf.bm;
     at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : (pf.split_in_wg ? 1 : 0);
     at.mixed = pf.mixed ? 1 : 0;
+    at.nt_loads = s->nt_loads >= 0 ? s->nt_loads : (pf.shared_rows ? 0 : 1);
     at.part_stride = pf.part_stride;
     at.max_group_rows = pf.max_group_rows;
     at.g = g.n_q_heads / g.n_kv_heads;
@@ -1385,7 +1392,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
                 }
         }
         assign_part_slots(groups, items, any_split ? part_stride : 0, n_slots);
-        xcd_order(items);
+        const bool shared_rows = xcd_order(items) || n_tiles_total < 16 * (int64_t)s->n_cu;  // (short launches: the hint measured slower)
         const uint64_t need = (uint64_t)n_slots * bm * (g.head_dim + 2) * sizeof(float);
         const uint64_t bytes = metas.size() * sizeof(ReqMeta) + groups.size() * sizeof(AttnGroup) +
                                items.size() * sizeof(AttnItem) + tiles.size() * sizeof(AttnTile) + 6 * 64;
@@ -1418,6 +1425,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         pk.bm = bm;
         pk.mixed = mixed;
         pk.split_in_wg = split_in_wg;
+        pk.shared_rows = shared_rows;
         pk.n_items = n_items_planned;
         pk.n_groups = n_groups_planned;
         pk.tot_q = tot_q;
@@ -1467,6 +1475,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     at.bm = pk.bm;
     at.split_in_wg = s->force_split_in_wg >= 0 ? s->force_split_in_wg : (pk.split_in_wg ? 1 : 0);
     at.mixed = pk.mixed ? 1 : 0;
+    at.nt_loads = s->nt_loads >= 0 ? s->nt_loads : (pk.shared_rows ? 0 : 1);
     at.part_stride = pk.part_stride;
     at.max_group_rows = pk.max_group_rows;
     at.g = g.n_q_heads / g.n_kv_heads;
