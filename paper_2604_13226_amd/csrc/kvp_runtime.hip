@@ -10,6 +10,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <deque>
+#include <unordered_set>
 #include <string>
 #include <thread>
 #include <unordered_map>
@@ -172,7 +173,7 @@ struct kvp_store {
     int n_cu = 256;
     int force_generic = 0;
     int target_items = 0;  // 0: three quarters of the CU count (measured optimum at 8K context)
-    int asm_tile_rows = 32, asm_nontemporal = 0;
+    int asm_tile_rows = 32, asm_nontemporal = -1;  // -1: non-temporal gather decided per call
     int nt_loads = -1;  // test knob (KVP_ATTN_NT_LOADS=0/1): streaming hint on the attention kernel's tile loads
     int mixed_blocks = 1;  // test knob (KVP_ATTN_MIXED=0): no half blocks in launches of 256-row blocks
     int plan_copy_engine = 0;  // test knob: plans go up with hipMemcpyAsync instead of the upload kernel
@@ -320,6 +321,20 @@ int upload_plan(kvp_store *s, PlanSlot *slot, uint64_t bytes, void *hip_stream)
     return KVP_OK;
 }
 
+// Does a gather of `rows` context rows per layer, of which `unique_rows` come from distinct
+// packets, stream far more than the last-level cache holds, nearly all of it read once?  Then
+// its loads and stores carry the non-temporal hint.  Measured (us per layer, assemble + prefill):
+// one request of 2.9K rows x 32 layers 26.97 -> 25.74, 8K rows 37.85 -> 37.48, 8 requests of 16.9K
+// rows x 4 layers 500.8 -> 482.7 -- the gather itself is no faster, the attention that follows
+// is, finding fewer dirty lines in its way; a batch whose popular packets are gathered several
+// times loses the reuse (1107 -> 1187), and a 67 MB call that the attention reads right back
+// out of the cache is slower too (49 -> 54).
+bool gather_streams_once(const kvp_store *s, int64_t rows, int64_t unique_rows, int n_layers)
+{
+    const int64_t bytes = 4 * rows * n_layers * s->cfg.n_kv_heads * s->cfg.head_dim * (int64_t)s->esize;  // K and V, read and written
+    return bytes >= (512ll << 20) && unique_rows * 10 >= rows * 9;
+}
+
 // Tiles of `rows` rows at the store's tile size.
 int tiles_of(const kvp_store *s, int rows) { return (rows + s->asm_tile_rows - 1) / s->asm_tile_rows; }
 
@@ -328,7 +343,7 @@ int tiles_of(const kvp_store *s, int rows) { return (rows + s->asm_tile_rows - 1
 // layered list.
 int run_gather(kvp_store *s, const std::vector<AsmSeg> &segs, int64_t n_tiles, bool layered, int layer_begin,
                int n_layers_launch, const kvp_cache_t *cache, const CacheCheck &cc, int n_req,
-               const std::vector<int> &first_blk, const std::vector<int> &n_blk, void *hip_stream)
+               const std::vector<int> &first_blk, const std::vector<int> &n_blk, bool streams_once, void *hip_stream)
 {
     const kvp_config_t &g = s->cfg;
     if (n_tiles > 0x7fffffff) return fail(s, KVP_E_CAPACITY, "%lld gather tiles in one call", (long long)n_tiles);
@@ -379,7 +394,7 @@ int run_gather(kvp_store *s, const std::vector<AsmSeg> &segs, int64_t n_tiles, b
     a.cache = make_view(s, cache, cc.shift, bt_dev, bt_stride);
     a.n_tiles = (int)n_tiles;
     a.tile_rows = s->asm_tile_rows;
-    a.nontemporal = s->asm_nontemporal;
+    a.nontemporal = s->asm_nontemporal >= 0 ? s->asm_nontemporal : (streams_once ? 1 : 0);
     a.layer_begin = layer_begin;
     a.n_layers_total = g.n_layers;
     a.n_kv = g.n_kv_heads;
@@ -403,7 +418,8 @@ int assemble_compressed(kvp_store *s, const kvp_request_t *reqs, int n_req, int 
     if (!cache->ctx_rows) return fail(s, KVP_E_INVAL, "compressed packets need kvp_cache_t.ctx_rows");
     const int n_l = layer_end - layer_begin;
     std::vector<AsmSeg> segs;
-    int64_t n_tiles = 0;
+    int64_t n_tiles = 0, rows_total = 0, rows_unique = 0;  // (rows of the first layer asked for stand for all)
+    std::unordered_set<int64_t> seen;
     std::vector<int> pos_end(n_req), first_blk(n_req, 0), n_blk(n_req, 0);
     std::vector<int64_t> rows_end((size_t)n_req * std::max(n_l, 1), 0);
     for (int r = 0; r < n_req; ++r) {
@@ -417,6 +433,11 @@ int assemble_compressed(kvp_store *s, const kvp_request_t *reqs, int n_req, int 
             const PacketRec &p = it->second;
             if (pos + p.n_tokens > g.max_positions)
                 return fail(s, KVP_E_CAPACITY, "request %d: context exceeds max_positions %d", r, g.max_positions);
+            if (n_l > 0) {
+                const int n0 = p.compressed() ? p.rows[layer_begin] : p.n_tokens;
+                rows_total += n0;
+                if (seen.insert(q.packet_ids[j]).second) rows_unique += n0;
+            }
             for (int li = 0; li < n_l; ++li) {
                 const int l = layer_begin + li;
                 // src: first K row of head 0 in this layer; a negative stride marks a blob laid out layer by layer
@@ -447,7 +468,8 @@ int assemble_compressed(kvp_store *s, const kvp_request_t *reqs, int n_req, int 
             n_blk[r] = (int)((max_rows - 1) >> cc.shift) + 1;
         }
     }
-    int rc = run_gather(s, segs, n_tiles, true, layer_begin, n_l, cache, cc, n_req, first_blk, n_blk, hip_stream);
+    int rc = run_gather(s, segs, n_tiles, true, layer_begin, n_l, cache, cc, n_req, first_blk, n_blk,
+                        gather_streams_once(s, rows_total, rows_unique, n_l), hip_stream);
     if (rc) return rc;
     for (int r = 0; r < n_req; ++r) {
         cache->ctx_len[r] = pos_end[r];
@@ -507,7 +529,7 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
     const char *tr = getenv("KVP_ASM_TILE_ROWS");  // tuning knobs of the gather kernel
     if (tr && (atoi(tr) == 16 || atoi(tr) == 32 || atoi(tr) == 64)) s->asm_tile_rows = atoi(tr);
     const char *nt = getenv("KVP_ASM_NONTEMPORAL");
-    if (nt) s->asm_nontemporal = nt[0] == '1';
+    if (nt) s->asm_nontemporal = nt[0] == '1';  // unset: decided per call (run_gather)
     if (const char *pc = getenv("KVP_PLAN_COPY_ENGINE")) s->plan_copy_engine = pc[0] == '1';
     if (const char *mb = getenv("KVP_ATTN_MIXED")) s->mixed_blocks = mb[0] != '0';
     if (const char *nl = getenv("KVP_ATTN_NT_LOADS")) s->nt_loads = nl[0] != '0';
@@ -747,7 +769,8 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
 
     // offsets Delta_j (Sec. 4.2.1 step 4: realign, then concatenate): one segment per packet
     std::vector<AsmSeg> segs;
-    int64_t n_tiles = 0;
+    int64_t n_tiles = 0, rows_total = 0, rows_unique = 0;
+    std::unordered_set<int64_t> seen;
     std::vector<int> ctx(n_req), first_blk(n_req, 0), n_blk(n_req, 0);
     for (int r = 0; r < n_req; ++r) {
         const kvp_request_t &q = reqs[r];
@@ -757,6 +780,8 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
             auto it = s->dir.find(q.packet_ids[j]);
             if (it == s->dir.end()) return fail(s, KVP_E_NOTFOUND, "request %d: packet %lld not in the store", r, (long long)q.packet_ids[j]);
             const PacketRec &p = it->second;
+            rows_total += p.n_tokens;
+            if (seen.insert(q.packet_ids[j]).second) rows_unique += p.n_tokens;
             if (pos + p.n_tokens > g.max_positions)
                 return fail(s, KVP_E_CAPACITY, "request %d: context exceeds max_positions %d", r, g.max_positions);
             if (p.head_rows) {  // the header rows come from the shared copy, at the packet's own Delta
@@ -774,7 +799,8 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
             n_blk[r] = (int)((pos - 1) >> cc.shift) + 1;
         }
     }
-    rc = run_gather(s, segs, n_tiles, false, layer_begin, layer_end - layer_begin, cache, cc, n_req, first_blk, n_blk, hip_stream);
+    rc = run_gather(s, segs, n_tiles, false, layer_begin, layer_end - layer_begin, cache, cc, n_req, first_blk, n_blk,
+                    gather_streams_once(s, rows_total, rows_unique, layer_end - layer_begin), hip_stream);
     if (rc) return rc;
     for (int r = 0; r < n_req; ++r) {
         cache->ctx_len[r] = ctx[r];
