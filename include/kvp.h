@@ -12,6 +12,9 @@
  *     kvp_query_prefill  causal attention of the query tokens over that cache: full
  *                        over the packet prefix, causal among themselves (Sec. 4.2.1
  *                        step 4; Fig. 2(d))
+ *     kvp_prefill_packets   the same attention read in place from the store, no cache
+ *     kvp_store_put_compressed, kvp_store_put_header / _body   packets pruned per layer
+ *                        (Sec. 5.4); the global header's rows stored once (Sec. 4.1)
  *
  * Conventions
  *   - Every pointer is labelled HOST or DEVICE.  The caller owns every DEVICE buffer
@@ -74,8 +77,9 @@ enum kvp_status {
 typedef struct {
     int32_t n_layers, n_q_heads, n_kv_heads, head_dim; /* head_dim even, <= 256;
                                                           n_q_heads % n_kv_heads == 0 */
-    int32_t n_header, n_trailer; /* N_h, N_t of Eq. 2: recorded, not interpreted --
-                                    adapter rows are ordinary rows at serving time */
+    int32_t n_header, n_trailer; /* N_h, N_t of Eq. 2.  Adapter rows are ordinary rows at serving
+                                    time; n_header is used only by kvp_store_put_header /
+                                    kvp_store_put_body (header rows stored once) */
     int32_t dtype;               /* kvp_dtype of store, caches, Q, K_new, V_new, O */
     int32_t max_positions;       /* bound on ctx_len + n_q; sizes the cos/sin table */
     double rope_base;
