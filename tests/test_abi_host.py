@@ -483,3 +483,13 @@ def test_compressed_packets_errors():
     with pytest.raises(kvp.KvpError) as e:
         kvp.kvp_query_prefill(s, cache, 0, None, None, None, np.array([0, 1], np.int32), None, None)
     assert e.value.code == kvp.KVP_E_INVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the build runs on one GPU; asking the benchmark for more ends with a message, no JSON line
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
