@@ -423,6 +423,24 @@ def test_full_size_llama_k5_sampled(gpu_device):
         check_output(got["out"][r][layer], ref["out"][r][layer], w.dtype, (w.name, layer))
 
 
+def test_full_size_qwen_k20_sampled(gpu_device):
+    """Config 3 at full depth (28 layers, 4 KV heads, 20 packets, 448 packed rows per KV head:
+    two row blocks of 256, the second three quarters full), as the benchmark launches it:
+    assembly bit-exact on every layer, attention on sampled layers."""
+    w = W.qwen_k20()
+    layers = [0, 9, 27]
+    got = run_workload(w, layers=layers)
+    ref = oracle_workload(w, layers=layers)
+    r = 0
+    ctx = ref["ctx"][0]
+    for layer in range(w.n_layers):
+        rows = ctx if layer not in layers else ctx + w.requests[0].n_q
+        assert np.array_equal(got["k"][r][layer][:, :rows], ref["k"][r][layer][:, :rows]), layer
+        assert np.array_equal(got["v"][r][layer][:, :rows], ref["v"][r][layer][:, :rows]), layer
+    for layer in layers:
+        check_output(got["out"][r][layer], ref["out"][r][layer], w.dtype, (w.name, layer))
+
+
 @pytest.mark.parametrize("mk", [lambda: W.tiny_fp32(), lambda: W.llama_k5(n_layers=1, n_packets=8)])
 def test_decode_steps_after_prefill(gpu_device, mk):
     """After the query prefill the caller advances ctx_len by n_q; every later token is one
