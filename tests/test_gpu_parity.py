@@ -107,7 +107,8 @@ def test_random_geometries(gpu_device, seed):
 def test_random_geometries_with_random_launch_shapes(gpu_device, seed):
     """The same random batches with the planner's choices overridden at random: how finely
     split-KV cuts, the row block, the two-group workgroup shape, half blocks on or off, the
-    gather's tile rows and the generic kernel.  Results must not depend on any of them."""
+    gather's tile rows, the streaming hint of the tile loads and the generic kernel.  Results must
+    not depend on any of them."""
     rng = np.random.default_rng(seed + 10000)
     w = _random_geometry(seed)
     env = {"KVP_ATTN_TARGET_ITEMS": str(int(rng.choice([1, 7, 64, 300, 4000]))),
@@ -124,6 +125,8 @@ def test_random_geometries_with_random_launch_shapes(gpu_device, seed):
         env["KVP_ASM_NONTEMPORAL"] = "1"
     if rng.random() < 0.2:
         env["KVP_PLAN_COPY_ENGINE"] = "1"
+    if rng.random() < 0.4:
+        env["KVP_ATTN_NT_LOADS"] = str(int(rng.integers(0, 2)))
     os.environ.update(env)
     try:
         got = run_workload(w)
@@ -966,8 +969,27 @@ def test_random_geometries_in_place(gpu_device, seed):
         w.n_header, w.shared_header = int(rng.choice([1, 4, 8])), True
     w.name = "in place %d" % seed
     layers = list(range(w.n_layers))
-    outs, tails = _run_packets(w, layers)
-    _check_packets(w, layers, outs, tails, oracle_workload(w))
+    env = {}
+    if seed >= 408:  # the second half with the planner's choices overridden at random
+        env["KVP_ATTN_TARGET_ITEMS"] = str(int(rng.choice([1, 7, 64, 300, 4000])))
+        if rng.random() < 0.5:
+            env["KVP_ATTN_BM"] = str(int(rng.choice([128, 256])))
+        if rng.random() < 0.5:
+            env["KVP_ATTN_SPLIT_IN_WG"] = str(int(rng.integers(0, 2)))
+        if rng.random() < 0.3:
+            env["KVP_ATTN_MIXED"] = "0"
+        if rng.random() < 0.4:
+            env["KVP_ATTN_NT_LOADS"] = str(int(rng.integers(0, 2)))
+    os.environ.update(env)
+    try:
+        outs, tails = _run_packets(w, layers)
+    finally:
+        for k in env:
+            os.environ.pop(k, None)
+    try:
+        _check_packets(w, layers, outs, tails, oracle_workload(w))
+    except AssertionError as e:
+        raise AssertionError("with %s: %s" % (env, e))
 
 
 @pytest.mark.parametrize("case", ["bf16", "bf16 paged", "f32", "mixed with compressed"])
