@@ -122,7 +122,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0,
                     help="instantiate only this many layers of the workload (counter runs, where every "
                          "dispatch is slow, keep the store small with it)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="timed steps only: neither the CPU oracle timing nor the graph replay that follow "
+                         "them (the profiling commands use it)")
     ap.add_argument("--cpu-layers", type=int, default=16)
     ap.add_argument("--path", default="cache", choices=["cache", "packets"],
                     help="cache: kvp_assemble + kvp_query_prefill (the metric's path); packets: "
@@ -144,6 +146,8 @@ def main():
                     help="with --per-request on serving_mix: time the requests of this many reseeded mixes")
     ap.add_argument("--per-request", action="store_true",
                     help="batched workloads: also time every request alone (p50 / p99 latency)")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the extra measurement of the step replayed from a HIP graph")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (a known-size kernel to scale "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
@@ -388,6 +392,30 @@ def main():
                               "p99_us": float(np.percentile(lat, 99)), "mean_us": float(lat.mean()),
                               "what": "one request at a time, each met without a kept plan: assemble + prefill over "
                                       "%d layer(s), wall clock from the call to the end of the GPU work" % w.n_layers}
+    if not pipelined and args.store == "device" and not args.no_graph and not args.no_cpu_baseline:
+        # The same step replayed from a HIP graph captured once: what a caller gains who captures
+        # the launches of a repeated geometry (the per-layer launches of a short context are
+        # launch-bound).  Reported beside `value`, which stays the eagerly launched step.
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            step()                      # the plans of this geometry on this stream
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            try:
+                with torch.cuda.graph(g, stream=side):
+                    step()
+                for _ in range(args.warmup):
+                    g.replay()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.steps):
+                    g.replay()
+                torch.cuda.synchronize()
+                res["graph_replay"] = {"us_per_layer": (time.perf_counter() - t0) * 1e6 / args.steps / w.n_layers,
+                                       "what": "the same step (every launch of it) replayed from a HIP graph captured once"}
+            except Exception as e:      # (a call that cannot be captured says so; `value` does not depend on this)
+                res["graph_replay"] = {"us_per_layer": None, "what": "not captured: %s" % e}
+        note("graph replay done")
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, min(args.cpu_layers, w.n_layers))
     print(json.dumps(res))

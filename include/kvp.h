@@ -24,6 +24,16 @@
  *     asynchronous on it; only validation errors are synchronous.  All validation
  *     happens on the host before anything is launched: a call that fails has changed
  *     nothing.
+ *   - Stream capture: kvp_query_prefill and kvp_prefill_packets may be captured into a HIP
+ *     graph once a call with the same geometry (context lengths, query offsets, block table;
+ *     for kvp_prefill_packets the same requests) has run on the same stream outside capture:
+ *     that call built and uploaded the plan, the captured call only launches from it, and the
+ *     store keeps that plan unchanged until it is destroyed.  kvp_assemble may be captured when
+ *     its plan rides in the kernel arguments: a contiguous cache and at most 80 segments over
+ *     all requests (a whole packet is one segment, a header-less packet two, a compressed
+ *     packet one per layer).  A call that cannot be
+ *     captured returns KVP_E_INVAL and launches nothing.  Host-side results (ctx_len, ctx_rows)
+ *     are written when the call is captured, not when the graph runs.
  *   - A store is thread-compatible: one thread at a time per store.
  *   - Return value: 0 (KVP_OK) or a negative kvp_status; text via kvp_last_error().
  *   - Tensors are dense row-major in the order written, innermost index last.

@@ -152,6 +152,7 @@ struct kvp_store {
         const AttnTile *tiles_dev = nullptr;
         int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0, part_stride = 1, max_group_rows = 0;
         bool any_split = false, mixed = false, split_in_wg = false, shared_rows = false;
+        bool captured = false;  // a HIP graph launches from this plan: the entry is never replaced
         uint64_t need = 0;
     };
     std::deque<PrefillCached> pf_set;  // kvp_query_prefill
@@ -206,6 +207,20 @@ int hip_fail(kvp_store *s, hipError_t e, const char *what)
         hipError_t e_ = (call);                                   \
         if (e_ != hipSuccess) return hip_fail((s), e_, #call);    \
     } while (0)
+
+// Is the stream being captured into a HIP graph?  (The null stream cannot be.)  Launches made
+// then run later, any number of times: nothing they read may be rewritten, and no event of
+// the library may be recorded into the graph.
+bool capturing(const kvp_store *s, void *hip_stream)
+{
+    if (s->dry || !hip_stream) return false;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing((hipStream_t)hip_stream, &cs) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return cs == hipStreamCaptureStatusActive;
+}
 
 bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 int ilog2(int x) { int s = 0; while ((1 << s) < x) ++s; return s; }
@@ -355,6 +370,9 @@ int run_gather(kvp_store *s, const std::vector<AsmSeg> &segs, int64_t n_tiles, b
     PlanRing::Slot *slot = nullptr;
     uint64_t upload = 0;
     if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
+    if (!inline_plan && capturing(s, hip_stream))
+        return fail(s, KVP_E_INVAL, "kvp_assemble under stream capture: only calls whose plan rides in the kernel arguments "
+                                    "(contiguous cache, at most %d segments) can be captured", ASM_INLINE_SEGS);
     if (!inline_plan) {
         const uint64_t bytes = align_up(segs.size() * sizeof(AsmSeg), 64) + (uint64_t)n_req * bt_stride * 4 + 256;
         int hrc = s->ring.acquire(bytes, &slot);
@@ -811,6 +829,8 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
 }
 
 // -------------------------------------------------------------------------------------
+}  // extern "C"
+
 namespace {
 
 // Partial slots: group gi owns slots gi * stride .. + stride - 1 (stride = the largest split
@@ -894,16 +914,19 @@ kvp_store::PrefillCached &find_plan(kvp_store *s, std::deque<kvp_store::PrefillC
     sig_hash = 1469598103934665603ull;
     for (int32_t x : sig) sig_hash = (sig_hash ^ (uint32_t)x) * 1099511628211ull;
     kvp_store::PrefillCached *victim = nullptr;
+    int replaceable = 0;
     for (auto &e : set) {
         if (e.valid && e.sig_hash == sig_hash && e.stream == stream && e.sig == sig) {
             hit = true;
             e.last_use = ++s->pf_clock;
             return e;
         }
+        if (e.captured) continue;  // a graph launches from it
+        ++replaceable;
         if (!victim || (!e.valid && victim->valid) || (e.valid == victim->valid && e.last_use < victim->last_use)) victim = &e;
     }
     hit = false;
-    if (!victim || (victim->valid && (int)set.size() < std::max(PlanRing::SLOTS, s->cfg.n_layers + 1))) {
+    if (!victim || (victim->valid && replaceable < std::max(PlanRing::SLOTS, s->cfg.n_layers + 1))) {
         set.emplace_back();
         victim = &set.back();
     }
@@ -1055,6 +1078,8 @@ uint64_t q_rot_bytes(const kvp_store *s, int64_t tot_q)
 
 }  // namespace
 
+extern "C" {
+
 uint64_t kvp_prefill_workspace_bytes(const kvp_store_t *s, int32_t n_req, int32_t max_tot_q, int32_t max_ctx)
 {
     if (!s || n_req < 0 || max_tot_q < 0 || max_ctx < 0) return 0;
@@ -1127,9 +1152,14 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         }
     uint64_t sig_hash = 0;
     bool hit = false;
+    if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
+    const bool in_capture = capturing(s, hip_stream);
+    if (in_capture && tot_q == 0) return KVP_OK;  // nothing to launch, and no plan to touch
     kvp_store::PrefillCached &pf = find_plan(s, s->pf_set, sig, hip_stream, sig_hash, hit);
     const uint64_t qrb = q_rot_bytes(s, tot_q);
-    if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
+    if (in_capture && !hit)
+        return fail(s, KVP_E_INVAL, "kvp_query_prefill under stream capture needs the plan of an earlier call with the same "
+                                    "geometry on the same stream (call it once before capturing)");
 
     if (!hit) {
         PrefillPlan p;
@@ -1263,8 +1293,12 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         e = launch_combine(g.dtype, at, hip_stream);
         if (e) return hip_fail(s, (hipError_t)e, "combine launch");
     }
-    HIP_TRY(s, hipEventRecord(pf.slot->ev, st));
-    pf.slot->pending = true;
+    if (in_capture) {
+        pf.captured = true;  // the graph reads this plan at every replay: keep it until the store goes
+    } else {
+        HIP_TRY(s, hipEventRecord(pf.slot->ev, st));
+        pf.slot->pending = true;
+    }
     return KVP_OK;
 }
 
@@ -1312,8 +1346,13 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     }
     uint64_t sig_hash = 0;
     bool hit = false;
-    kvp_store::PrefillCached &pk = find_plan(s, s->pk_set, sig, hip_stream, sig_hash, hit);
     if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
+    const bool in_capture = capturing(s, hip_stream);
+    if (in_capture && tot_q == 0) return KVP_OK;  // nothing to launch, and no plan to touch
+    kvp_store::PrefillCached &pk = find_plan(s, s->pk_set, sig, hip_stream, sig_hash, hit);
+    if (in_capture && !hit)
+        return fail(s, KVP_E_INVAL, "kvp_prefill_packets under stream capture needs the plan of an earlier call with the same "
+                                    "requests on the same stream (call it once before capturing)");
 
     if (!hit) {
         const int gq = g.n_q_heads / g.n_kv_heads;
@@ -1512,8 +1551,12 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         e = launch_combine(g.dtype, at, hip_stream);
         if (e) return hip_fail(s, (hipError_t)e, "combine launch");
     }
-    HIP_TRY(s, hipEventRecord(pk.slot->ev, (hipStream_t)hip_stream));
-    pk.slot->pending = true;
+    if (in_capture) {
+        pk.captured = true;
+    } else {
+        HIP_TRY(s, hipEventRecord(pk.slot->ev, (hipStream_t)hip_stream));
+        pk.slot->pending = true;
+    }
     return KVP_OK;
 }
 

@@ -1064,6 +1064,95 @@ def test_repeated_calls_reuse_the_plan_and_give_the_same_bits(gpu_device):
         assert np.array_equal(o, outs[0])
 
 
+@pytest.mark.filterwarnings("ignore:The CUDA Graph is empty")
+@pytest.mark.parametrize("path", ["cache", "packets"])
+def test_launches_replayed_from_a_graph(gpu_device, path):
+    """A caller may capture the calls into a HIP graph (the per-layer launches of a short context
+    are launch-bound) once the plan of the same geometry exists on that stream.  Every replay,
+    with eager calls of other geometries and synchronisations in between (they would replace the
+    captured plan if it were not kept), gives the bits of the eager run, which match the oracle."""
+    import paper_2604_13226_amd as kvp
+    w = W.llama_k5(n_layers=2, n_packets=8)
+    rq = w.requests[0]
+    rq.packet_ids, rq.n_q = rq.packet_ids[:3], 20
+    ref = oracle_workload(w)
+    store = build_store(w, kvp)
+    cache = make_cache(w, kvp, store)
+    reqs = [(rq.packet_ids, 0)]
+    q_off = np.array([0, rq.n_q], np.int32)
+    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, 1, rq.n_q, w.ctx_len(0) + rq.n_q))
+    qkv = [w.query(0, l, "cuda") for l in range(w.n_layers)]
+    outs = [torch.empty_like(qkv[0][0]) for _ in range(w.n_layers)]
+    k_tail = [torch.empty_like(qkv[0][1]) for _ in range(w.n_layers)]
+
+    def calls():
+        if path == "cache":
+            kvp.kvp_assemble(store, reqs, cache)
+        for l in range(w.n_layers):
+            q, kn, vn = qkv[l]
+            if path == "cache":
+                kvp.kvp_query_prefill(store, cache, l, q, kn, vn, q_off, ws, outs[l])
+            else:
+                kvp.kvp_prefill_packets(store, reqs, l, q, kn, vn, q_off, k_tail[l], ws, outs[l])
+
+    def other_geometries(n):  # eager calls with n other query lengths: each needs a plan of its own
+        for i in range(n):
+            nq = 1 + i
+            q, kn, vn = (x[:nq].contiguous() for x in qkv[0])
+            o = torch.empty_like(q)
+            qo = np.array([0, nq], np.int32)
+            if path == "cache":
+                kvp.kvp_query_prefill(store, cache, 0, q, kn, vn, qo, ws, o)
+            else:
+                kvp.kvp_prefill_packets(store, reqs, 0, q, kn, vn, qo, torch.empty_like(kn), ws, o)
+
+    def state():
+        torch.cuda.synchronize()
+        got = [o.clone() for o in outs]
+        if path == "cache":
+            rows = w.ctx_len(0) + rq.n_q
+            got += [x.clone() for l in range(w.n_layers) for x in cache.logical(0, l, rows)]
+        else:
+            got += [t.clone() for t in k_tail]
+        return got
+
+    def clobber():
+        for t in outs + k_tail:
+            t.fill_(float("nan"))
+        if path == "cache":
+            cache.k.zero_()
+            cache.v.zero_()
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        # a geometry the stream has no plan for cannot be captured: the call says so, launches nothing
+        empty = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(empty, stream=side):
+            with pytest.raises(kvp.KvpError, match="capture"):
+                if path == "cache":
+                    kvp.kvp_query_prefill(store, cache, 0, *qkv[0], q_off, ws, outs[0])
+                else:
+                    kvp.kvp_prefill_packets(store, reqs, 0, *qkv[0], q_off, k_tail[0], ws, outs[0])
+        calls()                               # eager: builds and keeps the plans
+        eager = state()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            calls()
+        for replay in range(3):
+            other_geometries(12)              # more plans than the store keeps beside captured ones
+            clobber()
+            g.replay()
+            now = state()
+            for a, b in zip(eager, now):
+                assert torch.equal(a.view(torch.int16), b.view(torch.int16)), (path, replay)
+        calls()                               # and eager calls still work next to the graph
+        for a, b in zip(eager, state()):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    for l in range(w.n_layers):
+        check_output(outs[l].float().cpu().numpy().astype(np.float64), ref["out"][0][l], w.dtype, (path, l))
+    kvp.kvp_store_destroy(store)
+
+
 def test_zz_report_worst_relative_rms(gpu_device):
     """Prints the largest relative rms error the tests above saw (run with -s to see it)."""
     print("worst relative rms error:", WORST_REL_RMS)
