@@ -153,6 +153,10 @@ struct kvp_store {
         int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0, part_stride = 1, max_group_rows = 0;
         bool any_split = false, mixed = false, split_in_wg = false, shared_rows = false;
         bool captured = false;  // a HIP graph launches from this plan: the entry is never replaced
+        // Launches from a kept plan record no event (an event per layer costs a marker packet
+        // between the kernels and a microsecond of host time); the entry remembers that work
+        // newer than its event may still read the plan, and settles that when it is replaced.
+        bool used_since_event = false;
         uint64_t need = 0;
     };
     std::deque<PrefillCached> pf_set;  // kvp_query_prefill
@@ -597,6 +601,10 @@ int kvp_store_destroy(kvp_store_t *s)
     if (!s) return KVP_E_INVAL;
     if (!s->dry) {
         (void)hipSetDevice(s->cfg.device);
+        bool unsettled = false;  // launches from kept plans that no event of ours stands behind
+        for (auto &e : s->pf_set) unsettled |= e.used_since_event;
+        for (auto &e : s->pk_set) unsettled |= e.used_since_event;
+        if (unsettled) (void)hipDeviceSynchronize();
         s->ring.release();
         for (auto &e : s->pf_set) e.own.release(false);
         for (auto &e : s->pk_set) e.own.release(false);
@@ -934,6 +942,24 @@ kvp_store::PrefillCached &find_plan(kvp_store *s, std::deque<kvp_store::PrefillC
     return *victim;
 }
 
+// Before an entry's plan buffer is rewritten: if launches newer than the entry's event may
+// still read it, put an event behind them now (the buffer's ensure() then waits for it).
+int settle_plan_entry(kvp_store *s, kvp_store::PrefillCached &e)
+{
+    if (s->dry || !e.used_since_event) return KVP_OK;
+    e.used_since_event = false;
+    PlanSlot &slot = e.own;
+    hipError_t rc = slot.ev ? hipEventRecord(slot.ev, (hipStream_t)e.stream) : hipErrorInvalidHandle;
+    if (rc == hipSuccess) {
+        slot.pending = true;
+        return KVP_OK;
+    }
+    (void)hipGetLastError();  // (the stream may be gone: wait for the whole device instead)
+    HIP_TRY(s, hipDeviceSynchronize());
+    slot.pending = false;
+    return KVP_OK;
+}
+
 struct PrefillPlan {
     int kind = ATTN_GENERIC, bm = 8, bn = 64;
     std::vector<ReqMeta> reqs;
@@ -1169,6 +1195,8 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
                                p.items.size() * sizeof(AttnItem) + (uint64_t)n_req * bt_stride * 4 + 6 * 64;
         pf.valid = false;  // the entry's buffer is rewritten below
         PlanSlot *slot = &pf.own;
+        rc = settle_plan_entry(s, pf);
+        if (rc) return rc;
         int hrc = slot->ensure(bytes, s->dry);
         if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
         PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
@@ -1295,6 +1323,8 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     }
     if (in_capture) {
         pf.captured = true;  // the graph reads this plan at every replay: keep it until the store goes
+    } else if (hit) {
+        pf.used_since_event = true;
     } else {
         HIP_TRY(s, hipEventRecord(pf.slot->ev, st));
         pf.slot->pending = true;
@@ -1463,6 +1493,8 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
                                items.size() * sizeof(AttnItem) + tiles.size() * sizeof(AttnTile) + 6 * 64;
         pk.valid = false;  // the entry's buffer is rewritten below
         PlanSlot *slot = &pk.own;
+        int src = settle_plan_entry(s, pk);
+        if (src) return src;
         int hrc = slot->ensure(bytes, s->dry);
         if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
         PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
@@ -1553,6 +1585,8 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     }
     if (in_capture) {
         pk.captured = true;
+    } else if (hit) {
+        pk.used_since_event = true;
     } else {
         HIP_TRY(s, hipEventRecord(pk.slot->ev, (hipStream_t)hip_stream));
         pk.slot->pending = true;
