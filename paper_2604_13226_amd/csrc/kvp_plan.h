@@ -38,22 +38,21 @@ struct CacheView {
 };
 
 // Short lists ride in the kernel arguments (nothing is uploaded) and are scanned linearly.
-// Longer ones are uploaded; the arguments then carry the first tile of every pivot_step-th
-// segment, so the search is a scan of at most ASM_PIVOTS argument words and a bisection of
-// pivot_step list entries.
+// Longer ones are uploaded together with a map from tile to segment, so a workgroup finds its
+// segment with two dependent loads whatever the length of the list.
 constexpr int ASM_INLINE_SEGS = 80;
-constexpr int ASM_PIVOTS = 32;
 
 struct AsmArgs {
     const void *arena;
     const float2 *cs;    // [max_positions][d/2] (cos, sin)
     const AsmSeg *segs;  // device list, or nullptr: use `inline_seg`
+    const int32_t *tile_seg;  // device, with `segs`: the segment of every tile
     CacheView cache;
     int32_t n_tiles, layer_begin, n_layers_total, n_kv, d;
     int32_t tile_rows, nontemporal;
+    int32_t split_kv;  // grid.z = 2: a workgroup moves the K rows of its tile (z = 0) or the V rows (z = 1)
     int32_t layered;  // segments name their own layer; blockIdx.y = kv head
-    int32_t n_segs, n_pivots, pivot_step;
-    int32_t pivot[ASM_PIVOTS];
+    int32_t n_segs;
     AsmSeg inline_seg[ASM_INLINE_SEGS];
 };
 static_assert(sizeof(AsmArgs) <= 4096, "kernel arguments are limited to 4 KB");

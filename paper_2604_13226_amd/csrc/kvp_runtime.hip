@@ -178,7 +178,10 @@ struct kvp_store {
     int n_cu = 256;
     int force_generic = 0;
     int target_items = 0;  // 0: three quarters of the CU count (measured optimum at 8K context)
-    int asm_tile_rows = 32, asm_nontemporal = -1;  // -1: non-temporal gather decided per call
+    int asm_tile_rows = 0;  // 0: chosen per call (tile_rows_for)
+    int asm_nontemporal = -1;  // -1: non-temporal gather decided per call
+    int asm_split_kv = 1;  // the gather's workgroups move either the K or the V rows of a tile (KVP_ASM_SPLIT_KV=0: both)
+    int dbg_tile_rows = 32;  // tile rows of the last gather plan
     int nt_loads = -1;  // test knob (KVP_ATTN_NT_LOADS=0/1): streaming hint on the attention kernel's tile loads
     int mixed_blocks = 1;  // test knob (KVP_ATTN_MIXED=0): no half blocks in launches of 256-row blocks
     int plan_copy_engine = 0;  // test knob: plans go up with hipMemcpyAsync instead of the upload kernel
@@ -355,12 +358,23 @@ bool gather_streams_once(const kvp_store *s, int64_t rows, int64_t unique_rows, 
 }
 
 // Tiles of `rows` rows at the store's tile size.
-int tiles_of(const kvp_store *s, int rows) { return (rows + s->asm_tile_rows - 1) / s->asm_tile_rows; }
+int tiles_of(int rows, int tile_rows) { return (rows + tile_rows - 1) / tile_rows; }
+
+// Rows per gather tile.  Measured with workgroups that move either K or V: 32 rows (8 KB in,
+// 8 KB out per workgroup) on a contiguous cache -- one 8K request x 32 layers 382 -> 365 us, eight
+// 16.9K requests x 4 layers 795 -> 783 us, against 374 and 788 with 64 rows -- and 64 rows on a
+// paged cache, where every row's block is looked up (64 requests, 290K rows: 352 -> 342 us, with
+// 32 rows 385).
+int tile_rows_for(const kvp_store *s, const kvp_cache_t *cache)
+{
+    if (s->asm_tile_rows) return s->asm_tile_rows;
+    return cache->layout == KVP_PAGED ? 64 : 32;
+}
 
 // Uploads a gather plan (segment list, block table) if it does not fit the kernel arguments,
 // and launches the gather: grid = (tiles, layers x kv heads), or (tiles, kv heads) for a
 // layered list.
-int run_gather(kvp_store *s, const std::vector<AsmSeg> &segs, int64_t n_tiles, bool layered, int layer_begin,
+int run_gather(kvp_store *s, const std::vector<AsmSeg> &segs, int64_t n_tiles, int tile_rows, bool layered, int layer_begin,
                int n_layers_launch, const kvp_cache_t *cache, const CacheCheck &cc, int n_req,
                const std::vector<int> &first_blk, const std::vector<int> &n_blk, bool streams_once, void *hip_stream)
 {
@@ -370,7 +384,7 @@ int run_gather(kvp_store *s, const std::vector<AsmSeg> &segs, int64_t n_tiles, b
     for (int r = 0; r < n_req; ++r) bt_stride = std::max(bt_stride, n_blk[r]);
     const bool inline_plan = (int)segs.size() <= ASM_INLINE_SEGS && cache->layout == KVP_CONTIG;
     const AsmSeg *segs_dev = nullptr;
-    const int32_t *bt_dev = nullptr;
+    const int32_t *bt_dev = nullptr, *tile_seg_dev = nullptr;
     PlanRing::Slot *slot = nullptr;
     uint64_t upload = 0;
     if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
@@ -378,12 +392,18 @@ int run_gather(kvp_store *s, const std::vector<AsmSeg> &segs, int64_t n_tiles, b
         return fail(s, KVP_E_INVAL, "kvp_assemble under stream capture: only calls whose plan rides in the kernel arguments "
                                     "(contiguous cache, at most %d segments) can be captured", ASM_INLINE_SEGS);
     if (!inline_plan) {
-        const uint64_t bytes = align_up(segs.size() * sizeof(AsmSeg), 64) + (uint64_t)n_req * bt_stride * 4 + 256;
+        const uint64_t bytes = align_up(segs.size() * sizeof(AsmSeg), 64) + align_up((uint64_t)n_tiles * 4, 64) +
+                               (uint64_t)n_req * bt_stride * 4 + 256;
         int hrc = s->ring.acquire(bytes, &slot);
         if (hrc) return hip_fail(s, (hipError_t)hrc, "plan buffer");
         PlanWriter w{slot->host, s->dry ? nullptr : slot->dev};
         AsmSeg *sh = w.put<AsmSeg>(segs.size(), &segs_dev);
         if (!segs.empty()) memcpy(sh, segs.data(), segs.size() * sizeof(AsmSeg));
+        int32_t *ts = w.put<int32_t>((uint64_t)n_tiles, &tile_seg_dev);
+        for (size_t i = 0; i < segs.size(); ++i) {
+            const int32_t end = i + 1 < segs.size() ? segs[i + 1].tile0 : (int32_t)n_tiles;
+            for (int32_t t = segs[i].tile0; t < end; ++t) ts[t] = (int32_t)i;
+        }
         if (cache->layout == KVP_PAGED && bt_stride > 0) {
             int32_t *bh = w.put<int32_t>((uint64_t)n_req * bt_stride, &bt_dev);
             int rc = compact_block_table(s, cache, n_req, first_blk, n_blk, bt_stride, bh);
@@ -393,6 +413,7 @@ int run_gather(kvp_store *s, const std::vector<AsmSeg> &segs, int64_t n_tiles, b
     }
     s->dbg_segs = segs;
     s->dbg_layered = layered;
+    s->dbg_tile_rows = tile_rows;
     if (s->dry || n_tiles == 0 || n_layers_launch <= 0) return KVP_OK;
 
     hipStream_t st = (hipStream_t)hip_stream;
@@ -401,8 +422,7 @@ int run_gather(kvp_store *s, const std::vector<AsmSeg> &segs, int64_t n_tiles, b
     a.cs = s->cs_dev;
     a.segs = nullptr;
     a.n_segs = (int)segs.size();
-    a.n_pivots = 0;
-    a.pivot_step = 1;
+    a.tile_seg = nullptr;
     a.layered = layered ? 1 : 0;
     if (inline_plan) {
         for (size_t i = 0; i < segs.size(); ++i) a.inline_seg[i] = segs[i];
@@ -410,13 +430,13 @@ int run_gather(kvp_store *s, const std::vector<AsmSeg> &segs, int64_t n_tiles, b
         int urc = upload_plan(s, slot, upload, hip_stream);
         if (urc) return urc;
         a.segs = segs_dev;
-        a.pivot_step = ((int)segs.size() + ASM_PIVOTS - 1) / ASM_PIVOTS;
-        for (int i = 0; i * a.pivot_step < (int)segs.size(); ++i) a.pivot[a.n_pivots++] = segs[(size_t)i * a.pivot_step].tile0;
+        a.tile_seg = tile_seg_dev;
     }
     a.cache = make_view(s, cache, cc.shift, bt_dev, bt_stride);
     a.n_tiles = (int)n_tiles;
-    a.tile_rows = s->asm_tile_rows;
+    a.tile_rows = tile_rows;
     a.nontemporal = s->asm_nontemporal >= 0 ? s->asm_nontemporal : (streams_once ? 1 : 0);
+    a.split_kv = s->asm_split_kv;
     a.layer_begin = layer_begin;
     a.n_layers_total = g.n_layers;
     a.n_kv = g.n_kv_heads;
@@ -439,6 +459,7 @@ int assemble_compressed(kvp_store *s, const kvp_request_t *reqs, int n_req, int 
     const kvp_config_t &g = s->cfg;
     if (!cache->ctx_rows) return fail(s, KVP_E_INVAL, "compressed packets need kvp_cache_t.ctx_rows");
     const int n_l = layer_end - layer_begin;
+    const int tile_rows = tile_rows_for(s, cache);
     std::vector<AsmSeg> segs;
     int64_t n_tiles = 0, rows_total = 0, rows_unique = 0;  // (rows of the first layer asked for stand for all)
     std::unordered_set<int64_t> seen;
@@ -466,7 +487,7 @@ int assemble_compressed(kvp_store *s, const kvp_request_t *reqs, int n_req, int 
                 auto emit = [&](int64_t src, int stride, int n) {
                     if (n == 0) return;
                     segs.push_back(AsmSeg{src, stride, n, (int32_t)row[li], (int32_t)pos, r, l, (int32_t)n_tiles, 0});
-                    n_tiles += tiles_of(s, n);
+                    n_tiles += tiles_of(n, tile_rows);
                     row[li] += n;
                 };
                 const int64_t slices = (int64_t)l * g.n_kv_heads * g.head_dim;  // x stride = elements before layer l
@@ -490,7 +511,7 @@ int assemble_compressed(kvp_store *s, const kvp_request_t *reqs, int n_req, int 
             n_blk[r] = (int)((max_rows - 1) >> cc.shift) + 1;
         }
     }
-    int rc = run_gather(s, segs, n_tiles, true, layer_begin, n_l, cache, cc, n_req, first_blk, n_blk,
+    int rc = run_gather(s, segs, n_tiles, tile_rows, true, layer_begin, n_l, cache, cc, n_req, first_blk, n_blk,
                         gather_streams_once(s, rows_total, rows_unique, n_l), hip_stream);
     if (rc) return rc;
     for (int r = 0; r < n_req; ++r) {
@@ -550,6 +571,8 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
     s->force_generic = fg && fg[0] == '1';
     const char *tr = getenv("KVP_ASM_TILE_ROWS");  // tuning knobs of the gather kernel
     if (tr && (atoi(tr) == 16 || atoi(tr) == 32 || atoi(tr) == 64)) s->asm_tile_rows = atoi(tr);
+    if (const char *sk = getenv("KVP_ASM_SPLIT_KV")) s->asm_split_kv = sk[0] != '0';
+    if (cfg->head_dim != 64 && cfg->head_dim != 128 && cfg->head_dim != 256) s->asm_split_kv = 0;  // (the scalar kernel moves both)
     const char *nt = getenv("KVP_ASM_NONTEMPORAL");
     if (nt) s->asm_nontemporal = nt[0] == '1';  // unset: decided per call (run_gather)
     if (const char *pc = getenv("KVP_PLAN_COPY_ENGINE")) s->plan_copy_engine = pc[0] == '1';
@@ -794,6 +817,7 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
     }
 
     // offsets Delta_j (Sec. 4.2.1 step 4: realign, then concatenate): one segment per packet
+    const int tile_rows = tile_rows_for(s, cache);
     std::vector<AsmSeg> segs;
     int64_t n_tiles = 0, rows_total = 0, rows_unique = 0;
     std::unordered_set<int64_t> seen;
@@ -812,10 +836,10 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
                 return fail(s, KVP_E_CAPACITY, "request %d: context exceeds max_positions %d", r, g.max_positions);
             if (p.head_rows) {  // the header rows come from the shared copy, at the packet's own Delta
                 segs.push_back(AsmSeg{s->header.elem_off, s->header.stride, p.head_rows, (int32_t)pos, (int32_t)pos, r, 0, (int32_t)n_tiles, 0});
-                n_tiles += tiles_of(s, p.head_rows);
+                n_tiles += tiles_of(p.head_rows, tile_rows);
             }
             segs.push_back(AsmSeg{p.elem_off, p.stride, p.body_rows(), (int32_t)pos + p.head_rows, (int32_t)pos, r, 0, (int32_t)n_tiles, 0});
-            n_tiles += tiles_of(s, p.body_rows());
+            n_tiles += tiles_of(p.body_rows(), tile_rows);
             pos += p.n_tokens;
         }
         if (pos > cc.cap_rows) return fail(s, KVP_E_CAPACITY, "request %d: %lld rows do not fit the cache (%lld)", r, (long long)pos, (long long)cc.cap_rows);
@@ -825,7 +849,7 @@ int kvp_assemble(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req, int32
             n_blk[r] = (int)((pos - 1) >> cc.shift) + 1;
         }
     }
-    rc = run_gather(s, segs, n_tiles, false, layer_begin, layer_end - layer_begin, cache, cc, n_req, first_blk, n_blk,
+    rc = run_gather(s, segs, n_tiles, tile_rows, false, layer_begin, layer_end - layer_begin, cache, cc, n_req, first_blk, n_blk,
                     gather_streams_once(s, rows_total, rows_unique, layer_end - layer_begin), hip_stream);
     if (rc) return rc;
     for (int r = 0; r < n_req; ++r) {
@@ -1603,8 +1627,8 @@ int64_t kvp_debug_last_plan(const kvp_store_t *s, int32_t which, int64_t *out, i
         // src_base, stride, first row in the segment, rows, cache row, Delta, request, layer (layered lists)
         tiles.push_back(0);
         for (const AsmSeg &g : s->dbg_segs)
-            for (int t0 = 0; t0 < g.n_rows; t0 += s->asm_tile_rows) {
-                int64_t row[8] = {g.src_base, g.stride, t0, std::min(s->asm_tile_rows, g.n_rows - t0), g.dst_row + t0,
+            for (int t0 = 0; t0 < g.n_rows; t0 += s->dbg_tile_rows) {
+                int64_t row[8] = {g.src_base, g.stride, t0, std::min(s->dbg_tile_rows, g.n_rows - t0), g.dst_row + t0,
                                   g.pos, g.req, s->dbg_layered ? g.layer : -1};
                 tiles.insert(tiles.end(), row, row + 8);
                 ++tiles[0];

@@ -107,8 +107,8 @@ def test_random_geometries(gpu_device, seed):
 def test_random_geometries_with_random_launch_shapes(gpu_device, seed):
     """The same random batches with the planner's choices overridden at random: how finely
     split-KV cuts, the row block, the two-group workgroup shape, half blocks on or off, the
-    gather's tile rows, the streaming hint of the tile loads and the generic kernel.  Results must
-    not depend on any of them."""
+    gather's tile rows and whether its workgroups move K and V together, the streaming hint of the
+    tile loads and the generic kernel.  Results must not depend on any of them."""
     rng = np.random.default_rng(seed + 10000)
     w = _random_geometry(seed)
     env = {"KVP_ATTN_TARGET_ITEMS": str(int(rng.choice([1, 7, 64, 300, 4000]))),
@@ -127,6 +127,8 @@ def test_random_geometries_with_random_launch_shapes(gpu_device, seed):
         env["KVP_PLAN_COPY_ENGINE"] = "1"
     if rng.random() < 0.4:
         env["KVP_ATTN_NT_LOADS"] = str(int(rng.integers(0, 2)))
+    if rng.random() < 0.4:
+        env["KVP_ASM_SPLIT_KV"] = "0"
     os.environ.update(env)
     try:
         got = run_workload(w)
