@@ -95,8 +95,18 @@ def _check(store, rc):
         raise KvpError(rc, (load().kvp_last_error(store) or b"").decode())
 
 
-def _stream(stream):
+_raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)  # the current stream's handle without a Stream object
+
+
+def _stream(stream, store=None):
+    """Raw hipStream_t of `stream` (a torch stream or a raw handle), or of torch's current stream
+    on the store's device."""
     if stream is None:
+        if store is not None:
+            if store.dry:
+                return None
+            if _raw_stream is not None:
+                return _raw_stream(store.cfg.device)
         return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
 
@@ -111,10 +121,9 @@ class Store:
     def __init__(self, handle, cfg, arena):
         self.handle, self.cfg, self.arena = handle, cfg, arena
         self.dry = cfg.device == KVP_DEVICE_NONE
-
-    @property
-    def torch_dtype(self):
-        return torch.bfloat16 if self.cfg.dtype == KVP_BF16 else torch.float32
+        self.torch_dtype = torch.bfloat16 if cfg.dtype == KVP_BF16 else torch.float32
+        self.q_row = (cfg.n_q_heads, cfg.head_dim)     # trailing dims of q / out
+        self.kv_row = (cfg.n_kv_heads, cfg.head_dim)   # ... of k_new / v_new
 
     def __del__(self):
         try:
@@ -353,12 +362,29 @@ def kvp_assemble(store, requests, cache, layer_begin=0, layer_end=None, stream=N
     if layer_end is None:
         layer_end = store.cfg.n_layers
     rc = load().kvp_assemble(store.handle, arr, n_req, int(layer_begin), int(layer_end),
-                             ctypes.byref(cache.c), _stream(stream))
-    _check(store.handle, rc)
+                             ctypes.byref(cache.c), _stream(stream, store))
+    if rc:
+        _check(store.handle, rc)
 
 
 def kvp_prefill_workspace_bytes(store, n_req, max_tot_q, max_ctx):
     return int(load().kvp_prefill_workspace_bytes(store.handle, int(n_req), int(max_tot_q), int(max_ctx)))
+
+
+def _check_qkv(store, tot_q, q, k_new, v_new, out, k_tail=None):
+    """The kernels take these shapes for granted: dense device tensors of the store's dtype,
+    [tot_q][heads][head_dim]."""
+    td = store.torch_dtype
+    qs, ks = (tot_q,) + store.q_row, (tot_q,) + store.kv_row
+    ok = (q.shape == qs and out.shape == qs and k_new.shape == ks and v_new.shape == ks
+          and q.dtype == td and out.dtype == td and k_new.dtype == td and v_new.dtype == td
+          and q.is_cuda and out.is_cuda and k_new.is_cuda and v_new.is_cuda
+          and q.is_contiguous() and out.is_contiguous() and k_new.is_contiguous() and v_new.is_contiguous())
+    if k_tail is not None:
+        ok = ok and k_tail.shape == ks and k_tail.dtype == td and k_tail.is_cuda and k_tail.is_contiguous()
+    if not ok:
+        raise ValueError("q / out must be dense %s tensors on the GPU of shape %s, k_new / v_new%s of shape %s"
+                         % (td, qs, " / k_tail" if k_tail is not None else "", ks))
 
 
 def kvp_query_prefill(store, cache, layer, q, k_new, v_new, q_offsets, workspace, out, flags=0,
@@ -371,17 +397,13 @@ def kvp_query_prefill(store, cache, layer, q, k_new, v_new, q_offsets, workspace
         rc = load().kvp_query_prefill(store.handle, ctypes.byref(cache.c), int(layer), None, None, None,
                                       qo.ctypes.data, n_req, int(flags), None, 1 << 60, None, None)
         return _check(store.handle, rc)
-    for t in (q, k_new, v_new, out):
-        assert t.is_cuda and t.is_contiguous() and t.dtype == store.torch_dtype
-    g = store.cfg
-    tot_q = int(qo[-1])
-    assert tuple(q.shape) == (tot_q, g.n_q_heads, g.head_dim) and out.shape == q.shape
-    assert tuple(k_new.shape) == (tot_q, g.n_kv_heads, g.head_dim) and v_new.shape == k_new.shape
+    _check_qkv(store, int(qo[-1]), q, k_new, v_new, out)
     rc = load().kvp_query_prefill(store.handle, ctypes.byref(cache.c), int(layer), q.data_ptr(),
                                   k_new.data_ptr(), v_new.data_ptr(), qo.ctypes.data, n_req, int(flags),
-                                  workspace.data_ptr(), int(workspace.numel()), out.data_ptr(),
-                                  _stream(stream))
-    _check(store.handle, rc)
+                                  workspace.data_ptr(), workspace.numel(), out.data_ptr(),
+                                  _stream(stream, store))
+    if rc:
+        _check(store.handle, rc)
 
 
 def kvp_prefill_packets(store, requests, layer, q, k_new, v_new, q_offsets, k_tail, workspace, out,
@@ -395,13 +417,13 @@ def kvp_prefill_packets(store, requests, layer, q, k_new, v_new, q_offsets, k_ta
         rc = load().kvp_prefill_packets(store.handle, arr, n_req, int(layer), None, None, None, qo.ctypes.data,
                                         int(flags), None, None, 1 << 60, None, None)
         return _check(store.handle, rc)
-    for t in (q, k_new, v_new, out, k_tail):
-        assert t.is_cuda and t.is_contiguous() and t.dtype == store.torch_dtype
-    assert k_tail.shape == k_new.shape and out.shape == q.shape
+    _check_qkv(store, int(qo[-1]), q, k_new, v_new, out, k_tail)
     rc = load().kvp_prefill_packets(store.handle, arr, n_req, int(layer), q.data_ptr(), k_new.data_ptr(),
                                     v_new.data_ptr(), qo.ctypes.data, int(flags), k_tail.data_ptr(),
-                                    workspace.data_ptr(), int(workspace.numel()), out.data_ptr(), _stream(stream))
-    _check(store.handle, rc)
+                                    workspace.data_ptr(), workspace.numel(), out.data_ptr(),
+                                    _stream(stream, store))
+    if rc:
+        _check(store.handle, rc)
 
 
 def kvp_last_error(store):
