@@ -227,7 +227,8 @@ def main():
                     main.wait_event(ready[layer])
                 q, kn, vn = qkv[layer]
                 kvp.kvp_query_prefill(store, cache, layer, q, kn, vn, q_off, ws, out)
-                free[layer].record(main)
+                if layer % G == G - 1 or layer == w.n_layers - 1:   # (only a group's last layer is waited for)
+                    free[layer].record(main)
             if ev:
                 ev[1].record()
                 ev[2].record()
