@@ -118,6 +118,32 @@ def test_assemble_plan_offsets_and_tiles():
     assert all((x * 2) % 256 == 0 for x in starts)
 
 
+def test_gather_tile_rows_follow_the_cache_layout_and_long_lists_plan():
+    """Tiles hold up to 32 rows on a contiguous cache and up to 64 on a paged one; a list too long
+    for the kernel arguments (more than 80 segments) plans the same way and covers every row once."""
+    s = dry_store(max_positions=1 << 17)
+    rng = np.random.default_rng(5)
+    lens = [int(x) for x in rng.integers(1, 200, size=120)]
+    for pid, n in enumerate(lens):
+        kvp.kvp_store_put(s, pid, None, None, n_tokens=n)
+    ids = list(range(120))
+    total = sum(lens)
+    contig = kvp.Cache.dry(1, t_cap=total)
+    nb = (total + 15) // 16
+    paged = kvp.Cache.dry(1, layout=kvp.KVP_PAGED, n_blocks=nb, block_size=16,
+                          block_table=np.arange(nb, dtype=np.int32)[None, :])
+    for cache, cap in ((contig, 32), (paged, 64)):
+        kvp.kvp_assemble(s, [(ids, 0)], cache)
+        t = _tiles(s)
+        assert int(t[:, 3].max()) == cap
+        covered = np.zeros(total, int)
+        for src, stride, tok0, n_tok, dst, pos, _, _ in t:
+            assert 1 <= n_tok <= cap and tok0 % cap == 0 and tok0 + n_tok <= stride and dst == pos + tok0
+            covered[dst:dst + n_tok] += 1
+        assert np.all(covered == 1)
+        assert len(t) == sum((n + cap - 1) // cap for n in lens)
+
+
 def test_assemble_errors_leave_ctx_len_alone():
     s = dry_store(max_positions=300)
     kvp.kvp_store_put(s, 0, None, None, n_tokens=100)
