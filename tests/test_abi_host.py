@@ -144,6 +144,25 @@ def test_gather_tile_rows_follow_the_cache_layout_and_long_lists_plan():
         assert len(t) == sum((n + cap - 1) // cap for n in lens)
 
 
+def test_empty_batches_are_legal_and_plan_nothing():
+    s = dry_store()
+    kvp.kvp_store_put(s, 0, None, None, n_tokens=50)
+    cache = kvp.Cache.dry(1, t_cap=100)
+    cache.ctx_len[0] = 7
+    kvp.kvp_assemble(s, [], cache)
+    assert int(kvp.kvp_debug_last_plan(s, 0)[0]) == 0 and cache.ctx_len[0] == 7
+    none = np.array([0], np.int32)
+    kvp.kvp_query_prefill(s, cache, 0, None, None, None, none, None, None)
+    assert list(kvp.kvp_debug_last_plan(s, 1)[2:5]) == [0, 0, 0]      # no groups, items or slots
+    kvp.kvp_prefill_packets(s, [], 0, None, None, None, none, None, None, None)
+    assert list(kvp.kvp_debug_last_plan(s, 1)[2:5]) == [0, 0, 0]
+    # a request without packets and without query rows is as empty
+    kvp.kvp_assemble(s, [([], 0)], cache)
+    assert cache.ctx_len[0] == 0 and int(kvp.kvp_debug_last_plan(s, 0)[0]) == 0
+    kvp.kvp_query_prefill(s, cache, 0, None, None, None, np.array([0, 0], np.int32), None, None)
+    assert list(kvp.kvp_debug_last_plan(s, 1)[2:5]) == [0, 0, 0]
+
+
 def test_assemble_errors_leave_ctx_len_alone():
     s = dry_store(max_positions=300)
     kvp.kvp_store_put(s, 0, None, None, n_tokens=100)

@@ -1066,6 +1066,31 @@ def test_repeated_calls_reuse_the_plan_and_give_the_same_bits(gpu_device):
         assert np.array_equal(o, outs[0])
 
 
+def test_empty_batches_touch_nothing(gpu_device):
+    """No requests, or requests without packets and without query rows: the calls succeed, launch
+    nothing and leave the cache, the output and ctx_len of other requests alone."""
+    import paper_2604_13226_amd as kvp
+    w = W.llama_k5(n_layers=1, n_packets=8)
+    store = build_store(w, kvp)
+    cache = make_cache(w, kvp, store)
+    cache.k.fill_(1.0)
+    cache.v.fill_(1.0)
+    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, 1, 8, 64))
+    q, kn, vn = (x[:0].contiguous() for x in w.query(0, 0, "cuda"))
+    out = torch.empty_like(q)
+    none = np.array([0], np.int32)
+    kvp.kvp_assemble(store, [], cache)
+    kvp.kvp_query_prefill(store, cache, 0, q, kn, vn, none, ws, out)
+    kvp.kvp_prefill_packets(store, [], 0, q, kn, vn, none, torch.empty_like(kn), ws, out)
+    kvp.kvp_assemble(store, [([], 0)], cache)
+    assert cache.ctx_len[0] == 0
+    kvp.kvp_query_prefill(store, cache, 0, q, kn, vn, np.array([0, 0], np.int32), ws, out)
+    kvp.kvp_prefill_packets(store, [([], 0)], 0, q, kn, vn, np.array([0, 0], np.int32), torch.empty_like(kn), ws, out)
+    torch.cuda.synchronize()
+    assert bool((cache.k == 1.0).all()) and bool((cache.v == 1.0).all())
+    kvp.kvp_store_destroy(store)
+
+
 @pytest.mark.filterwarnings("ignore:The CUDA Graph is empty")
 @pytest.mark.parametrize("path", ["cache", "packets"])
 def test_launches_replayed_from_a_graph(gpu_device, path):
