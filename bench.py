@@ -160,7 +160,7 @@ def main():
     import numpy as np
     import torch
     import paper_2604_13226_amd as kvp
-    from tests.gpu_harness import build_store, make_cache
+    from kvp_setup import build_store, make_cache
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     t_start = time.perf_counter()

@@ -34,6 +34,9 @@
  *     packet one per layer).  A call that cannot be
  *     captured returns KVP_E_INVAL and launches nothing.  Host-side results (ctx_len, ctx_rows)
  *     are written when the call is captured, not when the graph runs.
+ *   - A stream handed to kvp_query_prefill or kvp_prefill_packets must stay alive until the store
+ *     is destroyed: the store puts an event behind that stream's work before it rewrites a plan
+ *     the stream's launches read.
  *   - A store is thread-compatible: one thread at a time per store.
  *   - Return value: 0 (KVP_OK) or a negative kvp_status; text via kvp_last_error().
  *   - Tensors are dense row-major in the order written, innermost index last.
@@ -256,6 +259,12 @@ int kvp_prefill_packets(kvp_store_t *store, const kvp_request_t *reqs, int32_t n
                         const void *q, const void *k_new, const void *v_new, const int32_t *q_offsets,
                         uint32_t flags, void *k_tail, void *workspace, uint64_t workspace_bytes,
                         void *out, void *hip_stream);
+
+/* Stream capture keeps the plan a captured kvp_query_prefill / kvp_prefill_packets launches from
+ * (at most 64 per entry point and store; a capture beyond that returns KVP_E_CAPACITY).  Once the
+ * graphs that were captured on this store have been destroyed, this call makes those plans
+ * replaceable again.  Returns the number of plans released, or KVP_E_INVAL. */
+int kvp_release_captured_plans(kvp_store_t *store);
 
 /* Upper bound of the workspace kvp_query_prefill needs for n_req requests with at most
  * max_tot_q query rows in total and contexts (ctx_len + n_q) of at most max_ctx rows. */

@@ -39,9 +39,16 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        # KVP_ORACLE_LIB: tests/test_oracle_mutants.py points the pins at deliberately broken
-        # copies of the oracle to show that they notice; nothing else sets it.
-        path = os.environ.get("KVP_ORACLE_LIB") or build()
+        # tests/test_oracle_mutants.py points the pins at deliberately broken copies of the oracle
+        # to show that they notice.  Another library is taken only when that test says it is the
+        # one asking (a second variable), never on a GPU machine's parity run by accident, and the
+        # substitution is announced.
+        path = None
+        if os.environ.get("KVP_ORACLE_LIB") and os.environ.get("KVP_ORACLE_LIB_FOR") == "tests/test_oracle_mutants.py":
+            path = os.environ["KVP_ORACLE_LIB"]
+            import sys
+            print("oracle: using the substituted library %s" % path, file=sys.stderr, flush=True)
+        path = path or build()
         L = ctypes.CDLL(path)
         vp, i32, i64, dbl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
         L.kvo_inv_freq.argtypes = [dbl, i32, vp]

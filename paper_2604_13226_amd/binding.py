@@ -58,6 +58,7 @@ EXPORTS = {
                                  _u32, _vp, _u64, _vp, _vp]),
     "kvp_prefill_packets": (_i32, [_vp, ctypes.POINTER(kvp_request_t), _i32, _i32, _vp, _vp, _vp, _vp, _u32,
                                    _vp, _vp, _u64, _vp, _vp]),
+    "kvp_release_captured_plans": (_i32, [_vp]),
     "kvp_prefill_workspace_bytes": (_u64, [_vp, _i32, _i32, _i32]),
     "kvp_last_error": (ctypes.c_char_p, [_vp]),
     "kvp_debug_last_plan": (_i64, [_vp, _i32, _vp, _i64]),
@@ -424,6 +425,11 @@ def kvp_prefill_packets(store, requests, layer, q, k_new, v_new, q_offsets, k_ta
                                     _stream(stream, store))
     if rc:
         _check(store.handle, rc)
+
+
+def kvp_release_captured_plans(store):
+    """Makes the plans kept for destroyed HIP graphs replaceable again; returns how many."""
+    return int(load().kvp_release_captured_plans(store.handle))
 
 
 def kvp_last_error(store):

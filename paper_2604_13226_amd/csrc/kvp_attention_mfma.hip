@@ -34,7 +34,6 @@ namespace kvp {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
@@ -171,14 +170,17 @@ __device__ __forceinline__ void rotate_chunk_pair(const uint4 &ulo, const uint4 
 
 enum { SRC_CONTIG = 0, SRC_PAGED = 1, SRC_PACKETS = 2 };
 
-// Bench builds (-DKVP_TIMING) record per-workgroup time stamps; product builds compile
-// these to nothing.
+// A micro-benchmark that includes this file with -DKVP_TIMING gets per-workgroup time stamps and
+// per-wave phase totals through two file-scope pointers it sets itself; the library is never
+// built that way, and its kernel arguments are the same in either build.
 #ifdef KVP_TIMING
-#define KVP_STAMP(slot) do { if (threadIdx.x == 0 && (slot) < 32) a.dbg[blockIdx.x * 32 + (slot)] = wall_clock64(); } while (0)
+__device__ unsigned long long *kvp_timing_stamps;  // [item][32]
+__device__ unsigned long long *kvp_timing_phases;  // [item][8 waves][8]
+#define KVP_STAMP(slot) do { if (threadIdx.x == 0 && (slot) < 32 && kvp_timing_stamps) kvp_timing_stamps[blockIdx.x * 32 + (slot)] = wall_clock64(); } while (0)
 // per-wave cycle totals of the tile loop's phases
 #define KVP_PHASE_DECL unsigned long long ph_acc[6] = {0, 0, 0, 0, 0, 0}, ph_last = __builtin_readcyclecounter()
 #define KVP_PHASE(i) do { const unsigned long long t_ = __builtin_readcyclecounter(); ph_acc[i] += t_ - ph_last; ph_last = t_; } while (0)
-#define KVP_PHASE_WRITE do { if ((threadIdx.x & 63) == 0 && a.dbg2) for (int i_ = 0; i_ < 6; ++i_) a.dbg2[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 8 + i_] = ph_acc[i_]; } while (0)
+#define KVP_PHASE_WRITE do { if ((threadIdx.x & 63) == 0 && kvp_timing_phases) for (int i_ = 0; i_ < 6; ++i_) kvp_timing_phases[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 8 + i_] = ph_acc[i_]; } while (0)
 #else
 #define KVP_STAMP(slot) do {} while (0)
 #define KVP_PHASE_DECL do {} while (0)

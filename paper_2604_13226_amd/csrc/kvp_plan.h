@@ -124,10 +124,6 @@ struct AttnArgs {
     int32_t part_stride;  // partial slots per group
     int32_t max_group_rows;  // largest n_rows among the groups that are split (the combine grid covers no more)
     float scale_log2e;  // log2(e) / sqrt(d)
-#ifdef KVP_TIMING
-    unsigned long long *dbg;  // per-item timestamps (bench builds only)
-    unsigned long long *dbg2;  // per-wave phase cycle totals (bench builds only)
-#endif
 };
 
 struct AppendArgs {

@@ -938,9 +938,13 @@ bool xcd_order(std::vector<AttnItem> &items)  // returns whether any two items s
     return true;
 }
 
-// The kept plan with this signature on this stream, or the entry to build it in: a fresh one
-// while the set may grow, else an invalid one, else the least recently used.
-kvp_store::PrefillCached &find_plan(kvp_store *s, std::deque<kvp_store::PrefillCached> &set, const std::vector<int32_t> &sig,
+// The kept plan with this signature on this stream (hit), or the entry a new plan would be built
+// in: a fresh one while the set may grow, else an invalid one, else the least recently used.
+// Nothing of the victim is changed here: the caller invalidates it only once the new plan has
+// passed every check, so a call that fails leaves the kept plans as they were.
+constexpr int MAX_CAPTURED_PLANS = 64;  // plans a HIP graph launches from, per entry point and store
+
+kvp_store::PrefillCached *find_plan(kvp_store *s, std::deque<kvp_store::PrefillCached> &set, const std::vector<int32_t> &sig,
                                     void *stream, uint64_t &sig_hash, bool &hit)
 {
     sig_hash = 1469598103934665603ull;
@@ -951,7 +955,7 @@ kvp_store::PrefillCached &find_plan(kvp_store *s, std::deque<kvp_store::PrefillC
         if (e.valid && e.sig_hash == sig_hash && e.stream == stream && e.sig == sig) {
             hit = true;
             e.last_use = ++s->pf_clock;
-            return e;
+            return &e;
         }
         if (e.captured) continue;  // a graph launches from it
         ++replaceable;
@@ -959,11 +963,30 @@ kvp_store::PrefillCached &find_plan(kvp_store *s, std::deque<kvp_store::PrefillC
     }
     hit = false;
     if (!victim || (victim->valid && replaceable < std::max(PlanRing::SLOTS, s->cfg.n_layers + 1))) {
-        set.emplace_back();
+        set.emplace_back();  // (an empty entry: nothing is lost if the call fails later)
         victim = &set.back();
     }
-    victim->last_use = ++s->pf_clock;
-    return *victim;
+    return victim;
+}
+
+int captured_plans(const std::deque<kvp_store::PrefillCached> &set)
+{
+    int n = 0;
+    for (const auto &e : set) n += e.captured ? 1 : 0;
+    return n;
+}
+
+// Block ids of the table rows a call will read, checked before anything is changed.
+int check_block_table(kvp_store *s, const kvp_cache_t *c, int n_req, const std::vector<int> &first_blk, const std::vector<int> &n_blk)
+{
+    if (c->layout != KVP_PAGED) return KVP_OK;
+    for (int r = 0; r < n_req; ++r) {
+        const int32_t *row = c->block_table + (int64_t)r * c->max_blocks_per_req;
+        for (int b = first_blk[r]; b < n_blk[r]; ++b)
+            if (row[b] < 0 || row[b] >= c->n_blocks)
+                return fail(s, KVP_E_INVAL, "block_table[%d][%d] = %d is outside [0, %d)", r, b, row[b], c->n_blocks);
+    }
+    return KVP_OK;
 }
 
 // Before an entry's plan buffer is rewritten: if launches newer than the entry's event may
@@ -1205,11 +1228,13 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
     const bool in_capture = capturing(s, hip_stream);
     if (in_capture && tot_q == 0) return KVP_OK;  // nothing to launch, and no plan to touch
-    kvp_store::PrefillCached &pf = find_plan(s, s->pf_set, sig, hip_stream, sig_hash, hit);
+    kvp_store::PrefillCached &pf = *find_plan(s, s->pf_set, sig, hip_stream, sig_hash, hit);
     const uint64_t qrb = q_rot_bytes(s, tot_q);
     if (in_capture && !hit)
         return fail(s, KVP_E_INVAL, "kvp_query_prefill under stream capture needs the plan of an earlier call with the same "
                                     "geometry on the same stream (call it once before capturing)");
+    if (in_capture && !pf.captured && captured_plans(s->pf_set) >= MAX_CAPTURED_PLANS)
+        return fail(s, KVP_E_CAPACITY, "%d plans of this store are already held for HIP graphs (kvp_release_captured_plans)", MAX_CAPTURED_PLANS);
 
     if (!hit) {
         PrefillPlan p;
@@ -1217,7 +1242,17 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         const uint64_t need = qrb + (uint64_t)p.n_slots * p.bm * (g.head_dim + 2) * sizeof(float);
         const uint64_t bytes = p.reqs.size() * sizeof(ReqMeta) + p.row_req.size() * 4 + p.groups.size() * sizeof(AttnGroup) +
                                p.items.size() * sizeof(AttnItem) + (uint64_t)n_req * bt_stride * 4 + 6 * 64;
+        // every check comes before the entry is touched: a call that fails has changed nothing
+        if (tot_q > 0) {
+            if (!s->dry && !workspace) return fail(s, KVP_E_INVAL, "workspace is null");
+            if ((uintptr_t)workspace & (ALIGN - 1)) return fail(s, KVP_E_INVAL, "workspace must be 256-byte aligned");
+            if (workspace_bytes < need)
+                return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)need);
+        }
+        rc = check_block_table(s, cache, n_req, first_blk, n_blk);
+        if (rc) return rc;
         pf.valid = false;  // the entry's buffer is rewritten below
+        pf.last_use = ++s->pf_clock;
         PlanSlot *slot = &pf.own;
         rc = settle_plan_entry(s, pf);
         if (rc) return rc;
@@ -1264,13 +1299,6 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         pf.sig = sig;
         pf.sig_hash = sig_hash;
         pf.stream = hip_stream;
-        // validated below before the upload makes the entry usable
-        if (tot_q > 0) {
-            if (!s->dry && !workspace) return fail(s, KVP_E_INVAL, "workspace is null");
-            if ((uintptr_t)workspace & (ALIGN - 1)) return fail(s, KVP_E_INVAL, "workspace must be 256-byte aligned");
-            if (workspace_bytes < need)
-                return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)need);
-        }
         if (s->dry || tot_q == 0) return KVP_OK;
         rc = upload_plan(s, slot, w.off, hip_stream);
         if (rc) return rc;
@@ -1403,10 +1431,12 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
     const bool in_capture = capturing(s, hip_stream);
     if (in_capture && tot_q == 0) return KVP_OK;  // nothing to launch, and no plan to touch
-    kvp_store::PrefillCached &pk = find_plan(s, s->pk_set, sig, hip_stream, sig_hash, hit);
+    kvp_store::PrefillCached &pk = *find_plan(s, s->pk_set, sig, hip_stream, sig_hash, hit);
     if (in_capture && !hit)
         return fail(s, KVP_E_INVAL, "kvp_prefill_packets under stream capture needs the plan of an earlier call with the same "
                                     "requests on the same stream (call it once before capturing)");
+    if (in_capture && !pk.captured && captured_plans(s->pk_set) >= MAX_CAPTURED_PLANS)
+        return fail(s, KVP_E_CAPACITY, "%d plans of this store are already held for HIP graphs (kvp_release_captured_plans)", MAX_CAPTURED_PLANS);
 
     if (!hit) {
         const int gq = g.n_q_heads / g.n_kv_heads;
@@ -1515,7 +1545,13 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         const uint64_t need = (uint64_t)n_slots * bm * (g.head_dim + 2) * sizeof(float);
         const uint64_t bytes = metas.size() * sizeof(ReqMeta) + groups.size() * sizeof(AttnGroup) +
                                items.size() * sizeof(AttnItem) + tiles.size() * sizeof(AttnTile) + 6 * 64;
+        // every check comes before the entry is touched: a call that fails has changed nothing
+        if (tot_q > 0 && workspace_bytes < need)
+            return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)need);
+        if (!s->dry && tot_q > 0 && need > 0 && (!workspace || ((uintptr_t)workspace & (ALIGN - 1))))
+            return fail(s, KVP_E_INVAL, "workspace is null or not 256-byte aligned");
         pk.valid = false;  // the entry's buffer is rewritten below
+        pk.last_use = ++s->pf_clock;
         PlanSlot *slot = &pk.own;
         int src = settle_plan_entry(s, pk);
         if (src) return src;
@@ -1557,10 +1593,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         pk.sig = sig;
         pk.sig_hash = sig_hash;
         pk.stream = hip_stream;
-        if (tot_q > 0 && workspace_bytes < need)
-            return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)need);
         if (s->dry || tot_q == 0) return KVP_OK;
-        if (need > 0 && (!workspace || ((uintptr_t)workspace & (ALIGN - 1)))) return fail(s, KVP_E_INVAL, "workspace is null or not 256-byte aligned");
         int urc = upload_plan(s, slot, w.off, hip_stream);
         if (urc) return urc;
         pk.valid = true;
@@ -1616,6 +1649,20 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         pk.slot->pending = true;
     }
     return KVP_OK;
+}
+
+int kvp_release_captured_plans(kvp_store_t *s)
+{
+    if (!s) return KVP_E_INVAL;
+    int n = 0;
+    for (auto *set : {&s->pf_set, &s->pk_set})
+        for (auto &e : *set)
+            if (e.captured) {
+                e.captured = false;
+                e.used_since_event = true;  // a replay may still be running: settled before the buffer is rewritten
+                ++n;
+            }
+    return n;
 }
 
 int64_t kvp_debug_last_plan(const kvp_store_t *s, int32_t which, int64_t *out, int64_t cap)

@@ -334,6 +334,28 @@ def test_prefill_errors():
     assert cache.ctx_len[0] == 90                             # prefill never advances ctx_len
 
 
+def test_a_prefill_call_that_fails_on_its_workspace_keeps_the_kept_plans():
+    import ctypes
+    s = dry_store(max_positions=1 << 16)
+    lib = kvp.load()
+    cache = kvp.Cache.dry(1, t_cap=20000)
+
+    def call(ctx, n_q, ws_bytes):
+        cache.ctx_len[0] = ctx
+        qo = np.array([0, n_q], np.int32)
+        return lib.kvp_query_prefill(s.handle, ctypes.byref(cache.c), 0, None, None, None, qo.ctypes.data, 1, 0,
+                                     None, ws_bytes, None, None)
+
+    # fill the set of kept plans (max(8, n_layers + 1) entries), remember the last one's plan
+    for i in range(8):
+        assert call(1000 + 64 * i, 8, 1 << 60) == 0
+    before = kvp.kvp_debug_last_plan(s, 1).copy()
+    assert call(18000, 32, 4096) == kvp.KVP_E_CAPACITY             # a new geometry, workspace far too small
+    assert "workspace" in kvp.kvp_last_error(s)
+    assert np.array_equal(kvp.kvp_debug_last_plan(s, 1), before)   # nothing was planned into the store
+    assert kvp.kvp_release_captured_plans(s) == 0                  # nothing was captured
+
+
 def test_packets_plan_tiles_and_items():
     s = dry_store(n_q_heads=32, n_kv_heads=8)
     lens = {0: 70, 1: 1, 2: 64, 3: 129}

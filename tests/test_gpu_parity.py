@@ -290,6 +290,34 @@ def test_failed_calls_change_nothing_on_device(gpu_device):
     assert bool((out == 9.0).all()) and bool((cache.k == 3.0).all())
 
 
+def test_a_failed_prefill_call_keeps_the_kept_plans(gpu_device):
+    """A call with a new geometry that fails on its workspace must not evict a kept plan: the
+    geometries run before it are still found (a hit plans nothing, so the plan the store last
+    built stays the one of the last miss)."""
+    import paper_2604_13226_amd as kvp
+    w = W.llama_k5(n_layers=1, n_packets=8)
+    store = build_store(w, kvp)
+    cache = kvp.Cache.contiguous(store, 1, 6000)
+    q = torch.zeros(4, 32, 128, dtype=torch.bfloat16, device="cuda")
+    kn = torch.zeros(4, 8, 128, dtype=torch.bfloat16, device="cuda")
+    out = torch.empty_like(q)
+    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, 1, 4, 6000))
+    geoms = [300 + 64 * i for i in range(8)]                 # as many as the store keeps (max(8, n_layers + 1))
+    for c in geoms:
+        cache.ctx_len[0] = c
+        kvp.kvp_query_prefill(store, cache, 0, q, kn, kn, [0, 4], ws, out)
+    last = kvp.kvp_debug_last_plan(store, 1).copy()
+    cache.ctx_len[0] = 5000
+    with pytest.raises(kvp.KvpError) as e:
+        kvp.kvp_query_prefill(store, cache, 0, q, kn, kn, [0, 4], kvp.alloc_workspace(256), out)
+    assert e.value.code == kvp.KVP_E_CAPACITY
+    for c in geoms:
+        cache.ctx_len[0] = c
+        kvp.kvp_query_prefill(store, cache, 0, q, kn, kn, [0, 4], ws, out)
+        assert np.array_equal(kvp.kvp_debug_last_plan(store, 1), last), c
+    torch.cuda.synchronize()
+
+
 def test_split_invariance(gpu_device):
     """The split-KV reduction is exact algebra: any number of splits gives the same result
     within tolerance, including splits that see no visible row."""
