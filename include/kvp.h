@@ -260,6 +260,32 @@ int kvp_prefill_packets(kvp_store_t *store, const kvp_request_t *reqs, int32_t n
                         uint32_t flags, void *k_tail, void *workspace, uint64_t workspace_bytes,
                         void *out, void *hip_stream);
 
+/*
+ * kvp_query_prefill for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The same computation with the same kernels, but the
+ * split-KV partial results, the generic kernel's rotated query and the call's plan live in a static
+ * device array of the library instead of a caller workspace and a library-allocated plan buffer:
+ * the call makes no hipMalloc / hipFree (nor any other allocating call), on a plan it has seen
+ * before or on a new one.  The array (32 MiB per GPU, held by every GPU the library has a store on
+ * until the process ends) gives kvp_static_workspace_bytes() = 31 MiB of workspace and 1 MiB for the
+ * plan; a call that needs more of either returns KVP_E_CAPACITY and launches nothing (the
+ * metric's 8K-context request needs 12.6 MiB; the eight 16.9K-context requests of 128 query rows
+ * together need 34 MiB and must use kvp_query_prefill).  Arguments, results and other errors as
+ * kvp_query_prefill, without `workspace`.
+ * All calls on one GPU share that GPU's array, whichever store or stream they come from, and the
+ * array keeps the last call's contents: calls are correct one after the other in stream order
+ * (each call first replaces the plan if it differs from the one the array holds, and every
+ * partial result is written before it is read; nothing needs clearing), and calls that overlap
+ * on one GPU -- on two streams, or a captured graph replayed after another call has replaced its
+ * plan -- race.  kvp_query_prefill is unaffected by it and may overlap freely.
+ */
+int kvp_query_prefill_static(kvp_store_t *store, kvp_cache_t *cache, int32_t layer, const void *q,
+                             const void *k_new, const void *v_new, const int32_t *q_offsets, int32_t n_req,
+                             uint32_t flags, void *out, void *hip_stream);
+/* Workspace bytes the static array offers a kvp_query_prefill_static call (compare with
+ * kvp_prefill_workspace_bytes). */
+uint64_t kvp_static_workspace_bytes(void);
+
 /* Stream capture keeps the plan a captured kvp_query_prefill / kvp_prefill_packets launches from
  * (at most 64 per entry point and store; a capture beyond that returns KVP_E_CAPACITY).  Once the
  * graphs that were captured on this store have been destroyed, this call makes those plans

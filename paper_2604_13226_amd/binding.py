@@ -58,6 +58,9 @@ EXPORTS = {
                                  _u32, _vp, _u64, _vp, _vp]),
     "kvp_prefill_packets": (_i32, [_vp, ctypes.POINTER(kvp_request_t), _i32, _i32, _vp, _vp, _vp, _vp, _u32,
                                    _vp, _vp, _u64, _vp, _vp]),
+    "kvp_query_prefill_static": (_i32, [_vp, ctypes.POINTER(kvp_cache_t), _i32, _vp, _vp, _vp, _vp, _i32,
+                                        _u32, _vp, _vp]),
+    "kvp_static_workspace_bytes": (_u64, []),
     "kvp_release_captured_plans": (_i32, [_vp]),
     "kvp_prefill_workspace_bytes": (_u64, [_vp, _i32, _i32, _i32]),
     "kvp_last_error": (ctypes.c_char_p, [_vp]),
@@ -405,6 +408,23 @@ def kvp_query_prefill(store, cache, layer, q, k_new, v_new, q_offsets, workspace
                                   _stream(stream, store))
     if rc:
         _check(store.handle, rc)
+
+
+def kvp_query_prefill_static(store, cache, layer, q, k_new, v_new, q_offsets, out, flags=0, stream=None):
+    """kvp_query_prefill without a workspace argument: scratch and plan live in the library's
+    static device array (the entry point that allocates nothing)."""
+    qo = np.ascontiguousarray(q_offsets, np.int32)
+    n_req = len(qo) - 1
+    _check_qkv(store, int(qo[-1]), q, k_new, v_new, out)
+    rc = load().kvp_query_prefill_static(store.handle, ctypes.byref(cache.c), int(layer), q.data_ptr(),
+                                         k_new.data_ptr(), v_new.data_ptr(), qo.ctypes.data, n_req, int(flags),
+                                         out.data_ptr(), _stream(stream, store))
+    if rc:
+        _check(store.handle, rc)
+
+
+def kvp_static_workspace_bytes():
+    return int(load().kvp_static_workspace_bytes())
 
 
 def kvp_prefill_packets(store, requests, layer, q, k_new, v_new, q_offsets, k_tail, workspace, out,

@@ -122,6 +122,15 @@ thread_local std::string g_create_error;
 
 }  // namespace
 
+// ---- scratch of the entry point that allocates nothing (kvp_query_prefill_static) ----------
+// One array per GPU, held by every GPU the library runs on until the process ends: the plan of
+// the last call in its first KVP_STATIC_PLAN_BYTES, then the workspace (rotated query, split-KV
+// partials).  In host code the array's name is only a stand-in: the device address comes from
+// hipGetSymbolAddress, once per device, and is what every launch and copy gets.
+#define KVP_STATIC_SCRATCH_BYTES (32ull << 20)
+#define KVP_STATIC_PLAN_BYTES (1ull << 20)
+static __device__ __align__(256) unsigned char scratch[KVP_STATIC_SCRATCH_BYTES];
+
 struct kvp_store {
     kvp_config_t cfg;
     std::vector<float> inv_freq;
@@ -153,12 +162,14 @@ struct kvp_store {
         int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0, part_stride = 1, max_group_rows = 0;
         bool any_split = false, mixed = false, split_in_wg = false, shared_rows = false;
         bool captured = false;  // a HIP graph launches from this plan: the entry is never replaced
+        uint64_t owner = 0;     // the static scratch's entry only: serial of the store whose plan it holds
         // Launches from a kept plan record no event (an event per layer costs a marker packet
         // between the kernels and a microsecond of host time); the entry remembers that work
         // newer than its event may still read the plan, and settles that when it is replaced.
         bool used_since_event = false;
         uint64_t need = 0;
     };
+    uint64_t serial = 0;  // distinguishes this store from any other the process has had
     std::deque<PrefillCached> pf_set;  // kvp_query_prefill
     std::deque<PrefillCached> pk_set;  // kvp_prefill_packets
     uint64_t pf_clock = 0;
@@ -191,6 +202,43 @@ struct kvp_store {
 };
 
 namespace {
+
+// Per-device state of the static scratch: its device address, a pinned staging buffer for the
+// plan and an event behind the last upload, all made at set-up (kvp_store_create), never freed.
+constexpr int MAX_DEVICES = 64;
+struct StaticScratch {
+    char *ptr = nullptr;               // device address of `scratch` on this GPU
+    kvp_store::PrefillCached entry;    // the plan the scratch holds (entry.own: staging buffer / scratch / event)
+    bool ready = false;
+};
+StaticScratch g_static[MAX_DEVICES];
+uint64_t g_store_serial = 0;
+
+// Once per device, with that device current.
+hipError_t static_scratch_setup(int device)
+{
+    if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+    StaticScratch &ss = g_static[device];
+    if (ss.ready) return hipSuccess;
+    void *p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p || ((uintptr_t)p & (ALIGN - 1))) return hipErrorInvalidSymbol;
+    PlanSlot &slot = ss.entry.own;
+    e = hipHostMalloc((void **)&slot.host, KVP_STATIC_PLAN_BYTES, hipHostMallocDefault);
+    if (e != hipSuccess) return e;
+    e = hipEventCreateWithFlags(&slot.ev, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        (void)hipHostFree(slot.host);
+        slot.host = nullptr;
+        return e;
+    }
+    slot.dev = (char *)p;
+    slot.cap = KVP_STATIC_PLAN_BYTES;
+    ss.ptr = (char *)p;
+    ss.ready = true;
+    return hipSuccess;
+}
 
 int fail(kvp_store *s, int code, const char *fmt, ...)
 {
@@ -558,6 +606,7 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
     }
     kvp_store *s = new kvp_store();
     s->cfg = *cfg;
+    s->serial = ++g_store_serial;
     s->dry = dry;
     s->ring.dry = dry;
     s->esize = cfg->dtype == KVP_BF16 ? 2 : 4;
@@ -603,6 +652,12 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
                     return fail(nullptr, KVP_E_INVAL, "arena must be device memory or pinned (device-mapped) host memory");
                 }
             }
+            e = static_scratch_setup(cfg->device);  // address of this GPU's static scratch, its staging buffer
+            if (e != hipSuccess) {
+                int rc = hip_fail(nullptr, e, "static scratch set-up");
+                delete s;
+                return rc;
+            }
             std::vector<float2> cs;
             build_cos_sin(s->inv_freq, cfg->max_positions, cs);
             e = hipMalloc((void **)&s->cs_dev, cs.size() * sizeof(float2));
@@ -627,6 +682,15 @@ int kvp_store_destroy(kvp_store_t *s)
         bool unsettled = false;  // launches from kept plans that no event of ours stands behind
         for (auto &e : s->pf_set) unsettled |= e.used_since_event;
         for (auto &e : s->pk_set) unsettled |= e.used_since_event;
+        if (s->cfg.device < MAX_DEVICES) {
+            kvp_store::PrefillCached &se = g_static[s->cfg.device].entry;
+            if (se.owner == s->serial) {  // the scratch holds a plan of this store: forget it
+                unsettled |= se.used_since_event;
+                se.used_since_event = false;
+                se.valid = false;
+                se.owner = 0;
+            }
+        }
         if (unsettled) (void)hipDeviceSynchronize();
         s->ring.release();
         for (auto &e : s->pf_set) e.own.release(false);
@@ -1170,11 +1234,17 @@ uint64_t kvp_prefill_workspace_bytes(const kvp_store_t *s, int32_t n_req, int32_
     return q_rot_bytes(s, max_tot_q) + slots * (mfma ? 2 * bm : bm) * (g.head_dim + 2) * sizeof(float) + ALIGN;
 }
 
-int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const void *q, const void *k_new,
-                      const void *v_new, const int32_t *q_offsets, int32_t n_req, uint32_t flags, void *workspace,
-                      uint64_t workspace_bytes, void *out, void *hip_stream)
+}  // extern "C"
+
+namespace {
+
+// kvp_query_prefill and kvp_query_prefill_static.  `fixed`: the static scratch's plan entry (the
+// plan then lives in the scratch, which the call neither allocates nor frees), or nullptr: the
+// plan goes into one of the store's kept entries, each with a buffer of its own.
+int query_prefill_impl(kvp_store *s, kvp_cache_t *cache, int32_t layer, const void *q, const void *k_new,
+                       const void *v_new, const int32_t *q_offsets, int32_t n_req, uint32_t flags, void *workspace,
+                       uint64_t workspace_bytes, void *out, void *hip_stream, kvp_store::PrefillCached *fixed)
 {
-    if (!s) return KVP_E_INVAL;
     const kvp_config_t &g = s->cfg;
     if (n_req < 0 || !q_offsets) return fail(s, KVP_E_INVAL, "bad request count or q_offsets is null");
     if (layer < 0 || layer >= g.n_layers) return fail(s, KVP_E_INVAL, "layer %d outside [0, %d)", layer, g.n_layers);
@@ -1228,7 +1298,15 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
     if (!s->dry) HIP_TRY(s, hipSetDevice(g.device));
     const bool in_capture = capturing(s, hip_stream);
     if (in_capture && tot_q == 0) return KVP_OK;  // nothing to launch, and no plan to touch
-    kvp_store::PrefillCached &pf = *find_plan(s, s->pf_set, sig, hip_stream, sig_hash, hit);
+    kvp_store::PrefillCached *found;
+    if (fixed) {
+        found = fixed;
+        sig_hash = 0;
+        hit = fixed->valid && fixed->owner == s->serial && fixed->stream == hip_stream && fixed->sig == sig;
+    } else {
+        found = find_plan(s, s->pf_set, sig, hip_stream, sig_hash, hit);
+    }
+    kvp_store::PrefillCached &pf = *found;
     const uint64_t qrb = q_rot_bytes(s, tot_q);
     if (in_capture && !hit)
         return fail(s, KVP_E_INVAL, "kvp_query_prefill under stream capture needs the plan of an earlier call with the same "
@@ -1247,12 +1325,18 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
             if (!s->dry && !workspace) return fail(s, KVP_E_INVAL, "workspace is null");
             if ((uintptr_t)workspace & (ALIGN - 1)) return fail(s, KVP_E_INVAL, "workspace must be 256-byte aligned");
             if (workspace_bytes < need)
-                return fail(s, KVP_E_CAPACITY, "workspace too small: %llu < %llu", (unsigned long long)workspace_bytes, (unsigned long long)need);
+                return fail(s, KVP_E_CAPACITY, fixed ? "this call needs %2$llu bytes of workspace, the static scratch holds %1$llu"
+                                                     : "workspace too small: %llu < %llu",
+                            (unsigned long long)workspace_bytes, (unsigned long long)need);
         }
         rc = check_block_table(s, cache, n_req, first_blk, n_blk);
         if (rc) return rc;
+        if (fixed && bytes > KVP_STATIC_PLAN_BYTES)
+            return fail(s, KVP_E_CAPACITY, "the plan of this call (%llu bytes) exceeds the %llu the static scratch keeps for it",
+                        (unsigned long long)bytes, (unsigned long long)KVP_STATIC_PLAN_BYTES);
         pf.valid = false;  // the entry's buffer is rewritten below
         pf.last_use = ++s->pf_clock;
+        pf.owner = s->serial;
         PlanSlot *slot = &pf.own;
         rc = settle_plan_entry(s, pf);
         if (rc) return rc;
@@ -1374,7 +1458,7 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         if (e) return hip_fail(s, (hipError_t)e, "combine launch");
     }
     if (in_capture) {
-        pf.captured = true;  // the graph reads this plan at every replay: keep it until the store goes
+        if (!fixed) pf.captured = true;  // the graph reads this plan at every replay: keep it until the store goes
     } else if (hit) {
         pf.used_since_event = true;
     } else {
@@ -1382,6 +1466,35 @@ int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const v
         pf.slot->pending = true;
     }
     return KVP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int kvp_query_prefill(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const void *q, const void *k_new,
+                      const void *v_new, const int32_t *q_offsets, int32_t n_req, uint32_t flags, void *workspace,
+                      uint64_t workspace_bytes, void *out, void *hip_stream)
+{
+    if (!s) return KVP_E_INVAL;
+    return query_prefill_impl(s, cache, layer, q, k_new, v_new, q_offsets, n_req, flags, workspace, workspace_bytes, out,
+                              hip_stream, nullptr);
+}
+
+uint64_t kvp_static_workspace_bytes(void) { return KVP_STATIC_SCRATCH_BYTES - KVP_STATIC_PLAN_BYTES; }
+
+int kvp_query_prefill_static(kvp_store_t *s, kvp_cache_t *cache, int32_t layer, const void *q, const void *k_new,
+                             const void *v_new, const int32_t *q_offsets, int32_t n_req, uint32_t flags, void *out,
+                             void *hip_stream)
+{
+    if (!s) return KVP_E_INVAL;
+    if (s->dry) return fail(s, KVP_E_INVAL, "kvp_query_prefill_static needs a store on a GPU");
+    const int dev = s->cfg.device;
+    if (dev < 0 || dev >= MAX_DEVICES || !g_static[dev].ready) return fail(s, KVP_E_HIP, "no static scratch on device %d", dev);
+    StaticScratch &ss = g_static[dev];
+    // the workspace is the scratch behind the plan: never the array's name, always its device address
+    return query_prefill_impl(s, cache, layer, q, k_new, v_new, q_offsets, n_req, flags, ss.ptr + KVP_STATIC_PLAN_BYTES,
+                              KVP_STATIC_SCRATCH_BYTES - KVP_STATIC_PLAN_BYTES, out, hip_stream, &ss.entry);
 }
 
 // -------------------------------------------------------------------------------------
