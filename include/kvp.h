@@ -251,8 +251,11 @@ int kvp_query_prefill(kvp_store_t *store, kvp_cache_t *cache, int32_t layer, con
  *            rounded exactly as kvp_query_prefill would have appended it (V_new needs no
  *            copy); the caller keeps it if decoding continues.
  * `out` equals what kvp_assemble + kvp_query_prefill give, within the attention tolerance
- * (operands are rounded to bf16 at different points).  reqs[r].base_pos must be 0.  bf16
- * stores with head_dim 128 only.  workspace as for kvp_query_prefill.
+ * (operands are rounded to bf16 at different points).  reqs[r].base_pos must be 0: rows below
+ * base_pos are rows the caller wrote into a cache, and this path has none to read them from; a
+ * prompt that precedes the documents is stored as a packet of its own and named first (it lands
+ * at Delta = 0, which rotates nothing: the same composition).  bf16 stores with head_dim 128
+ * only.  workspace as for kvp_query_prefill.
  * Errors: KVP_E_INVAL, KVP_E_NOTFOUND, KVP_E_CAPACITY.
  */
 int kvp_prefill_packets(kvp_store_t *store, const kvp_request_t *reqs, int32_t n_req, int32_t layer,

@@ -597,6 +597,46 @@ def test_prefill_packets_split_invariance(gpu_device):
         _check_packets(w, [0], outs, tails, ref)
 
 
+def test_a_prompt_prefix_is_a_first_packet_for_the_in_place_path(gpu_device):
+    """Sec. 6.2 has a task prompt ahead of the documents.  The cache path takes it as rows the
+    caller has written below base_pos; the in-place path has no cache to find such rows in and
+    takes base_pos = 0 only: there the prompt's K/V is stored as a packet of its own (no adapter
+    rows) and named first.  Both are the same composition -- the first packet sits at Delta = 0,
+    which rotates nothing -- so one oracle run (the prompt as first packet) checks both."""
+    import paper_2604_13226_amd as kvp
+    w = W.llama_k5(n_layers=2, n_packets=8)
+    w.packet_lens[w.requests[0].packet_ids[0]] = 37           # the "prompt": a short first packet
+    rq = w.requests[0]
+    prompt, docs, P = rq.packet_ids[0], rq.packet_ids[1:], 37
+    ref = oracle_workload(w)
+    layers = [0, 1]
+    # in place: the prompt is one more packet
+    outs, tails = _run_packets(w, layers)
+    _check_packets(w, layers, outs, tails, ref)
+    # cache path: the caller lays the prompt's rows into the cache and passes base_pos
+    store = build_store(w, kvp)
+    cache = make_cache(w, kvp, store)
+    pk, pv = w.packet_kv(prompt, device="cuda")
+    cache.k[0, :, :, :P], cache.v[0, :, :, :P] = pk, pv
+    kvp.kvp_assemble(store, [(docs, P)], cache)
+    ctx = int(cache.ctx_len[0])
+    assert ctx == w.ctx_len(0)
+    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, 1, rq.n_q, ctx + rq.n_q))
+    with pytest.raises(kvp.KvpError) as e:                      # the in-place path says so when asked for base_pos
+        kvp.kvp_prefill_packets(store, [(docs, P)], 0, *w.query(0, 0, "cuda"), [0, rq.n_q],
+                                torch.empty(rq.n_q, 8, 128, dtype=torch.bfloat16, device="cuda"), ws,
+                                torch.empty(rq.n_q, 32, 128, dtype=torch.bfloat16, device="cuda"))
+    assert e.value.code == kvp.KVP_E_INVAL and "base_pos" in str(e.value)
+    for layer in layers:
+        q, kn, vn = w.query(0, layer, "cuda")
+        out = torch.full_like(q, float("nan"))
+        kvp.kvp_query_prefill(store, cache, layer, q, kn, vn, [0, rq.n_q], ws, out)
+        torch.cuda.synchronize()
+        check_output(out.float().cpu().numpy().astype(np.float64), ref["out"][0][layer], w.dtype, ("prefix", layer))
+        kg, vg = (W.to_numpy(x) for x in cache.logical(0, layer, ctx + rq.n_q))
+        assert np.array_equal(kg, ref["k"][0][layer]) and np.array_equal(vg, ref["v"][0][layer])
+
+
 def _compare_sampled(w, got, ref, sample, layers):
     for r in sample:
         rows = ref["ctx"][r] + w.requests[r].n_q
@@ -725,6 +765,63 @@ def test_host_pinned_arena(gpu_device):
     assert kvp.kvp_store_arena_on_host(dev_store) == 0
 
 
+def test_host_store_assembled_layer_group_by_layer_group_under_the_prefill(gpu_device):
+    """The paper's own tier as a pipeline (Sec. 5.1: packets wait in CPU memory and are loaded on
+    retrieval; Sec. 5.2: that copy is inside the time to first token): the store is pinned host
+    memory, kvp_assemble brings one group of layers at a time over PCIe on a side stream while
+    the main stream attends to the group before it.  ready[g] orders a group's prefill behind its
+    assembly, free[g] orders the NEXT step's assembly of that group behind this step's prefill.
+    Two steps back to back with different retrieval orders, so that an assembly that overtakes
+    the previous step's prefill, or a prefill that overtakes its own assembly, changes an output."""
+    import paper_2604_13226_amd as kvp
+    wa = W.llama_k5(n_layers=4, n_packets=8)
+    wb = W.llama_k5(n_layers=4, n_packets=8)
+    wb.requests = [W.Request(list(wa.requests[0].packet_ids[::-1]), wa.requests[0].n_q)]
+    refs = [oracle_workload(wa), oracle_workload(wb)]
+    store = build_store(wa, kvp, arena="host")
+    assert kvp.kvp_store_arena_on_host(store) == 1
+    cache = make_cache(wa, kvp, store)
+    n_q, L, G = wa.requests[0].n_q, wa.n_layers, 2
+    ctx = wa.ctx_len(0)
+    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, 1, n_q, ctx + n_q))
+    qkv = [[w.query(0, layer, "cuda") for layer in range(L)] for w in (wa, wb)]
+    outs = [[torch.full_like(qkv[0][0][0], float("nan")) for _ in range(L)] for _ in range(2)]
+    side, main = torch.cuda.Stream(), torch.cuda.current_stream()
+    ready = [torch.cuda.Event() for _ in range(L // G)]
+    free = [torch.cuda.Event() for _ in range(L // G)]
+    for e in free:
+        e.record(main)
+    torch.cuda.synchronize()
+    for step, w in enumerate((wa, wb)):
+        reqs = [(w.requests[0].packet_ids, 0)]
+        for gi in range(L // G):                       # every group's assembly is queued on the side stream at once
+            side.wait_event(free[gi])
+            kvp.kvp_assemble(store, reqs, cache, gi * G, (gi + 1) * G, stream=side)
+            ready[gi].record(side)
+        for layer in range(L):
+            if layer % G == 0:
+                main.wait_event(ready[layer // G])
+            q, kn, vn = qkv[step][layer]
+            kvp.kvp_query_prefill(store, cache, layer, q, kn, vn, [0, n_q], ws, outs[step][layer], stream=main)
+            if layer % G == G - 1:
+                free[layer // G].record(main)
+        assert int(cache.ctx_len[0]) == ctx
+    torch.cuda.synchronize()
+    for step, w in enumerate((wa, wb)):
+        for layer in range(L):
+            o = outs[step][layer].float().cpu().numpy().astype(np.float64)
+            check_output(o, refs[step]["out"][0][layer], w.dtype, ("pipelined", step, layer))
+    # the cache now holds the second step's rows, query rows included, bit for bit
+    for layer in range(L):
+        kg, vg = (W.to_numpy(x) for x in cache.logical(0, layer, ctx + n_q))
+        assert np.array_equal(kg, refs[1]["k"][0][layer]), ("K", layer)
+        assert np.array_equal(vg, refs[1]["v"][0][layer]), ("V", layer)
+    # the two orders really differ (else the test would not notice a reordering)
+    assert not np.array_equal(refs[0]["k"][0][0], refs[1]["k"][0][0])
+    a, b = refs[0]["out"][0][0], refs[1]["out"][0][0]
+    assert np.sqrt(np.mean((a - b) ** 2)) > 20 * REL_RMS_TOL["bf16"] * np.sqrt(np.mean(b * b))   # far beyond check_output's relative bar
+
+
 def _compressed_case(w, seed, keep_prob, compressed_ids):
     """Per packet and layer the sorted rows a pruning pass kept (None: the packet stays whole)."""
     rng = np.random.default_rng(seed)
@@ -756,6 +853,7 @@ def test_compressed_packets_match_oracle(gpu_device, dtype, paged):
     else:
         w = W.random_small(77, dtype="f32", d=64, n_q_heads=4, n_kv_heads=2, n_layers=2, n_packets=4, k=3, n_q=5, max_len=90)
         comp = {w.requests[0].packet_ids[0], w.requests[0].packet_ids[-1]}
+        w.requests.append(W.Request(packet_ids=list(w.requests[0].packet_ids[::-1]), n_q=6, base_pos=5))
     w.paged = paged
     w.block_size = 16
     keeps = _compressed_case(w, 5, 0.55, comp)
@@ -796,6 +894,21 @@ def test_compressed_packets_match_oracle(gpu_device, dtype, paged):
     cache.with_ctx_rows(L)
     kvp.kvp_assemble(store, [(rq.packet_ids, rq.base_pos) for rq in w.requests], cache)
     assert [int(x) for x in cache.ctx_len[:n_req]] == pos_q
+    # the caller's own rows below base_pos (a prompt prefix): seeded values, laid into the cache
+    # by the test as a caller would, keys as they are (already at positions 0 .. base_pos - 1)
+    prefix = {}
+    for r, rq in enumerate(w.requests):
+        for layer in range(L):
+            if rq.base_pos:
+                pk_, pv_ = (W.normal_tensor((w.n_kv_heads, rq.base_pos, w.head_dim), 4321, 10 + i, r * 64 + layer, w.kv_scale,
+                                            w.torch_dtype, "cuda") for i in range(2))
+                prefix[r, layer] = (W.to_numpy(pk_), W.to_numpy(pv_))
+                for t in range(rq.base_pos):
+                    if paged:
+                        blk, slot = int(cache.block_table[r, t // 16]), t % 16
+                        cache.k[layer, blk, :, slot], cache.v[layer, blk, :, slot] = pk_[:, t], pv_[:, t]
+                    else:
+                        cache.k[r, layer, :, t], cache.v[r, layer, :, t] = pk_[:, t], pv_[:, t]
     q_off = np.zeros(n_req + 1, np.int32)
     for r in range(n_req):
         q_off[r + 1] = q_off[r] + w.requests[r].n_q
@@ -828,10 +941,17 @@ def test_compressed_packets_match_oracle(gpu_device, dtype, paged):
             kg, vg = W.to_numpy(kg)[:, rq.base_pos:], W.to_numpy(vg)[:, rq.base_pos:]
             assert np.array_equal(kg[:, :rows], Ko[:, :rows]), (r, layer, "K")
             assert np.array_equal(vg[:, :rows], Vo[:, :rows]), (r, layer, "V")
-            if rq.base_pos:      # the caller's rows take part in attention: keep this case assembly-only
-                continue
             qq, kn, vn = (W.to_numpy(x) for x in w.query(r, layer))
-            ref = oracle.query_prefill_at(w.dtype, qq, kn, vn, f, rows, pos_end, Ko, Vo)
+            if rq.base_pos:
+                # the caller's rows take part in attention: the oracle's layer gets them in front of
+                # the packets' rows; rows and positions are now shifted by different amounts
+                # (rows: base_pos + kept rows, positions: base_pos + spans)
+                Kf = np.concatenate([prefix[r, layer][0], Ko], axis=1)
+                Vf = np.concatenate([prefix[r, layer][1], Vo], axis=1)
+                ref = oracle.query_prefill_at(w.dtype, qq, kn, vn, f, rq.base_pos + rows, pos_end, Kf, Vf)
+                Ko, Vo = Kf[:, rq.base_pos:], Vf[:, rq.base_pos:]
+            else:
+                ref = oracle.query_prefill_at(w.dtype, qq, kn, vn, f, rows, pos_end, Ko, Vo)
             assert np.array_equal(kg[:, rows:rows + rq.n_q], Ko[:, rows:rows + rq.n_q]), (r, layer, "K_new")
             assert np.array_equal(vg[:, rows:rows + rq.n_q], Vo[:, rows:rows + rq.n_q]), (r, layer, "V_new")
             check_output(outs[layer][q_off[r]:q_off[r + 1]], ref, w.dtype, ("compressed", r, layer))
