@@ -726,41 +726,53 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
         }
     }
     if (it.part_slot >= 0) {
-        // a slot holds a.bm rows (the launch's largest row block; BM <= a.bm), then m and l of each
-        float *pp = a.partials + (int64_t)it.part_slot * a.bm * (D + 2);
-        if (KS == 1) {
-            // The split's unnormalised O rows go through LDS so that they leave as whole 512-byte
-            // rows (two per store instruction) instead of 32-byte pieces: each wave parks its
-            // 32 x 128 floats in its own 16 KiB of the (now idle) tile stages, 16-byte chunk c of
-            // row n at chunk c ^ n, and reads them back row by row.
-            wg_barrier();  // every wave is done with the tiles
-            char *reg = lds + wave * (32 * D * 4);
+        // A slot holds a.bm rows of D fp16 values (the launch's largest row block; BM <= a.bm), then
+        // m and l of each row in fp32.  A row of the split's unnormalised O goes out as fp16 scaled
+        // by a power of two 2^-e that brings its largest magnitude below 1; m + e and l 2^-e go with
+        // it, which is the same partial result relative to another reference, so the merge's
+        // algebra does not change.  Eleven significant bits relative to the row's maximum, where the
+        // bf16 output keeps eight.
+        char *pp = (char *)a.partials + (int64_t)it.part_slot * part_slot_bytes(a.bm, D, 1);
+        float amax = 0.f;
 #pragma unroll
-            for (int eb = 0; eb < 4; ++eb)
+        for (int eb = 0; eb < 4; ++eb)
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4)
-                    *(float4 *)(reg + n * (D * 4) + 16 * ((8 * eb + 2 * q4 + h) ^ n)) =
-                        make_float4(oacc[eb][4 * q4], oacc[eb][4 * q4 + 1], oacc[eb][4 * q4 + 2], oacc[eb][4 * q4 + 3]);
-            // (a wave reads only what it wrote itself: no barrier, the compiler orders the two)
-            const int c = lane & 31;
+            for (int r = 0; r < 16; ++r) amax = fmaxf(amax, __builtin_fabsf(oacc[eb][r]));
+        amax = xhalf_max(amax);
+        int e = amax > 0.f ? __builtin_amdgcn_frexp_expf(amax) : 0;  // amax = f 2^e with f in [0.5, 1)
+        e = e < -100 ? -100 : (e > 120 ? 120 : e);                   // (keeps l 2^-e and 2^-e itself in range)
+        const float sc = __builtin_ldexpf(1.f, -e);
+        typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
+        auto pack4 = [&](int eb, int q4) -> uint2 {  // four neighbouring columns of this lane's row
+            const floatx2 lo = {oacc[eb][4 * q4] * sc, oacc[eb][4 * q4 + 1] * sc};
+            const floatx2 hi = {oacc[eb][4 * q4 + 2] * sc, oacc[eb][4 * q4 + 3] * sc};
+            return make_uint2(__builtin_bit_cast(uint32_t, __builtin_convertvector(lo, halfx2)),
+                              __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, halfx2)));
+        };
+        // The rows go through LDS so that they leave as whole 256-byte rows (four per store
+        // instruction) instead of 16-byte pieces: each wave parks its 32 x 128 halves in 8 KiB of its
+        // own in the (now idle) tile stages, 8-byte chunk c of row n at chunk c ^ n, and reads them
+        // back row by row.  (KS = 2: the merge above has used the first 66 KiB; the rows go behind.)
+        if (KS == 1) wg_barrier();  // every wave is done with the tiles
+        char *reg = lds + (KS == 2 ? 68 * 1024 : 0) + wave_r * (32 * D * 2);
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int r = 2 * j + (lane >> 5);
-                const float4 f = *(const float4 *)(reg + r * (D * 4) + 16 * (c ^ r));
-                if (32 * wave_r + r < it.n_rows) *(float4 *)(pp + (int64_t)(32 * wave_r + r) * D + 4 * c) = f;
-            }
-        } else if (row_ok) {
+        for (int eb = 0; eb < 4; ++eb)
 #pragma unroll
-            for (int eb = 0; eb < 4; ++eb)
+            for (int q4 = 0; q4 < 4; ++q4) *(uint2 *)(reg + n * (D * 2) + 8 * ((8 * eb + 2 * q4 + h) ^ n)) = pack4(eb, q4);
+        // (a wave reads only what it wrote itself: no barrier, the compiler orders the two)
+        const int c = lane & 15;
 #pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    float4 f = make_float4(oacc[eb][4 * q4], oacc[eb][4 * q4 + 1], oacc[eb][4 * q4 + 2], oacc[eb][4 * q4 + 3]);
-                    *(float4 *)(pp + (int64_t)rr * D + 32 * eb + 8 * q4 + 4 * h) = f;
-                }
+        for (int j = 0; j < 8; ++j) {
+            const int r = 4 * j + (lane >> 4);
+            // logical 8-byte chunks 2c and 2c + 1 of row r sit in the 16-byte unit c ^ (r >> 1), swapped when r is odd
+            uint4 f = *(const uint4 *)(reg + r * (D * 2) + 16 * (c ^ (r >> 1)));
+            if (r & 1) f = make_uint4(f.z, f.w, f.x, f.y);
+            if (32 * wave_r + r < it.n_rows) *(uint4 *)(pp + (int64_t)(32 * wave_r + r) * (D * 2) + 16 * c) = f;
         }
         if (row_ok && h == 0) {
-            pp[a.bm * D + rr] = m_ref;
-            pp[a.bm * D + a.bm + rr] = l_i;
+            float *ml = (float *)(pp + part_rows_bytes(a.bm, D, 1));
+            ml[rr] = m_ref == -INFINITY ? -INFINITY : m_ref + (float)e;
+            ml[a.bm + rr] = l_i * sc;
         }
     }
     KVP_STAMP(31);

@@ -115,7 +115,9 @@ struct AttnArgs {
     const ReqMeta *reqs;
     const AttnGroup *groups;
     const AttnItem *items;
-    float *partials;  // [slot][bm][d + 2]: O~ rows, then m[bm], then l[bm]
+    float *partials;  // [slot]: bm O~ rows of d elements, then m[bm], then l[bm] (fp32).  The rows are fp32, or
+                      // (part_f16) fp16 scaled per row by a power of two that m and l carry along
+    int32_t part_f16;
     void *out;        // [tot_q][Hq][d]
     int32_t n_items, n_groups, layer, n_q_heads, n_kv, d, bm, g;
     int32_t split_in_wg;  // MFMA kernel, 128-row blocks: two wave groups take alternate tiles
@@ -136,6 +138,10 @@ struct AppendArgs {
     int32_t tot_q, layer, n_q_heads, n_kv, d, prerotated;
     float q_scale;  // the rotated query is multiplied by this before it is stored
 };
+
+// Bytes of one partial slot and of its block of O~ rows.
+__host__ __device__ inline int64_t part_rows_bytes(int bm, int d, int f16) { return (int64_t)bm * d * (f16 ? 2 : 4); }
+__host__ __device__ inline int64_t part_slot_bytes(int bm, int d, int f16) { return part_rows_bytes(bm, d, f16) + (int64_t)bm * 8; }
 
 // launchers (defined next to their kernels)
 int launch_assemble(int dtype, const AsmArgs &a, int n_layers_launch, void *stream);

@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256) void attention_generic_kernel(AttnArgs a)
                 if (e < d) st_elem(op + e, o[j] * inv);
             }
         } else {
-            float *pp = a.partials + (int64_t)(gp.part0 + it.split) * a.bm * (d + 2);
+            float *pp = (float *)((char *)a.partials + (int64_t)(gp.part0 + it.split) * part_slot_bytes(a.bm, d, 0));
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 int e = lane + 64 * j;
@@ -175,29 +175,58 @@ __global__ __launch_bounds__(256) void attention_generic_kernel(AttnArgs a)
 // two halves are added with one exchange.
 constexpr int COMBINE_ROWS = 4;  // rows per 256-thread workgroup
 
-template <typename T, int EARLY>  // EARLY: float4 loads per lane issued up front (2 EARLY splits of 128 columns)
+// Four neighbouring columns of a partial row: fp32 as they are, or fp16 (the MFMA kernel's rows,
+// scaled per row by a power of two that their m and l carry along) widened.
+// A piece stays as loaded (raw) until it is used: widening it right behind its load would put a
+// wait behind every load and serialise the memory round trips.
+typedef _Float16 halfx4_t __attribute__((ext_vector_type(4)));
+template <typename P> struct Part4;
+template <> struct Part4<float> { typedef float4 raw; };
+template <> struct Part4<_Float16> { typedef uint2 raw; };
+__device__ __forceinline__ float4 ld_raw4(const float *p) { return *(const float4 *)p; }
+__device__ __forceinline__ uint2 ld_raw4(const _Float16 *p) { return *(const uint2 *)p; }
+__device__ __forceinline__ float4 widen4(const float4 &v) { return v; }
+__device__ __forceinline__ float4 widen4(const uint2 &u)
+{
+    const halfx4_t v = __builtin_bit_cast(halfx4_t, u);
+    return make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
+}
+__device__ __forceinline__ void zero_raw(float4 &v) { v = make_float4(0.f, 0.f, 0.f, 0.f); }
+__device__ __forceinline__ void zero_raw(uint2 &v) { v = make_uint2(0u, 0u); }
+__device__ __forceinline__ float ld_part1(const float *p) { return *p; }
+__device__ __forceinline__ float ld_part1(const _Float16 *p) { return (float)*p; }
+
+template <typename T, typename P, int EARLY>  // EARLY: 4-column loads per lane issued up front (2 EARLY splits of 128 columns)
 __global__ __launch_bounds__(256) void combine_wave_kernel(AttnArgs a)
 {
     const int lane = threadIdx.x & 63, li = lane & 31, hf = lane >> 5;
     const int rr = (int)blockIdx.y * COMBINE_ROWS + (threadIdx.x >> 6);
     const int d = a.d, stride = a.part_stride;
-    const int64_t slot = (int64_t)a.bm * (d + 2);
+    const int64_t slot_b = part_slot_bytes(a.bm, d, sizeof(P) == 2);
+    const int64_t slot = slot_b / (int64_t)sizeof(P), slot_f = slot_b / 4;  // in row elements / in floats
     // Group gi's partial slots start at gi * stride, so the first loads below do not wait for
     // the group's record; slots and rows the group does not use hold stale bytes of the
     // workspace (in bounds) and are masked once the record has arrived.
-    const float *base = a.partials + (int64_t)blockIdx.x * stride * slot;
-    const float *ml = base + (int64_t)a.bm * d + rr;
-    const float *row = base + (int64_t)rr * d;
+    const char *base = (const char *)a.partials + (int64_t)blockIdx.x * stride * slot_b;
+    const float *ml = (const float *)(base + part_rows_bytes(a.bm, d, sizeof(P) == 2)) + rr;
+    // (loads are unconditional, from addresses clamped into the group's slots: a piece that is not
+    // needed is dropped by its weight, and no load waits for a branch to rejoin)
+    const P *row = (const P *)base + (int64_t)(rr < a.bm ? rr : a.bm - 1) * d;
     constexpr int BATCH = 8;   // later loads go out BATCH per lane at a time, all before the first is used
-    const bool early = (d & 3) == 0 && 4 * li < d && rr < a.bm;
-    float4 v0[EARLY];
+    const int col0 = (d & 3) == 0 ? (4 * li < d ? 4 * li : d - 4) : 0;
+    typename Part4<P>::raw v0[EARLY];
+    if ((d & 3) == 0) {
 #pragma unroll
-    for (int i = 0; i < EARLY; ++i) {
-        const int sq = 2 * i + hf;
-        v0[i] = early && sq < stride ? *(const float4 *)(row + sq * slot + 4 * li) : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int i = 0; i < EARLY; ++i) {
+            const int sq = 2 * i + hf;
+            v0[i] = ld_raw4(row + (sq < stride ? sq : stride - 1) * slot + col0);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < EARLY; ++i) zero_raw(v0[i]);
     }
     float mi = -INFINITY, lv = 0.f;
-    if (lane < stride && rr < a.bm) { mi = ml[lane * slot]; lv = ml[lane * slot + a.bm]; }
+    if (lane < stride && rr < a.bm) { mi = ml[lane * slot_f]; lv = ml[lane * slot_f + a.bm]; }
     const AttnGroup gp = a.groups[blockIdx.x];
     const int ns = gp.n_splits;
     if (ns <= 1 || rr >= gp.n_rows) return;
@@ -223,25 +252,28 @@ __global__ __launch_bounds__(256) void combine_wave_kernel(AttnArgs a)
                 for (int i = 0; i < EARLY; ++i) {
                     const int sq = 2 * i + hf, sp = sq < ns ? sq : ns - 1;
                     const float ws = __shfl(w, sp, 64);
-                    if (sq < ns) { acc.x += v0[i].x * ws; acc.y += v0[i].y * ws; acc.z += v0[i].z * ws; acc.w += v0[i].w * ws; }
+                    // (a split without visible rows has weight 0 and may hold anything)
+                    const float4 v = widen4(v0[i]);
+                    if (sq < ns && ws != 0.f) { acc.x += v.x * ws; acc.y += v.y * ws; acc.z += v.z * ws; acc.w += v.w * ws; }
                 }
                 s_from = 2 * EARLY;
             }
             // (a loop that loads one piece per trip waits a memory round trip per trip: with 22
             // splits its three last trips cost 2 us)
             for (int s2 = s_from; s2 < ns; s2 += 2 * BATCH) {  // same trip count in both halves
-                float4 v[BATCH];
+                typename Part4<P>::raw vr[BATCH];
 #pragma unroll
                 for (int i = 0; i < BATCH; ++i) {
                     const int sq = s2 + 2 * i + hf;
-                    v[i] = on && sq < ns ? *(const float4 *)(row + sq * slot + e) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    vr[i] = ld_raw4(row + (sq < ns ? sq : ns - 1) * slot + (on ? e : d - 4));
                 }
 #pragma unroll
                 for (int i = 0; i < BATCH; ++i) {
                     const int sq = s2 + 2 * i + hf, sp = sq < ns ? sq : ns - 1;
                     float ws = __shfl(w, sp, 64);
                     if (sq >= ns) ws = 0.f;
-                    acc.x += v[i].x * ws; acc.y += v[i].y * ws; acc.z += v[i].z * ws; acc.w += v[i].w * ws;
+                    const float4 v = widen4(vr[i]);
+                    if (ws != 0.f) { acc.x += v.x * ws; acc.y += v.y * ws; acc.z += v.z * ws; acc.w += v.w * ws; }
                 }
             }
             acc.x += __shfl_xor(acc.x, 32, 64);
@@ -262,7 +294,7 @@ __global__ __launch_bounds__(256) void combine_wave_kernel(AttnArgs a)
             float acc = 0.f;
             for (int sp = 0; sp < ns; ++sp) {
                 const float ws = __shfl(w, sp, 64);
-                if (on) acc += row[sp * slot + e] * ws;
+                if (on && ws != 0.f) acc += ld_part1(row + sp * slot + e) * ws;
             }
             if (on) st_elem(op + e, acc * inv);
         }
@@ -289,13 +321,27 @@ __device__ __forceinline__ void cv_fma(float4 &acc, const float4 &v, float w) { 
 __device__ __forceinline__ void cv_fma(float &acc, const float &v, float w) { acc += v * w; }
 __device__ __forceinline__ void cv_zero(float4 &v) { v = make_float4(0.f, 0.f, 0.f, 0.f); }
 __device__ __forceinline__ void cv_zero(float &v) { v = 0.f; }
+// raw piece types of the thread kernel: VW = 4 as above, VW = 1 a single fp32 / fp16 value
+template <typename P, int VW> struct RawVec { typedef typename Part4<P>::raw type; };
+template <> struct RawVec<float, 1> { typedef float type; };
+template <> struct RawVec<_Float16, 1> { typedef _Float16 type; };
+__device__ __forceinline__ void cv_load_raw(float4 &v, const float *p) { v = ld_raw4(p); }
+__device__ __forceinline__ void cv_load_raw(uint2 &v, const _Float16 *p) { v = ld_raw4(p); }
+__device__ __forceinline__ void cv_load_raw(float &v, const float *p) { v = *p; }
+__device__ __forceinline__ void cv_load_raw(_Float16 &v, const _Float16 *p) { v = *p; }
+__device__ __forceinline__ void zero_raw(float &v) { v = 0.f; }
+__device__ __forceinline__ void zero_raw(_Float16 &v) { v = (_Float16)0.f; }
+__device__ __forceinline__ float widen(const float &v) { return v; }
+__device__ __forceinline__ float widen(const _Float16 &v) { return (float)v; }
+__device__ __forceinline__ float4 widen(const float4 &v) { return v; }
+__device__ __forceinline__ float4 widen(const uint2 &v) { return widen4(v); }
 template <typename T> __device__ __forceinline__ void cv_store(T *p, const float4 &v, float s)
 {
     st_elem(p, v.x * s); st_elem(p + 1, v.y * s); st_elem(p + 2, v.z * s); st_elem(p + 3, v.w * s);
 }
 template <typename T> __device__ __forceinline__ void cv_store(T *p, const float &v, float s) { st_elem(p, v * s); }
 
-template <typename T, int VW>
+template <typename T, typename P, int VW>
 __global__ __launch_bounds__(256) void combine_thread_kernel(AttnArgs a)
 {
     typedef typename CombineVec<VW>::type vec_t;
@@ -306,23 +352,24 @@ __global__ __launch_bounds__(256) void combine_thread_kernel(AttnArgs a)
     const bool active = rb < rpb;      // threads beyond the block's last whole row only keep the barrier company
     const int rr = active ? (int)blockIdx.y * rpb + rb : a.bm;
     const int stride = a.part_stride;
-    const int64_t slot = (int64_t)a.bm * (d + 2);
-    const float *base = a.partials + (int64_t)blockIdx.x * stride * slot;
+    const int64_t slot_b = part_slot_bytes(a.bm, d, sizeof(P) == 2);
+    const int64_t slot = slot_b / (int64_t)sizeof(P), slot_f = slot_b / 4;  // in row elements / in floats
+    const char *base = (const char *)a.partials + (int64_t)blockIdx.x * stride * slot_b;
     const bool in_slot = rr < a.bm;
-    const float *ml = base + (int64_t)a.bm * d + rr;
-    const vec_t *row = (const vec_t *)(base + (int64_t)rr * d) + c;
-    const int64_t vslot = slot / VW;  // slot is a multiple of VW whenever d is
+    const float *ml = (const float *)(base + part_rows_bytes(a.bm, d, sizeof(P) == 2)) + rr;
+    const P *row = (const P *)base + (int64_t)rr * d + c * VW;
 
-    vec_t v0[COMBINE_EARLY];
+    typedef typename RawVec<P, VW>::type raw_t;
+    raw_t v0[COMBINE_EARLY];
 #pragma unroll
     for (int i = 0; i < COMBINE_EARLY; ++i) {
-        cv_zero(v0[i]);
-        if (in_slot && i < stride) v0[i] = row[i * vslot];
+        zero_raw(v0[i]);
+        if (in_slot && i < stride) cv_load_raw(v0[i], row + i * slot);
     }
     float *my_m = ml_lds + ((active ? rb : 0) * 2) * stride, *my_l = my_m + stride;
     for (int sp = c; active && sp < stride; sp += cpr) {
-        my_m[sp] = in_slot ? ml[sp * slot] : -INFINITY;
-        my_l[sp] = in_slot ? ml[sp * slot + a.bm] : 0.f;
+        my_m[sp] = in_slot ? ml[sp * slot_f] : -INFINITY;
+        my_l[sp] = in_slot ? ml[sp * slot_f + a.bm] : 0.f;
     }
     const AttnGroup gp = a.groups[blockIdx.x];
     __syncthreads();
@@ -339,20 +386,41 @@ __global__ __launch_bounds__(256) void combine_thread_kernel(AttnArgs a)
             const float mi = my_m[i];
             const float w = mi == -INFINITY ? 0.f : exp2f(mi - mx);
             lsum += my_l[i] * w;
-            if (w != 0.f) cv_fma(acc, v0[i], w);  // a split without visible rows may hold anything
+            if (w != 0.f) cv_fma(acc, widen(v0[i]), w);  // a split without visible rows may hold anything
         }
 #pragma unroll 4
     for (int sp = COMBINE_EARLY; sp < ns; ++sp) {
         const float mi = my_m[sp];
         const float w = mi == -INFINITY ? 0.f : exp2f(mi - mx);
         lsum += my_l[sp] * w;
-        const vec_t v = row[sp * vslot];
-        if (w != 0.f) cv_fma(acc, v, w);
+        raw_t v;
+        cv_load_raw(v, row + sp * slot);
+        if (w != 0.f) cv_fma(acc, widen(v), w);
     }
     const int m = gp.m0 + rr;
     const int t = m / a.g, hq = gp.kv_head * a.g + m % a.g;
     T *op = (T *)a.out + ((int64_t)(gp.q_off + t) * a.n_q_heads + hq) * d + c * VW;
     cv_store(op, acc, 1.f / lsum);
+}
+
+template <typename T, typename P> static void launch_combine_typed(const AttnArgs &a, int rows, hipStream_t st)
+{
+    if (a.part_stride > COMBINE_EARLY) {  // many splits: a wavefront per row, its lanes over the splits
+        dim3 grid((unsigned)a.n_groups, (unsigned)((rows + COMBINE_ROWS - 1) / COMBINE_ROWS));
+        // up to 16 splits: 8 early loads per lane cover them; more: 12, so that the 19-24 splits of
+        // a single 8K request still take one memory round trip (measured per layer: 8K 22.5 -> 22.0 us,
+        // one decode step over it 17.5 -> 16.9; with 12 splits the larger kernel is 0.2 us slower)
+        if (a.part_stride <= 16) hipLaunchKernelGGL((combine_wave_kernel<T, P, 8>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((combine_wave_kernel<T, P, 12>), grid, dim3(256), 0, st, a);
+        return;
+    }
+    const int vw = a.d % 4 == 0 ? 4 : 1;
+    const int cpr = a.d / vw;
+    const int rpb = combine_rows_per_block(cpr);
+    dim3 grid((unsigned)a.n_groups, (unsigned)((rows + rpb - 1) / rpb));
+    const size_t lds = (size_t)rpb * 2 * a.part_stride * sizeof(float);
+    if (vw == 4) hipLaunchKernelGGL((combine_thread_kernel<T, P, 4>), grid, dim3(256), lds, st, a);
+    else hipLaunchKernelGGL((combine_thread_kernel<T, P, 1>), grid, dim3(256), lds, st, a);
 }
 
 int launch_combine(int dtype, const AttnArgs &a, void *stream)
@@ -361,32 +429,15 @@ int launch_combine(int dtype, const AttnArgs &a, void *stream)
     const int rows = a.max_group_rows > 0 && a.max_group_rows < a.bm ? a.max_group_rows : a.bm;
     hipStream_t st = (hipStream_t)stream;
     if (a.part_stride > COMBINE_MAX_SPLITS) return (int)hipErrorInvalidValue;
-    if (a.part_stride > COMBINE_EARLY) {  // many splits: a wavefront per row, its lanes over the splits
-        dim3 grid((unsigned)a.n_groups, (unsigned)((rows + COMBINE_ROWS - 1) / COMBINE_ROWS));
-        // up to 16 splits: 8 early loads per lane cover them; more: 12, so that the 19-24 splits of
-        // a single 8K request still take one memory round trip (measured per layer: 8K 22.5 -> 22.0 us,
-        // one decode step over it 17.5 -> 16.9; with 12 splits the larger kernel is 0.2 us slower)
-        if (a.part_stride <= 16) {
-            if (dtype == 1) hipLaunchKernelGGL((combine_wave_kernel<bf16_t, 8>), grid, dim3(256), 0, st, a);
-            else hipLaunchKernelGGL((combine_wave_kernel<float, 8>), grid, dim3(256), 0, st, a);
-        } else {
-            if (dtype == 1) hipLaunchKernelGGL((combine_wave_kernel<bf16_t, 12>), grid, dim3(256), 0, st, a);
-            else hipLaunchKernelGGL((combine_wave_kernel<float, 12>), grid, dim3(256), 0, st, a);
-        }
-        return (int)hipGetLastError();
-    }
-    const int vw = a.d % 4 == 0 ? 4 : 1;
-    const int cpr = a.d / vw;
+    const int cpr = a.d / (a.d % 4 == 0 ? 4 : 1);
     if (cpr < 1 || cpr > 256) return (int)hipErrorInvalidValue;
-    const int rpb = combine_rows_per_block(cpr);
-    dim3 grid((unsigned)a.n_groups, (unsigned)((rows + rpb - 1) / rpb));
-    const size_t lds = (size_t)rpb * 2 * a.part_stride * sizeof(float);
-    if (dtype == 1) {
-        if (vw == 4) hipLaunchKernelGGL((combine_thread_kernel<bf16_t, 4>), grid, dim3(256), lds, st, a);
-        else hipLaunchKernelGGL((combine_thread_kernel<bf16_t, 1>), grid, dim3(256), lds, st, a);
+    if (a.part_f16) {  // the MFMA kernel's partial rows (bf16 stores only)
+        if (dtype != 1 || (a.d & 3)) return (int)hipErrorInvalidValue;
+        launch_combine_typed<bf16_t, _Float16>(a, rows, st);
+    } else if (dtype == 1) {
+        launch_combine_typed<bf16_t, float>(a, rows, st);
     } else {
-        if (vw == 4) hipLaunchKernelGGL((combine_thread_kernel<float, 4>), grid, dim3(256), lds, st, a);
-        else hipLaunchKernelGGL((combine_thread_kernel<float, 1>), grid, dim3(256), lds, st, a);
+        launch_combine_typed<float, float>(a, rows, st);
     }
     return (int)hipGetLastError();
 }

@@ -1436,6 +1436,7 @@ int query_prefill_impl(kvp_store *s, kvp_cache_t *cache, int32_t layer, const vo
     at.groups = pf.groups_dev;
     at.items = pf.items_dev;
     at.partials = (float *)((char *)workspace + qrb);
+    at.part_f16 = pf.kind == ATTN_MFMA ? 1 : 0;
     at.out = out;
     at.n_items = pf.n_items;
     at.n_groups = pf.n_groups;
@@ -1732,6 +1733,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     at.groups = pk.groups_dev;
     at.items = pk.items_dev;
     at.partials = (float *)workspace;
+    at.part_f16 = 1;
     at.out = out;
     at.n_items = pk.n_items;
     at.n_groups = pk.n_groups;
