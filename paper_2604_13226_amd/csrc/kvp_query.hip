@@ -410,8 +410,11 @@ template <typename T, typename P> static void launch_combine_typed(const AttnArg
         // up to 16 splits: 8 early loads per lane cover them; more: 12, so that the 19-24 splits of
         // a single 8K request still take one memory round trip (measured per layer: 8K 22.5 -> 22.0 us,
         // one decode step over it 17.5 -> 16.9; with 12 splits the larger kernel is 0.2 us slower)
+        // (... and 16 / 20 for up to 32 / 40 splits: a second round trip costs 2 us)
         if (a.part_stride <= 16) hipLaunchKernelGGL((combine_wave_kernel<T, P, 8>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((combine_wave_kernel<T, P, 12>), grid, dim3(256), 0, st, a);
+        else if (a.part_stride <= 24) hipLaunchKernelGGL((combine_wave_kernel<T, P, 12>), grid, dim3(256), 0, st, a);
+        else if (a.part_stride <= 32) hipLaunchKernelGGL((combine_wave_kernel<T, P, 16>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((combine_wave_kernel<T, P, 20>), grid, dim3(256), 0, st, a);
         return;
     }
     const int vw = a.d % 4 == 0 ? 4 : 1;

@@ -1214,6 +1214,46 @@ def test_repeated_calls_reuse_the_plan_and_give_the_same_bits(gpu_device):
         assert np.array_equal(o, outs[0])
 
 
+def test_a_gather_plan_kept_on_the_device_serves_the_same_call_again_and_no_other(gpu_device):
+    """A paged assembly uploads its plan (segments, tile map, block table); the same call again
+    launches from the kept copy, a call with another block table or other requests does not.
+    Every pass is checked bit for bit against the oracle after the caches were overwritten, on
+    more calls than the library keeps plans for."""
+    import paper_2604_13226_amd as kvp
+    w = W.serving_mix(n_layers=1, n_packets=64, n_req=5)
+    ref = oracle_workload(w)
+    store = build_store(w, kvp)
+    reqs = [(rq.packet_ids, rq.base_pos) for rq in w.requests]
+
+    def check(cache, ref_, n_req):
+        torch.cuda.synchronize()
+        for r in range(n_req):
+            k, v = cache.logical(r, 0, ref_["ctx"][r])
+            assert np.array_equal(W.to_numpy(k), ref_["k"][r][0][:, :ref_["ctx"][r]]), r
+            assert np.array_equal(W.to_numpy(v), ref_["v"][r][0][:, :ref_["ctx"][r]]), r
+
+    c1 = make_cache(w, kvp, store, block_order="random")
+    c2 = make_cache(w, kvp, store, block_order="sequential")     # same shapes, another block table
+    for rep in range(3):
+        for c in (c1, c2, c1):
+            c.k.fill_(7.0), c.v.fill_(7.0)
+            kvp.kvp_assemble(store, reqs, c)
+            check(c, ref, len(reqs))
+    # other requests on the same cache: fewer, in another order
+    w2 = W.serving_mix(n_layers=1, n_packets=64, n_req=5)
+    w2.requests = [w.requests[3], w.requests[0]]
+    ref2 = oracle_workload(w2)
+    c3 = make_cache(w2, kvp, store)
+    for rep in range(12):                                        # more rewrites than there are kept plans
+        c3.k.fill_(float(rep)), c3.v.fill_(float(rep))
+        kvp.kvp_assemble(store, [(rq.packet_ids, rq.base_pos) for rq in w2.requests], c3)
+        check(c3, ref2, 2)
+        if rep % 4 == 0:
+            c1.k.fill_(9.0), c1.v.fill_(9.0)
+            kvp.kvp_assemble(store, reqs, c1)
+            check(c1, ref, len(reqs))
+
+
 def test_empty_batches_touch_nothing(gpu_device):
     """No requests, or requests without packets and without query rows: the calls succeed, launch
     nothing and leave the cache, the output and ctx_len of other requests alone."""
