@@ -305,8 +305,10 @@ uint64_t kvp_prefill_workspace_bytes(const kvp_store_t *store, int32_t n_req,
 const char *kvp_last_error(const kvp_store_t *store);
 
 /* Host-logic introspection (tests): copies up to cap int64 words describing the plan of
- * the last kvp_assemble (which == 0) or kvp_query_prefill (which == 1) and returns the
- * number of words the full description has.  Layout: see kvp_plan.h in the sources. */
+ * the last kvp_assemble (which == 0) or kvp_query_prefill / kvp_prefill_packets (which == 1) and
+ * returns the number of words the full description has.  Layout: see kvp_plan.h in the sources.
+ * which == 2: one word, the number of work items of that prefill plan that the workgroups
+ * rebuild from their index (regular launches for one request), 0 if they read them from memory. */
 int64_t kvp_debug_last_plan(const kvp_store_t *store, int32_t which, int64_t *out,
                             int64_t cap);
 

@@ -217,7 +217,7 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
     static_assert(STAGES % KS == 0 && PR >= 1, "stages");
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     KVP_STAMP(0);
-    const AttnItem it = a.items[blockIdx.x];
+    const AttnItem it = a.inl.n ? attn_inline_item(a.inl, blockIdx.x, a.n_kv, a.part_stride) : a.items[blockIdx.x];
     if (it.n_rows <= 0) return;  // padding item of the launch order
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -791,7 +791,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
 template <int SRC>
 __global__ __launch_bounds__(512, 2) void attention_mfma_mixed_kernel(AttnArgs a)
 {
-    if (a.items[blockIdx.x].half_block) attention_body<4, SRC, 8, 2>(a);
+    const bool half = a.inl.n ? false : a.items[blockIdx.x].half_block != 0;  // (regular launches have no half blocks)
+    if (half) attention_body<4, SRC, 8, 2>(a);
     else attention_body<4, SRC, 8, 1>(a);
 }
 

@@ -100,6 +100,51 @@ struct AttnTile {
 };
 static_assert(sizeof(AttnTile) == 32, "AttnTile is 32 bytes");
 
+// The work items of a launch for ONE request whose packed rows fit one row block are a regular
+// pattern -- kv head h, split sp, all splits the same length but the last -- in a known launch
+// order (the full splits of every head, head by head, then the heads' shorter last splits).  A
+// workgroup of such a launch rebuilds its AttnItem from its index with scalar arithmetic and
+// starts its query and tile loads one memory round trip earlier than one that first has to fetch
+// its item.  The host fills this only after it has rebuilt every planned item with the same
+// function and found it equal, field by field.  (A table of items in the kernel arguments was
+// measured too: kernel arguments of 2 KB cost more per launch than the fetch they saved.)
+struct AttnInline {
+    int32_t n;                   // items of the launch (0: the items are read from memory)
+    int32_t ctx_len, pos0, n_q;  // the request
+    int32_t split_len;           // kv rows (in-place path: tiles) per split
+    int32_t vis;                 // end of the kv range the rows may see
+    int32_t ns, n_front;         // splits per head; how many of them come in the front part of the launch order
+    int32_t n_rows;              // packed rows (n_q x heads per kv head)
+};
+
+__host__ __device__ inline AttnItem attn_inline_item(const AttnInline &t, int i, int n_kv, int part_stride)
+{
+    AttnItem it{};
+    int h, sp;
+    if (i < n_kv * t.n_front) {
+        h = i / t.n_front;
+        sp = i - h * t.n_front;
+    } else {  // (n_front = ns - 1: the last splits follow, one per head)
+        h = i - n_kv * t.n_front;
+        sp = t.ns - 1;
+    }
+    it.group = h;
+    it.split = sp;
+    it.kv_begin = sp * t.split_len;
+    it.kv_end = (sp + 1) * t.split_len < t.vis ? (sp + 1) * t.split_len : t.vis;
+    it.req = 0;
+    it.kv_head = h;
+    it.m0 = 0;
+    it.n_rows = t.n_rows;
+    it.ctx_len = t.ctx_len;
+    it.q_off = 0;
+    it.part_slot = t.ns > 1 ? h * part_stride + sp : -1;
+    it.n_q = t.n_q;
+    it.pos0 = t.pos0;
+    it.half_block = 0;
+    return it;
+}
+
 struct AttnArgs {
     const void *q_rot;  // [tot_q][Hq][d], store dtype, rotated (generic kernel)
     // the MFMA kernel rotates the query and appends K_new / V_new itself:
@@ -126,7 +171,9 @@ struct AttnArgs {
     int32_t part_stride;  // partial slots per group
     int32_t max_group_rows;  // largest n_rows among the groups that are split (the combine grid covers no more)
     float scale_log2e;  // log2(e) / sqrt(d)
+    AttnInline inl;     // MFMA kernel: the items as a formula (inl.n > 0), when the launch is that regular
 };
+static_assert(sizeof(AttnArgs) <= 4096, "kernel arguments are limited to 4 KB");
 
 struct AppendArgs {
     const void *q, *k_new, *v_new;

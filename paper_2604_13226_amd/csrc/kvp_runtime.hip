@@ -200,6 +200,7 @@ struct kvp_store {
         const AttnTile *tiles_dev = nullptr;
         int kind = 0, bm = 0, n_items = 0, n_groups = 0, bt_stride = 0, tot_q = 0, part_stride = 1, max_group_rows = 0;
         bool any_split = false, mixed = false, split_in_wg = false, shared_rows = false;
+        AttnInline inl{};       // the items as kernel arguments (inl.n = 0: not applicable)
         bool captured = false;  // a HIP graph launches from this plan: the entry is never replaced
         uint64_t owner = 0;     // the static scratch's entry only: serial of the store whose plan it holds
         // Launches from a kept plan record no event (an event per layer costs a marker packet
@@ -224,6 +225,7 @@ struct kvp_store {
         std::vector<AttnItem> items;
         std::vector<AttnTile> tiles;
         bool has_tiles = false;
+        int64_t inl_n = 0;  // items that ride in the kernel arguments (0: none)
     } dbg_plan;
     bool dry = false;
     int n_cu = 256;
@@ -236,6 +238,7 @@ struct kvp_store {
     int nt_loads = -1;  // test knob (KVP_ATTN_NT_LOADS=0/1): streaming hint on the attention kernel's tile loads
     int mixed_blocks = 1;  // test knob (KVP_ATTN_MIXED=0): no half blocks in launches of 256-row blocks
     int plan_copy_engine = 0;  // test knob: plans go up with hipMemcpyAsync instead of the upload kernel
+    int inline_items = 1;  // test knob (KVP_ATTN_INLINE_ITEMS=0): work items are always read from memory
     int force_bm = 0;  // test knob: row-block size of the MFMA attention kernel
     int force_split_in_wg = -1;  // test knob: 0 / 1 forces the 4-wave / 8-wave-in-two-groups shape of 128-row blocks
     size_t esize = 2;
@@ -690,6 +693,7 @@ int kvp_store_create(const kvp_config_t *cfg, kvp_store_t **out)
     if (const char *mb = getenv("KVP_ATTN_MIXED")) s->mixed_blocks = mb[0] != '0';
     if (const char *nl = getenv("KVP_ATTN_NT_LOADS")) s->nt_loads = nl[0] != '0';
     if (const char *fb = getenv("KVP_ATTN_BM")) s->force_bm = atoi(fb);
+    if (const char *ii = getenv("KVP_ATTN_INLINE_ITEMS")) s->inline_items = ii[0] != '0';
     if (const char *fd = getenv("KVP_ATTN_SPLIT_IN_WG")) s->force_split_in_wg = atoi(fd) != 0;
     const char *ti = getenv("KVP_ATTN_TARGET_ITEMS");  // test knob: how finely split-KV cuts
     if (ti && atoi(ti) > 0) s->target_items = std::min(atoi(ti), 1 << 16);
@@ -1146,6 +1150,7 @@ struct PrefillPlan {
     bool split_in_wg = false;  // MFMA kernel, 128-row blocks: 8 waves in two groups on alternate tiles
     bool shared_rows = false;  // some work items read the same K/V rows (several row blocks per request and head),
                                // or the launch is short: either way no streaming hint on the tile loads
+    int split_len0 = 0;        // kv rows per split of request 0
 };
 
 constexpr int MFMA_BM = 128;
@@ -1223,6 +1228,7 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
         split_len = std::max(split_len, min_split);
         split_len = (split_len + p.bn - 1) / p.bn * p.bn;
         split_len = std::min(split_len, max_split);
+        if (r == 0) p.split_len0 = split_len;
         const int M = rq.n_q * gq;
         for (int h = 0; h < g.n_kv_heads; ++h)
             for (int m0 = 0; m0 < M; m0 += p.bm) {
@@ -1269,6 +1275,45 @@ void plan_prefill(const kvp_store *s, const kvp_cache_t *cache, int n_req, const
     }
     assign_part_slots(p.groups, p.items, p.any_split ? p.part_stride : 0, p.n_slots);
     p.shared_rows = xcd_order(p.items) || tiles < 16 * (int64_t)s->n_cu;  // (short launches: the hint measured slower)
+}
+
+// The items of a one-request MFMA launch as a formula in the kernel arguments (AttnInline), if
+// the launch is that regular: rebuilding every item with the kernel's own function must give
+// exactly the planned item; else t.n = 0.
+void fill_inline_items(const kvp_store *s, int n_req, const ReqMeta *reqs, const std::vector<AttnGroup> &groups,
+                       const std::vector<AttnItem> &items, int bm, int part_stride, int split_len, int gq, AttnInline &t)
+{
+    t.n = 0;
+    const int n_kv = s->cfg.n_kv_heads;
+    if (!s->inline_items || n_req != 1 || (int)groups.size() != n_kv || items.empty() || split_len <= 0 || reqs[0].q_off != 0 ||
+        reqs[0].n_q * gq > bm)
+        return;
+    t.ctx_len = reqs[0].ctx_len;
+    t.pos0 = reqs[0].pos0;
+    t.n_q = reqs[0].n_q;
+    t.n_rows = reqs[0].n_q * gq;
+    t.split_len = split_len;
+    t.ns = groups[0].n_splits;
+    t.vis = 0;
+    for (const AttnItem &it : items) t.vis = std::max(t.vis, it.kv_end);
+    if ((int64_t)n_kv * t.ns != (int64_t)items.size()) return;
+    for (int n_front : {t.ns, t.ns - 1}) {  // the last splits in place, or behind all the others
+        if (n_front < 1 && t.ns > 1) continue;
+        t.n_front = n_front;
+        bool same = true;
+        for (size_t i = 0; i < items.size() && same; ++i) {
+            const AttnItem &want = items[i];
+            const AttnItem got = attn_inline_item(t, (int)i, n_kv, part_stride);
+            same = got.group == want.group && got.split == want.split && got.kv_begin == want.kv_begin && got.kv_end == want.kv_end &&
+                   got.req == want.req && got.kv_head == want.kv_head && got.m0 == want.m0 && got.n_rows == want.n_rows &&
+                   got.ctx_len == want.ctx_len && got.q_off == want.q_off && got.part_slot == want.part_slot && got.n_q == want.n_q &&
+                   got.pos0 == want.pos0 && got.half_block == want.half_block;
+        }
+        if (same) {
+            t.n = (int32_t)items.size();
+            return;
+        }
+    }
 }
 
 uint64_t q_rot_bytes(const kvp_store *s, int64_t tot_q)
@@ -1394,6 +1439,11 @@ int query_prefill_impl(kvp_store *s, kvp_cache_t *cache, int32_t layer, const vo
         }
         rc = check_block_table(s, cache, n_req, first_blk, n_blk);
         if (rc) return rc;
+        AttnInline inl;
+        inl.n = 0;
+        if (p.kind == ATTN_MFMA)
+            fill_inline_items(s, n_req, p.reqs.data(), p.groups, p.items, p.bm, p.part_stride, p.split_len0,
+                              g.n_q_heads / g.n_kv_heads, inl);
         if (fixed && bytes > KVP_STATIC_PLAN_BYTES)
             return fail(s, KVP_E_CAPACITY, "the plan of this call (%llu bytes) exceeds the %llu the static scratch keeps for it",
                         (unsigned long long)bytes, (unsigned long long)KVP_STATIC_PLAN_BYTES);
@@ -1428,6 +1478,7 @@ int query_prefill_impl(kvp_store *s, kvp_cache_t *cache, int32_t layer, const vo
             dp.items.swap(p.items);
             dp.tiles.clear();
             dp.has_tiles = false;
+            dp.inl_n = inl.n;
         }
         pf.slot = slot;
         pf.kind = p.kind;
@@ -1446,6 +1497,8 @@ int query_prefill_impl(kvp_store *s, kvp_cache_t *cache, int32_t layer, const vo
         pf.sig = sig;
         pf.sig_hash = sig_hash;
         pf.stream = hip_stream;
+        pf.inl.n = inl.n;
+        if (inl.n) pf.inl = inl;
         if (s->dry || tot_q == 0) return KVP_OK;
         rc = upload_plan(s, slot, w.off, hip_stream);
         if (rc) return rc;
@@ -1515,6 +1568,8 @@ int query_prefill_impl(kvp_store *s, kvp_cache_t *cache, int32_t layer, const vo
     at.max_group_rows = pf.max_group_rows;
     at.g = g.n_q_heads / g.n_kv_heads;
     at.scale_log2e = (float)(1.4426950408889634 / sqrt((double)g.head_dim));
+    at.inl.n = pf.inl.n;
+    if (pf.inl.n) at.inl = pf.inl;
     e = launch_attention(g.dtype, at, pf.kind, hip_stream);
     if (e) return hip_fail(s, (hipError_t)e, "attention launch");
     if (pf.any_split) {
@@ -1719,6 +1774,12 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         }
         assign_part_slots(groups, items, any_split ? part_stride : 0, n_slots);
         const bool shared_rows = xcd_order(items) || n_tiles_total < 16 * (int64_t)s->n_cu;  // (short launches: the hint measured slower)
+        AttnInline inl;
+        inl.n = 0;
+        if (n_req == 1 && metas[0].n_q > 0) {
+            const int n_t0 = n_pkt_tiles[0] + (metas[0].n_q + 63) / 64;
+            fill_inline_items(s, n_req, metas.data(), groups, items, bm, part_stride, std::max(4, (n_t0 + want - 1) / want), gq, inl);
+        }
         const uint64_t need = (uint64_t)n_slots * bm * (g.head_dim + 2) * sizeof(float);
         const uint64_t bytes = metas.size() * sizeof(ReqMeta) + groups.size() * sizeof(AttnGroup) +
                                items.size() * sizeof(AttnItem) + tiles.size() * sizeof(AttnTile) + 6 * 64;
@@ -1753,6 +1814,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
             dp.items.swap(items);
             dp.tiles.swap(tiles);
             dp.has_tiles = true;
+            dp.inl_n = inl.n;
         }
         pk.slot = slot;
         pk.kind = ATTN_MFMA;
@@ -1770,6 +1832,8 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         pk.sig = sig;
         pk.sig_hash = sig_hash;
         pk.stream = hip_stream;
+        pk.inl.n = inl.n;
+        if (inl.n) pk.inl = inl;
         if (s->dry || tot_q == 0) return KVP_OK;
         int urc = upload_plan(s, slot, w.off, hip_stream);
         if (urc) return urc;
@@ -1812,6 +1876,8 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
     at.max_group_rows = pk.max_group_rows;
     at.g = g.n_q_heads / g.n_kv_heads;
     at.scale_log2e = (float)(1.4426950408889634 / sqrt((double)g.head_dim));
+    at.inl.n = pk.inl.n;
+    if (pk.inl.n) at.inl = pk.inl;
     int e = launch_attention(g.dtype, at, ATTN_MFMA, hip_stream);
     if (e) return hip_fail(s, (hipError_t)e, "attention launch");
     if (pk.any_split) {
@@ -1859,7 +1925,9 @@ int64_t kvp_debug_last_plan(const kvp_store_t *s, int32_t which, int64_t *out, i
                 ++tiles[0];
             }
     }
-    if (which != 0) {
+    if (which == 2) {  // how many of the last prefill plan's items ride in the kernel arguments
+        tiles.push_back(s->dbg_plan.inl_n);
+    } else if (which != 0) {
         // the last prefill plan: head, then groups (6 numbers each), items (4 each) and, for the
         // in-place path, the tile count and the tiles (6 each)
         const kvp_store::DebugPlan &dp = s->dbg_plan;

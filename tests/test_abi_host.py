@@ -356,6 +356,31 @@ def test_a_prefill_call_that_fails_on_its_workspace_keeps_the_kept_plans():
     assert kvp.kvp_release_captured_plans(s) == 0                  # nothing was captured
 
 
+def test_regular_one_request_plans_are_rebuilt_from_the_block_index():
+    """A launch for one request whose packed rows fit one row block has a regular item pattern;
+    its workgroups rebuild their items from their index, and the host only lets them after
+    rebuilding every planned item with the same function.  Batches, several row blocks per head
+    and the generic kernel keep reading their items from memory."""
+    s = dry_store(n_q_heads=32, n_kv_heads=8, max_positions=1 << 17)
+    for ctx, n_q, regular in [(8192, 32, True), (3000, 32, True), (8192, 1, True), (0, 20, True), (511, 30, True),
+                              (100000, 7, True), (8192 - 32, 32, True), (6720, 100, False), (100000, 200, False)]:
+        cache = kvp.Cache.dry(1, t_cap=ctx + n_q)
+        cache.ctx_len[0] = ctx
+        kvp.kvp_query_prefill(s, cache, 0, None, None, None, np.array([0, n_q], np.int32), None, None)
+        kind, bm, groups, items, slots, need = _attn_plan(s)
+        assert kind == 1
+        assert int(kvp.kvp_debug_last_plan(s, 2)[0]) == (len(items) if regular else 0), (ctx, n_q)
+    cache = kvp.Cache.dry(2, t_cap=5000)
+    cache.ctx_len[:2] = [4000, 3000]
+    kvp.kvp_query_prefill(s, cache, 0, None, None, None, np.array([0, 32, 64], np.int32), None, None)
+    assert int(kvp.kvp_debug_last_plan(s, 2)[0]) == 0                       # two requests
+    f32 = dry_store(head_dim=64, dtype="f32")
+    cache = kvp.Cache.dry(1, t_cap=600)
+    cache.ctx_len[0] = 500
+    kvp.kvp_query_prefill(f32, cache, 0, None, None, None, np.array([0, 5], np.int32), None, None)
+    assert int(kvp.kvp_debug_last_plan(f32, 2)[0]) == 0                     # the generic kernel reads its items from memory
+
+
 def test_packets_plan_tiles_and_items():
     s = dry_store(n_q_heads=32, n_kv_heads=8)
     lens = {0: 70, 1: 1, 2: 64, 3: 129}

@@ -1254,6 +1254,34 @@ def test_a_gather_plan_kept_on_the_device_serves_the_same_call_again_and_no_othe
             check(c1, ref, len(reqs))
 
 
+@pytest.mark.parametrize("mk", [
+    lambda: W.llama_k5(n_layers=1, n_packets=8),
+    lambda: W.llama_8k(n_layers=1, n_packets=16),
+    lambda: W.llama_8k(n_layers=1, n_packets=16, n_q=1),
+])
+def test_items_rebuilt_from_the_block_index_give_the_same_bits_as_items_read_from_memory(gpu_device, mk):
+    """The workgroups of a regular one-request launch rebuild their work items from their index;
+    with that switched off (KVP_ATTN_INLINE_ITEMS=0) the same items are read from memory.  Same
+    items, same arithmetic: the outputs and the appended rows agree bit for bit, on both attention
+    paths."""
+    import paper_2604_13226_amd as kvp
+    w = mk()
+    res = {}
+    for inline in ("1", "0"):
+        os.environ["KVP_ATTN_INLINE_ITEMS"] = inline
+        try:
+            got = run_workload(w)
+            n_inl = int(kvp.kvp_debug_last_plan(got["store"], 2)[0])
+            assert (n_inl > 0) == (inline == "1")
+            outs, tails = _run_packets(w, [0])
+        finally:
+            del os.environ["KVP_ATTN_INLINE_ITEMS"]
+        res[inline] = (got["out"][0][0], got["k"][0][0], outs[0][0], tails[0][0])
+    for a, b in zip(res["1"], res["0"]):
+        assert np.array_equal(a, b)
+    compare(w, got, oracle_workload(w))
+
+
 def test_empty_batches_touch_nothing(gpu_device):
     """No requests, or requests without packets and without query rows: the calls succeed, launch
     nothing and leave the cache, the output and ctx_len of other requests alone."""
