@@ -95,9 +95,12 @@ __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "mem
 // `stream`: the rows will not be read again soon by anyone (no other work item shares them
 // through the L2): the load carries the non-temporal hint, which a plain streaming read of HBM
 // was measured to reward with 7.0 instead of 6.3 TB/s.
-__device__ __forceinline__ void load_to_lds_16(const void *sbase, uint32_t voff, uint32_t lds_addr, bool stream = false)
+// (A compile-time choice: selected at run time, every load became a branch between two copies of
+// the instruction, and the tile loads could no longer be issued between the matrix instructions.)
+template <bool STREAM>
+__device__ __forceinline__ void load_to_lds_16(const void *sbase, uint32_t voff, uint32_t lds_addr)
 {
-    if (stream)  // wave-uniform
+    if (STREAM)
         asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
     else
         asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
@@ -207,7 +210,7 @@ __device__ unsigned long long *kvp_timing_phases;  // [item][8 waves][8]
 //   NW 8, KS 2, 4 stages: 128 rows, the two groups take alternate tiles of the item's range
 //                         (an in-workgroup split-KV that halves the serial chain of a
 //                         latency-bound item) and merge their (m, l, O) through LDS.
-template <int STAGES, int SRC, int NW, int KS>
+template <int STAGES, int SRC, int NW, int KS, bool NTL>
 __device__ __forceinline__ void attention_body(const AttnArgs &a)
 {
     constexpr int RW = NW / KS;    // waves per group (a group owns 32 RW rows)
@@ -260,62 +263,69 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
         const int rb = 4 * (NW * i + wave) < max_r ? 4 * (NW * i + wave) : max_r;
         return blk_ids[((it.kv_begin + tj * BN + rb) >> a.cache.block_shift) - blk0];
     };
-    const bool nt_loads = a.nt_loads != 0;
-    auto issue = [&](int tj) {
-        const uint32_t st = lds_base + (uint32_t)((tj % STAGES) * STAGE_BYTES);
+    // The loads of tile tj: NI parts per wave, each one K and one V load instruction.  tile_src
+    // is the scalar part (where the tile's rows are), issue_part the per-lane part.
+    struct TileSrc {
+        const char *kt, *vt;   // wave-uniform byte address of the tile's first K / V row
+        uint32_t row_bytes;    // distance between rows
+        int max_r;             // last row of the tile that exists (rows past it repeat it; they are masked later)
+    };
+    auto tile_src = [&](int tj) -> TileSrc {
+        TileSrc ts;
         if (SRC == SRC_PACKETS) {
             const AttnTile td = a.tiles[it.kv_begin + tj];
-            const char *kt, *vt;
-            uint32_t row_bytes;
             if (td.kind == 0) {
                 // stride < 0: a compressed packet, src_base is this layer's own part of the blob
                 // ([K: Hkv x rows][V: Hkv x rows], rows = -stride)
                 const bool own_layer = td.stride < 0;
                 const int stride = own_layer ? -td.stride : td.stride;
                 const int64_t slice = ((int64_t)(own_layer ? 0 : a.layer) * a.n_kv + it.kv_head) * stride + td.row0;
-                kt = (const char *)((const bf16_t *)a.arena + td.src_base + slice * D);
-                vt = kt + (int64_t)(own_layer ? 1 : a.n_layers_total) * a.n_kv * stride * ROW_BYTES;
-                row_bytes = ROW_BYTES;
+                ts.kt = (const char *)((const bf16_t *)a.arena + td.src_base + slice * D);
+                ts.vt = ts.kt + (int64_t)(own_layer ? 1 : a.n_layers_total) * a.n_kv * stride * ROW_BYTES;
+                ts.row_bytes = ROW_BYTES;
             } else {
-                kt = (const char *)((const bf16_t *)a.k_tail + tail_off + (int64_t)td.row0 * a.n_kv * D);
-                vt = (const char *)((const bf16_t *)a.v_new + tail_off + (int64_t)td.row0 * a.n_kv * D);
-                row_bytes = (uint32_t)(a.n_kv * ROW_BYTES);
+                ts.kt = (const char *)((const bf16_t *)a.k_tail + tail_off + (int64_t)td.row0 * a.n_kv * D);
+                ts.vt = (const char *)((const bf16_t *)a.v_new + tail_off + (int64_t)td.row0 * a.n_kv * D);
+                ts.row_bytes = (uint32_t)(a.n_kv * ROW_BYTES);
             }
-            kt = uniform_ptr(kt);
-            vt = uniform_ptr(vt);
-#pragma unroll
-            for (int i = 0; i < NI; ++i) {
-                int r = 4 * (NW * i + wave) + slot_row;
-                r = r < td.n_rows - 1 ? r : td.n_rows - 1;  // rows past the tile repeat its last row (masked)
-                const uint32_t dst = st + (uint32_t)(4 * (NW * i + wave) * ROW_BYTES);
-                load_to_lds_16(kt, (uint32_t)r * row_bytes + 16 * k_chunk, dst, nt_loads);
-                load_to_lds_16(vt, (uint32_t)r * row_bytes + 16 * v_chunk, dst + TILE_BYTES, nt_loads);
-            }
-            return;
+            ts.kt = uniform_ptr(ts.kt);
+            ts.vt = uniform_ptr(ts.vt);
+            ts.max_r = td.n_rows - 1;
+            return ts;
         }
-        // rows past the range (last tile only) repeat the last row; they are masked later
-        const int max_r = tj == n_tiles - 1 ? last_tile_rows - 1 : BN - 1;
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            int r = 4 * (NW * i + wave) + slot_row;
-            r = r < max_r ? r : max_r;
-            const uint32_t dst = st + (uint32_t)(4 * (NW * i + wave) * ROW_BYTES);
-            if (SRC == SRC_CONTIG) {
-                const char *kt = uniform_ptr(k_item + (int64_t)tj * TILE_BYTES);
-                const char *vt = uniform_ptr(v_item + (int64_t)tj * TILE_BYTES);
-                load_to_lds_16(kt, (uint32_t)(r * ROW_BYTES + 16 * k_chunk), dst, nt_loads);
-                load_to_lds_16(vt, (uint32_t)(r * ROW_BYTES + 16 * v_chunk), dst + TILE_BYTES, nt_loads);
-            } else {
-                // the block id is wave-uniform: the address is a scalar base plus a 32-bit lane offset
-                const int b = __builtin_amdgcn_readfirstlane(blk_word(tj, i));
-                const int64_t blk_off = paged_base + (((int64_t)b * a.n_kv + it.kv_head) << a.cache.block_shift) * D;
-                const int slot = (it.kv_begin + tj * BN + r) & ((1 << a.cache.block_shift) - 1);
-                const char *kt = uniform_ptr((const char *)(kc + blk_off));
-                const char *vt = uniform_ptr((const char *)(vc + blk_off));
-                load_to_lds_16(kt, (uint32_t)(slot * ROW_BYTES + 16 * k_chunk), dst, nt_loads);
-                load_to_lds_16(vt, (uint32_t)(slot * ROW_BYTES + 16 * v_chunk), dst + TILE_BYTES, nt_loads);
-            }
+        ts.max_r = tj == n_tiles - 1 ? last_tile_rows - 1 : BN - 1;
+        ts.row_bytes = ROW_BYTES;
+        if (SRC == SRC_CONTIG) {
+            ts.kt = uniform_ptr(k_item + (int64_t)tj * TILE_BYTES);
+            ts.vt = uniform_ptr(v_item + (int64_t)tj * TILE_BYTES);
+        } else {
+            ts.kt = ts.vt = nullptr;  // (paged: every load instruction looks its block up)
         }
+        return ts;
+    };
+    auto issue_part = [&](const TileSrc &ts, int tj, int i) {
+        const uint32_t st = lds_base + (uint32_t)((tj % STAGES) * STAGE_BYTES);
+        int r = 4 * (NW * i + wave) + slot_row;
+        r = r < ts.max_r ? r : ts.max_r;
+        const uint32_t dst = st + (uint32_t)(4 * (NW * i + wave) * ROW_BYTES);
+        if (SRC != SRC_PAGED) {
+            load_to_lds_16<NTL>(ts.kt, (uint32_t)r * ts.row_bytes + 16 * k_chunk, dst);
+            load_to_lds_16<NTL>(ts.vt, (uint32_t)r * ts.row_bytes + 16 * v_chunk, dst + TILE_BYTES);
+        } else {
+            // the block id is wave-uniform: the address is a scalar base plus a 32-bit lane offset
+            const int b = __builtin_amdgcn_readfirstlane(blk_word(tj, i));
+            const int64_t blk_off = paged_base + (((int64_t)b * a.n_kv + it.kv_head) << a.cache.block_shift) * D;
+            const int slot = (it.kv_begin + tj * BN + r) & ((1 << a.cache.block_shift) - 1);
+            const char *kt = uniform_ptr((const char *)(kc + blk_off));
+            const char *vt = uniform_ptr((const char *)(vc + blk_off));
+            load_to_lds_16<NTL>(kt, (uint32_t)(slot * ROW_BYTES + 16 * k_chunk), dst);
+            load_to_lds_16<NTL>(vt, (uint32_t)(slot * ROW_BYTES + 16 * v_chunk), dst + TILE_BYTES);
+        }
+    };
+    auto issue = [&](int tj) {
+        const TileSrc ts = tile_src(tj);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) issue_part(ts, tj, i);
     };
     // this lane's query row
     const int rr = 32 * wave_r + n;
@@ -542,8 +552,18 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
         }
         // K fragments are requested in batches ahead of the MFMAs that use them, so the LDS
         // latency is paid once per batch instead of once per fragment.
+        // The next loads -- they refill the stages the previous round used, which every wave left
+        // before the barrier above -- are issued between the matrix instructions, one part (a K and
+        // a V load with their address arithmetic) behind each of the first k-steps' MFMA pair: the
+        // matrix pipe is busy for 64 cycles per pair, which is about what a part takes to issue.
         {
             constexpr int KS_PER_BATCH = SRC == SRC_PACKETS ? 4 : 8;  // fewer live registers there
+            constexpr int N_PARTS = KS * NI;                         // <= 4
+            static_assert(N_PARTS <= 8, "one part per k-step");
+            TileSrc rsrc[KS];
+#pragma unroll
+            for (int k2 = 0; k2 < KS; ++k2)
+                if (KS * (rd + PR) + k2 < n_tiles) rsrc[k2] = tile_src(KS * (rd + PR) + k2);
 #pragma unroll
             for (int b = 0; b < 8 / KS_PER_BATCH; ++b) {
                 uint4 kf[2 * KS_PER_BATCH];
@@ -556,15 +576,18 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
                 __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the matrix code
 #pragma unroll
                 for (int i = 0; i < KS_PER_BATCH; ++i) {
-                    const bool head = b == 0 && i == 0;  // compile-time: the tile's first k-step
-                    sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[2 * i]), qf[KS_PER_BATCH * b + i], head ? cinit : sacc[0], 0, 0, 0);
-                    sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[2 * i + 1]), qf[KS_PER_BATCH * b + i], head ? cinit : sacc[1], 0, 0, 0);
+                    const int kstep = KS_PER_BATCH * b + i;
+                    const bool head = kstep == 0;  // compile-time: the tile's first k-step
+                    sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[2 * i]), qf[kstep], head ? cinit : sacc[0], 0, 0, 0);
+                    sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[2 * i + 1]), qf[kstep], head ? cinit : sacc[1], 0, 0, 0);
+                    if (kstep < N_PARTS) {
+                        const int k2 = kstep / NI, tj = KS * (rd + PR) + k2;
+                        if (tj < n_tiles) issue_part(rsrc[k2], tj, kstep % NI);
+                        __builtin_amdgcn_sched_barrier(0);  // this part stays behind this pair
+                    }
                 }
             }
         }
-        // The next loads are issued while the matrix cores work on S: they refill the stages
-        // the previous round used, which every wave left before the barrier above.
-        refill();
         KVP_PHASE(2);
 
         // ---- online softmax; accumulator r of block kb is tile row 32 kb + 8 (r/4) + 4 h + r%4
@@ -778,10 +801,10 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
     KVP_STAMP(31);
 }
 
-template <int STAGES, int SRC, int NW, int KS>
+template <int STAGES, int SRC, int NW, int KS, bool NTL>
 __global__ __launch_bounds__(64 * NW, 2) void attention_mfma_kernel(AttnArgs a)
 {
-    attention_body<STAGES, SRC, NW, KS>(a);
+    attention_body<STAGES, SRC, NW, KS, NTL>(a);
 }
 
 // 8 waves, 4 stages, the row block chosen item by item: 256 packed rows, or (AttnItem::half_block)
@@ -792,8 +815,8 @@ template <int SRC>
 __global__ __launch_bounds__(512, 2) void attention_mfma_mixed_kernel(AttnArgs a)
 {
     const bool half = a.inl.n ? false : a.items[blockIdx.x].half_block != 0;  // (regular launches have no half blocks)
-    if (half) attention_body<4, SRC, 8, 2>(a);
-    else attention_body<4, SRC, 8, 1>(a);
+    if (half) attention_body<4, SRC, 8, 2, false>(a);
+    else attention_body<4, SRC, 8, 1, false>(a);
 }
 
 template <typename K> static int launch_kernel(K kernel, bool &attr_set, int lds_bytes, int threads, const AttnArgs &a, void *stream)
@@ -807,11 +830,20 @@ template <typename K> static int launch_kernel(K kernel, bool &attr_set, int lds
     return (int)hipGetLastError();
 }
 
-template <int SRC, int NW, int KS, int STAGES> static int launch_variant(const AttnArgs &a, void *stream)
+template <int SRC, int NW, int KS, int STAGES, bool NTL> static int launch_variant_nt(const AttnArgs &a, void *stream)
 {
     constexpr int lds_bytes = STAGES * STAGE_BYTES + (SRC == SRC_PAGED ? MAX_BLOCK_IDS * 4 : 0);
     static bool attr_set = false;
-    return launch_kernel(attention_mfma_kernel<STAGES, SRC, NW, KS>, attr_set, lds_bytes, 64 * NW, a, stream);
+    return launch_kernel(attention_mfma_kernel<STAGES, SRC, NW, KS, NTL>, attr_set, lds_bytes, 64 * NW, a, stream);
+}
+
+// The streaming hint on the tile loads (a.nt_loads) exists for the 8-wave shapes, which stream
+// long contexts; the planner asks for it nowhere else (launches of 4-wave workgroups are short or
+// share their rows).
+template <int SRC, int NW, int KS, int STAGES> static int launch_variant(const AttnArgs &a, void *stream)
+{
+    if (NW == 8 && a.nt_loads) return launch_variant_nt<SRC, NW, KS, STAGES, NW == 8>(a, stream);
+    return launch_variant_nt<SRC, NW, KS, STAGES, false>(a, stream);
 }
 
 template <int SRC> static int launch_mixed(const AttnArgs &a, void *stream)
