@@ -307,10 +307,12 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
         const uint32_t st = lds_base + (uint32_t)((tj % STAGES) * STAGE_BYTES);
         int r = 4 * (NW * i + wave) + slot_row;
         r = r < ts.max_r ? r : ts.max_r;
-        const uint32_t dst = st + (uint32_t)(4 * (NW * i + wave) * ROW_BYTES);
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(st + (uint32_t)(4 * (NW * i + wave) * ROW_BYTES));  // (wave-uniform)
         if (SRC != SRC_PAGED) {
-            load_to_lds_16<NTL>(ts.kt, (uint32_t)r * ts.row_bytes + 16 * k_chunk, dst);
-            load_to_lds_16<NTL>(ts.vt, (uint32_t)r * ts.row_bytes + 16 * v_chunk, dst + TILE_BYTES);
+            // (uniform_ptr again: should the compiler have moved the address to vector registers, it
+            // comes back to scalar ones, which the instruction needs; otherwise this folds away)
+            load_to_lds_16<NTL>(uniform_ptr(ts.kt), (uint32_t)r * ts.row_bytes + 16 * k_chunk, dst);
+            load_to_lds_16<NTL>(uniform_ptr(ts.vt), (uint32_t)r * ts.row_bytes + 16 * v_chunk, dst + TILE_BYTES);
         } else {
             // the block id is wave-uniform: the address is a scalar base plus a 32-bit lane offset
             const int b = __builtin_amdgcn_readfirstlane(blk_word(tj, i));
