@@ -552,42 +552,45 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) cinit[r] = c;
         }
-        // K fragments are requested in batches ahead of the MFMAs that use them, so the LDS
-        // latency is paid once per batch instead of once per fragment.
-        // The next loads -- they refill the stages the previous round used, which every wave left
-        // before the barrier above -- are issued between the matrix instructions, one part (a K and
-        // a V load with their address arithmetic) behind each of the first k-steps' MFMA pair: the
-        // matrix pipe is busy for 64 cycles per pair, which is about what a part takes to issue.
+        // K fragments run AHEAD k-steps in front of the MFMAs that use them: the first AHEAD k-steps'
+        // fragments are requested up front, and each k-step's MFMA pair is followed by the request
+        // for the fragments AHEAD steps on, so the matrix pipe starts after a quarter of the tile has
+        // arrived from LDS instead of all of it (the four waves of a workgroup reach this point
+        // together, and 64 KB of fragment reads keep the LDS busy for about as long as the 16 MFMAs
+        // keep the matrix pipe).
+        // The next tile loads -- they refill the stages the previous round used, which every wave
+        // left before the barrier above -- are issued between the matrix instructions too, one part
+        // (a K and a V load with their address arithmetic) behind each of the first k-steps' MFMA
+        // pair: the matrix pipe is busy for 64 cycles per pair, about what a part takes to issue.
         {
-            constexpr int KS_PER_BATCH = SRC == SRC_PACKETS ? 4 : 8;  // fewer live registers there
-            constexpr int N_PARTS = KS * NI;                         // <= 4
+            constexpr int AHEAD = SRC == SRC_PACKETS ? 2 : 4;  // (fewer live registers in the in-place variant)
+            constexpr int N_PARTS = KS * NI;                   // <= 4
             static_assert(N_PARTS <= 8, "one part per k-step");
             TileSrc rsrc[KS];
 #pragma unroll
             for (int k2 = 0; k2 < KS; ++k2)
                 if (KS * (rd + PR) + k2 < n_tiles) rsrc[k2] = tile_src(KS * (rd + PR) + k2);
+            uint4 kf[2 * AHEAD];
+            auto read_k = [&](int kstep) {
+                const int coff = 16 * ((2 * kstep + h) ^ (n & 15));
+                kf[2 * (kstep % AHEAD)] = *(const uint4 *)(kl + n * ROW_BYTES + coff);
+                kf[2 * (kstep % AHEAD) + 1] = *(const uint4 *)(kl + (32 + n) * ROW_BYTES + coff);
+            };
 #pragma unroll
-            for (int b = 0; b < 8 / KS_PER_BATCH; ++b) {
-                uint4 kf[2 * KS_PER_BATCH];
+            for (int i = 0; i < AHEAD; ++i) read_k(i);
+            __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the matrix code
 #pragma unroll
-                for (int i = 0; i < KS_PER_BATCH; ++i) {
-                    const int coff = 16 * ((2 * (KS_PER_BATCH * b + i) + h) ^ (n & 15));
-                    kf[2 * i] = *(const uint4 *)(kl + n * ROW_BYTES + coff);
-                    kf[2 * i + 1] = *(const uint4 *)(kl + (32 + n) * ROW_BYTES + coff);
+            for (int kstep = 0; kstep < 8; ++kstep) {
+                const bool head = kstep == 0;  // compile-time: the tile's first k-step
+                const int sl = 2 * (kstep % AHEAD);
+                sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[sl]), qf[kstep], head ? cinit : sacc[0], 0, 0, 0);
+                sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[sl + 1]), qf[kstep], head ? cinit : sacc[1], 0, 0, 0);
+                if (kstep + AHEAD < 8) read_k(kstep + AHEAD);
+                if (kstep < N_PARTS) {
+                    const int k2 = kstep / NI, tj = KS * (rd + PR) + k2;
+                    if (tj < n_tiles) issue_part(rsrc[k2], tj, kstep % NI);
                 }
-                __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the matrix code
-#pragma unroll
-                for (int i = 0; i < KS_PER_BATCH; ++i) {
-                    const int kstep = KS_PER_BATCH * b + i;
-                    const bool head = kstep == 0;  // compile-time: the tile's first k-step
-                    sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[2 * i]), qf[kstep], head ? cinit : sacc[0], 0, 0, 0);
-                    sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[2 * i + 1]), qf[kstep], head ? cinit : sacc[1], 0, 0, 0);
-                    if (kstep < N_PARTS) {
-                        const int k2 = kstep / NI, tj = KS * (rd + PR) + k2;
-                        if (tj < n_tiles) issue_part(rsrc[k2], tj, kstep % NI);
-                        __builtin_amdgcn_sched_barrier(0);  // this part stays behind this pair
-                    }
-                }
+                __builtin_amdgcn_sched_barrier(0);  // what follows a pair stays behind it
             }
         }
         KVP_PHASE(2);
