@@ -437,38 +437,66 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
         if (n_tail > 0) {
             bf16_t *kcw = SRC == SRC_PACKETS ? (bf16_t *)a.k_tail : (bf16_t *)a.cache.k;
             bf16_t *vcw = (bf16_t *)a.cache.v;
-            const int n_chunks = SRC == SRC_PACKETS ? 8 : 24;  // 8 K chunk pairs (+ 16 V chunks)
-            for (int idx = tid; idx < n_tail * n_chunks; idx += NT) {
-                const int qr = tail_lo + idx / n_chunks, cidx = idx % n_chunks;
+            // Work units: 8 K chunk pairs per row (rotate, store) and, with a cache, 16 V chunks per
+            // row (copy).  A thread takes two K units and four V units per trip and issues all their
+            // loads before it uses the first, so the append costs one memory round trip per trip
+            // (32 query rows: one trip) instead of one per unit.
+            auto unit_dst = [&](int qr, int64_t src) -> int64_t {
                 const int row = it.ctx_len + qr;  // cache row of the query token
-                const int pos = it.pos0 + qr;     // its position
-                const int64_t src = ((int64_t)(it.q_off + qr) * a.n_kv + it.kv_head) * D;
-                int64_t dst;
-                if (SRC == SRC_PACKETS) {
-                    dst = src;
-                } else if (SRC == SRC_CONTIG) {
-                    dst = contig_off + (int64_t)(row - it.kv_begin) * D;
-                } else {
-                    const int b = blk_ids[(row >> a.cache.block_shift) - blk0];
-                    const int slot = row & ((1 << a.cache.block_shift) - 1);
-                    dst = paged_base + ((((int64_t)b * a.n_kv + it.kv_head) << a.cache.block_shift) + slot) * D;
-                }
-                if (cidx >= 8) {
-                    const int e = 8 * (cidx - 8);
-                    *(uint4 *)(vcw + dst + e) = *(const uint4 *)((const bf16_t *)a.v_new + src + e);
-                } else {
-                    const int e = 8 * cidx;
-                    const uint4 ulo = *(const uint4 *)((const bf16_t *)a.k_new + src + e);
-                    const uint4 uhi = *(const uint4 *)((const bf16_t *)a.k_new + src + 64 + e);
+                if (SRC == SRC_PACKETS) return src;
+                if (SRC == SRC_CONTIG) return contig_off + (int64_t)(row - it.kv_begin) * D;
+                const int b = blk_ids[(row >> a.cache.block_shift) - blk0];
+                const int slot = row & ((1 << a.cache.block_shift) - 1);
+                return paged_base + ((((int64_t)b * a.n_kv + it.kv_head) << a.cache.block_shift) + slot) * D;
+            };
+            const int n_k = n_tail * 8, n_v = SRC == SRC_PACKETS ? 0 : n_tail * 16;
+            // (loads are unconditional, from units clamped into range; only the stores are guarded)
+            for (int s0 = 0; 2 * s0 * NT < n_k || 4 * s0 * NT < n_v; ++s0) {
+                if (4 * s0 * NT + tid >= n_v && 2 * s0 * NT + tid >= n_k) continue;  // (a thread without a unit: few query rows)
+                uint4 vv0, vv1, vv2, vv3;
+                int64_t vd0, vd1, vd2, vd3;
+                auto v_load = [&](int j, uint4 &vv, int64_t &vd) -> bool {
+                    const int idx = (4 * s0 + j) * NT + tid;
+                    const int ic = idx < n_v ? idx : (n_v > 0 ? n_v - 1 : 0);
+                    const int qr = tail_lo + ic / 16, e = 8 * (ic % 16);
+                    const int64_t src = ((int64_t)(it.q_off + qr) * a.n_kv + it.kv_head) * D;
+                    vd = unit_dst(qr, src) + e;
+                    vv = n_v > 0 ? *(const uint4 *)((const bf16_t *)a.v_new + src + e) : make_uint4(0, 0, 0, 0);
+                    return idx < n_v;
+                };
+                const bool von0 = v_load(0, vv0, vd0), von1 = v_load(1, vv1, vd1), von2 = v_load(2, vv2, vd2), von3 = v_load(3, vv3, vd3);
+                struct KUnit { uint4 ulo, uhi; float4 c0, c1, c2, c3; int64_t dst; bool on; };
+                auto k_load = [&](int j) -> KUnit {
+                    KUnit u;
+                    const int idx = (2 * s0 + j) * NT + tid;
+                    const int ic = idx < n_k ? idx : n_k - 1;
+                    const int qr = tail_lo + ic / 8, e = 8 * (ic % 8);
+                    const int pos = it.pos0 + qr;     // the token's position
+                    const int64_t src = ((int64_t)(it.q_off + qr) * a.n_kv + it.kv_head) * D;
+                    u.dst = unit_dst(qr, src) + e;
+                    u.ulo = *(const uint4 *)((const bf16_t *)a.k_new + src + e);
+                    u.uhi = *(const uint4 *)((const bf16_t *)a.k_new + src + 64 + e);
                     const float4 *csr = (const float4 *)(a.cs + (int64_t)pos * 64 + e);
-                    float4 cs4[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) cs4[j] = a.prerotated ? make_float4(1.f, 0.f, 1.f, 0.f) : csr[j];
+                    u.c0 = csr[0]; u.c1 = csr[1]; u.c2 = csr[2]; u.c3 = csr[3];
+                    u.on = idx < n_k;
+                    return u;
+                };
+                const KUnit k0 = k_load(0), k1 = k_load(1);
+                if (von0) *(uint4 *)(vcw + vd0) = vv0;
+                if (von1) *(uint4 *)(vcw + vd1) = vv1;
+                if (von2) *(uint4 *)(vcw + vd2) = vv2;
+                if (von3) *(uint4 *)(vcw + vd3) = vv3;
+                auto k_store = [&](const KUnit &u) {
+                    if (!u.on) return;
+                    const float4 one = make_float4(1.f, 0.f, 1.f, 0.f);
+                    const float4 cs4[4] = {a.prerotated ? one : u.c0, a.prerotated ? one : u.c1, a.prerotated ? one : u.c2, a.prerotated ? one : u.c3};
                     uint4 olo, ohi;
-                    rotate_chunk_pair<true>(ulo, uhi, cs4, 1.f, 1.f, olo, ohi);
-                    *(uint4 *)(kcw + dst + e) = olo;
-                    *(uint4 *)(kcw + dst + 64 + e) = ohi;
-                }
+                    rotate_chunk_pair<true>(u.ulo, u.uhi, cs4, 1.f, 1.f, olo, ohi);
+                    *(uint4 *)(kcw + u.dst) = olo;
+                    *(uint4 *)(kcw + u.dst + 64) = ohi;
+                };
+                k_store(k0);
+                k_store(k1);
             }
             wait_vmcnt<0>();   // this wave's stores have reached the L2
             __syncthreads();   // ... and so have every other wave's
