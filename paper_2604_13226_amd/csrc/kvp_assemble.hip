@@ -56,6 +56,8 @@ __device__ __forceinline__ Tile fetch_tile(const AsmArgs &a, int d)
     AsmSeg g;
     if (a.segs) {
         g = a.segs[a.tile_seg[b]];  // (wave-uniform)
+    } else if (a.seg_tiles > 0) {
+        g = a.inline_seg[b / a.seg_tiles];  // packets of one length: no search
     } else {
         int j = 0;
         while (j + 1 < a.n_segs && a.inline_seg[j + 1].tile0 <= b) ++j;

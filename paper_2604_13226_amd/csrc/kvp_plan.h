@@ -53,6 +53,7 @@ struct AsmArgs {
     int32_t split_kv;  // grid.z = 2: a workgroup moves the K rows of its tile (z = 0) or the V rows (z = 1)
     int32_t layered;  // segments name their own layer; blockIdx.y = kv head
     int32_t n_segs;
+    int32_t seg_tiles;  // > 0: every segment has this many tiles (segment of tile b = b / seg_tiles, no search)
     AsmSeg inline_seg[ASM_INLINE_SEGS];
 };
 static_assert(sizeof(AsmArgs) <= 4096, "kernel arguments are limited to 4 KB");

@@ -531,8 +531,14 @@ int run_gather(kvp_store *s, const std::vector<AsmSeg> &segs, int64_t n_tiles, i
     a.n_segs = (int)segs.size();
     a.tile_seg = nullptr;
     a.layered = layered ? 1 : 0;
+    a.seg_tiles = 0;
     if (inline_plan) {
         for (size_t i = 0; i < segs.size(); ++i) a.inline_seg[i] = segs[i];
+        // equal tile counts (packets of one length): a workgroup finds its segment by division
+        const int64_t per = segs.empty() ? 0 : n_tiles / (int64_t)segs.size();
+        bool uniform = per > 0 && per * (int64_t)segs.size() == n_tiles;
+        for (size_t i = 0; uniform && i < segs.size(); ++i) uniform = segs[i].tile0 == (int64_t)i * per;
+        if (uniform) a.seg_tiles = (int32_t)per;
     } else {
         if (!kept) {
             int urc = upload_plan(s, slot, upload, hip_stream);
