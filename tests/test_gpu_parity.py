@@ -332,6 +332,44 @@ def test_split_invariance(gpu_device):
         compare(w, got, ref)
 
 
+@pytest.mark.parametrize("k", [60, -60, 0])
+def test_values_scaled_by_a_power_of_two_scale_the_output(gpu_device, k):
+    """The split-KV partial rows are fp16 scaled per row by a power of two chosen from the row's
+    largest magnitude.  Scaling every value row (V and V_new) by 2^k scales every product and sum of
+    the path exactly, so the output must be the unscaled output times 2^k, whatever the magnitude:
+    2^60 and 2^-60 are far outside what fp16 holds without the per-row exponent.  Bit for bit but
+    for the merge weights: a partial row's reference travels as the float m + e, whose rounding
+    depends on e's size (relative 2^-17 at most), which may move an output by one bf16 step."""
+    import paper_2604_13226_amd as kvp
+    w = W.llama_k5(n_layers=1, n_packets=8)
+    n_q = w.requests[0].n_q
+    outs = []
+    for scale in (1.0, 2.0 ** k):
+        store = kvp.kvp_store_create(1, w.n_q_heads, w.n_kv_heads, w.head_dim, "bf16", w.rope_base, 4096,
+                                     sum(kvp.packet_bytes(1, w.n_kv_heads, w.head_dim, "bf16", int(w.packet_lens[p]))
+                                         for p in w.requests[0].packet_ids), 8, 8, device=0)
+        for p in w.requests[0].packet_ids:
+            kk, vv = w.packet_kv(p, device="cuda")
+            kvp.kvp_store_put(store, p, kk, (vv.float() * scale).to(torch.bfloat16))
+        cache = make_cache(w, kvp, store)
+        kvp.kvp_assemble(store, [(w.requests[0].packet_ids, 0)], cache)
+        q, kn, vn = w.query(0, 0, "cuda")
+        vn = (vn.float() * scale).to(torch.bfloat16)
+        ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, 1, n_q, w.ctx_len(0) + n_q))
+        out = torch.full_like(q, float("nan"))
+        kvp.kvp_query_prefill(store, cache, 0, q, kn, vn, [0, n_q], ws, out)
+        torch.cuda.synchronize()
+        assert int(kvp.kvp_debug_last_plan(store, 1)[4]) > 0          # the call was split: partial rows were used
+        outs.append(out.float().cpu().numpy().astype(np.float64))
+    assert np.all(np.isfinite(outs[1]))
+    want, got = outs[0], outs[1] / 2.0 ** k
+    rowmax = np.abs(want).max(axis=-1, keepdims=True)
+    assert np.all(np.abs(got - want) <= 2.0 ** -7 * np.abs(want) + 2.0 ** -11 * rowmax)   # one bf16 step; tiny elements: the fp16 rows' step
+    assert np.mean(got == want) > 0.99
+    if k == 0:
+        assert np.array_equal(got, want)
+
+
 @pytest.mark.parametrize("paged", [False, True])
 @pytest.mark.parametrize("target", [None, "3000"])
 def test_half_blocks_in_a_launch_of_256_row_blocks(gpu_device, paged, target):
