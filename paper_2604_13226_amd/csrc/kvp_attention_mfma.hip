@@ -173,6 +173,23 @@ __device__ __forceinline__ void rotate_chunk_pair(const uint4 &ulo, const uint4 
 
 enum { SRC_CONTIG = 0, SRC_PAGED = 1, SRC_PACKETS = 2 };
 
+// A tile record of the in-place path, read through the scalar cache: the records are written by
+// the host before the launch and never by a kernel, and the index is the same in every lane.  (As
+// an ordinary load this was a vector load, and the wait for it -- placed by the compiler, who cannot
+// count the tile loads in flight -- drained the whole prefetch ring at every tile.)
+__device__ __forceinline__ AttnTile load_tile_record(const AttnTile *tiles, int idx)
+{
+    typedef const __attribute__((address_space(4))) int32_t *const_i32_p;
+    const_i32_p p = (const_i32_p)(uintptr_t)(tiles + __builtin_amdgcn_readfirstlane(idx));
+    int32_t w[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w[i] = p[i];
+    AttnTile t;
+    __builtin_memcpy(&t, w, sizeof t);
+    return t;
+}
+static_assert(sizeof(AttnTile) == 8 * sizeof(int32_t), "eight words");
+
 // A micro-benchmark that includes this file with -DKVP_TIMING gets per-workgroup time stamps and
 // per-wave phase totals through two file-scope pointers it sets itself; the library is never
 // built that way, and its kernel arguments are the same in either build.
@@ -273,7 +290,7 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
     auto tile_src = [&](int tj) -> TileSrc {
         TileSrc ts;
         if (SRC == SRC_PACKETS) {
-            const AttnTile td = a.tiles[it.kv_begin + tj];
+            const AttnTile td = load_tile_record(a.tiles, it.kv_begin + tj);
             if (td.kind == 0) {
                 // stride < 0: a compressed packet, src_base is this layer's own part of the blob
                 // ([K: Hkv x rows][V: Hkv x rows], rows = -stride)
@@ -408,7 +425,7 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qf[ks]));
     };
-    int cur_delta = SRC == SRC_PACKETS && n_tiles > 0 ? a.tiles[it.kv_begin].pos : 0;
+    int cur_delta = SRC == SRC_PACKETS && n_tiles > 0 ? load_tile_record(a.tiles, it.kv_begin).pos : 0;
     KVP_STAMP(1);
     q_issue(cur_delta);  // first, so that the query arrives ahead of the tiles
     if (SRC == SRC_PAGED) {  // the block ids travel while the query does
@@ -418,7 +435,7 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
         __syncthreads();
     }
     // a first tile that cannot contain query rows can start its trip right away
-    const bool early0 = n_tiles > 0 && (SRC == SRC_PACKETS ? a.tiles[it.kv_begin].kind == 0 : it.kv_begin + BN <= it.ctx_len);
+    const bool early0 = n_tiles > 0 && (SRC == SRC_PACKETS ? load_tile_record(a.tiles, it.kv_begin).kind == 0 : it.kv_begin + BN <= it.ctx_len);
     if (early0) issue(0);
 
     // ---- query rows inside this item's range: rotate K_new to its row's position and
@@ -427,7 +444,7 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
         int tail_lo, n_tail;  // query rows [tail_lo, tail_lo + n_tail) relative to ctx_len
         if (SRC == SRC_PACKETS) {
             // an item that reaches the query tiles writes all of this head's rotated K_new rows
-            const bool has_tail = n_tiles > 0 && a.tiles[it.kv_end - 1].kind != 0;
+            const bool has_tail = n_tiles > 0 && load_tile_record(a.tiles, it.kv_end - 1).kind != 0;
             tail_lo = 0;
             n_tail = has_tail ? it.n_q : 0;
         } else {
@@ -566,7 +583,7 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
         const char *vl = kl + TILE_BYTES;
         AttnTile td;
         if (SRC == SRC_PACKETS) {
-            td = a.tiles[it.kv_begin + ti];
+            td = load_tile_record(a.tiles, it.kv_begin + ti);
             if (td.pos != cur_delta && wave_active) {  // the tile belongs to another packet: re-rotate the query
                 cur_delta = td.pos;
                 reload_q(cur_delta);
