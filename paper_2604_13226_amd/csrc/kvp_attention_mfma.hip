@@ -516,6 +516,11 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
                 k_store(k1);
             }
             wait_vmcnt<0>();   // this wave's stores have reached the L2
+            // The same wait once more, in the form the compiler's own wait bookkeeping understands:
+            // without it the compiler takes the loads and stores above for still outstanding when the
+            // tile loop is entered and puts a full vmcnt(0) in front of every tile's first MFMA -- which
+            // waits for every tile load in flight and turns a four-stage ring into a one-deep prefetch.
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), the other counters left alone
             __syncthreads();   // ... and so have every other wave's
         }
     }
