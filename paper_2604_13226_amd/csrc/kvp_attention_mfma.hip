@@ -613,7 +613,7 @@ __device__ __forceinline__ void attention_body(const AttnArgs &a)
         // (a K and a V load with their address arithmetic) behind each of the first k-steps' MFMA
         // pair: the matrix pipe is busy for 64 cycles per pair, about what a part takes to issue.
         {
-            constexpr int AHEAD = SRC == SRC_PACKETS ? 2 : 4;  // (fewer live registers in the in-place variant)
+            constexpr int AHEAD = 2;  // (2, 3, 4, 6 and 8 k-steps measured: 2 is the fastest by a little, and holds the fewest registers)
             constexpr int N_PARTS = KS * NI;                   // <= 4
             static_assert(N_PARTS <= 8, "one part per k-step");
             TileSrc rsrc[KS];
