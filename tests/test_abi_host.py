@@ -363,7 +363,8 @@ def test_regular_one_request_plans_are_rebuilt_from_the_block_index():
     and the generic kernel keep reading their items from memory."""
     s = dry_store(n_q_heads=32, n_kv_heads=8, max_positions=1 << 17)
     for ctx, n_q, regular in [(8192, 32, True), (3000, 32, True), (8192, 1, True), (0, 20, True), (511, 30, True),
-                              (100000, 7, True), (8192 - 32, 32, True), (6720, 100, False), (100000, 200, False)]:
+                              (100000, 7, True), (8192 - 32, 32, True), (6144 - 32, 32, True),   # (the last: 24 equal splits, none shorter)
+                              (6720, 100, False), (100000, 200, False)]:
         cache = kvp.Cache.dry(1, t_cap=ctx + n_q)
         cache.ctx_len[0] = ctx
         kvp.kvp_query_prefill(s, cache, 0, None, None, None, np.array([0, n_q], np.int32), None, None)

@@ -1292,10 +1292,16 @@ def test_a_gather_plan_kept_on_the_device_serves_the_same_call_again_and_no_othe
             check(c1, ref, len(reqs))
 
 
+def _with_lens(w, n):
+    w.packet_lens[:] = n
+    return w
+
+
 @pytest.mark.parametrize("mk", [
     lambda: W.llama_k5(n_layers=1, n_packets=8),
     lambda: W.llama_8k(n_layers=1, n_packets=16),
     lambda: W.llama_8k(n_layers=1, n_packets=16, n_q=1),
+    lambda: _with_lens(W.llama_8k(n_layers=1, n_packets=16), 526),      # 8416 + 32 rows = 22 x 384: the last kv range is a full one
 ])
 def test_items_rebuilt_from_the_block_index_give_the_same_bits_as_items_read_from_memory(gpu_device, mk):
     """The workgroups of a regular one-request launch rebuild their work items from their index;
