@@ -272,9 +272,10 @@ int kvp_prefill_packets(kvp_store_t *store, const kvp_request_t *reqs, int32_t n
  * before or on a new one.  The array (32 MiB per GPU, held by every GPU the library has a store on
  * until the process ends) gives kvp_static_workspace_bytes() = 31 MiB of workspace and 1 MiB for the
  * plan; a call that needs more of either returns KVP_E_CAPACITY and launches nothing (the
- * metric's 8K-context request needs 12.6 MiB; the eight 16.9K-context requests of 128 query rows
- * together need 34 MiB and must use kvp_query_prefill).  Arguments, results and other errors as
- * kvp_query_prefill, without `workspace`.
+ * metric's 8K-context request needs 5.7 MiB, eight 16.9K-context requests of 128 query rows
+ * together 16.5 MiB; the split counts the planner chooses by itself keep a call's partial rows
+ * under about 26 MiB, so only calls cut finer through a tuning knob exceed the array).  Arguments,
+ * results and other errors as kvp_query_prefill, without `workspace`.
  * All calls on one GPU share that GPU's array, whichever store or stream they come from, and the
  * array keeps the last call's contents: calls are correct one after the other in stream order
  * (each call first replaces the plan if it differs from the one the array holds, and every

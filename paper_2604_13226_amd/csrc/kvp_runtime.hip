@@ -1421,7 +1421,7 @@ int query_prefill_impl(kvp_store *s, kvp_cache_t *cache, int32_t layer, const vo
         found = find_plan(s, s->pf_set, sig, hip_stream, sig_hash, hit);
     }
     kvp_store::PrefillCached &pf = *found;
-    const uint64_t qrb = q_rot_bytes(s, tot_q);
+    const uint64_t qrb = use_mfma(s, cache) ? 0 : q_rot_bytes(s, tot_q);  // (the MFMA kernel rotates the query in registers)
     if (in_capture && !hit)
         return fail(s, KVP_E_INVAL, "kvp_query_prefill under stream capture needs the plan of an earlier call with the same "
                                     "geometry on the same stream (call it once before capturing)");
@@ -1431,7 +1431,8 @@ int query_prefill_impl(kvp_store *s, kvp_cache_t *cache, int32_t layer, const vo
     if (!hit) {
         PrefillPlan p;
         plan_prefill(s, cache, n_req, rows.data(), cache->ctx_len, q_offsets, p);
-        const uint64_t need = qrb + (uint64_t)p.n_slots * p.bm * (g.head_dim + 2) * sizeof(float);
+        // (the MFMA kernel's partial rows are fp16: half the bytes of the generic kernel's)
+        const uint64_t need = qrb + (uint64_t)p.n_slots * (uint64_t)part_slot_bytes(p.bm, g.head_dim, p.kind == ATTN_MFMA ? 1 : 0);
         const uint64_t bytes = p.reqs.size() * sizeof(ReqMeta) + p.row_req.size() * 4 + p.groups.size() * sizeof(AttnGroup) +
                                p.items.size() * sizeof(AttnItem) + (uint64_t)n_req * bt_stride * 4 + 6 * 64;
         // every check comes before the entry is touched: a call that fails has changed nothing
@@ -1806,7 +1807,7 @@ int kvp_prefill_packets(kvp_store_t *s, const kvp_request_t *reqs, int32_t n_req
         if (n_req == 1 && metas[0].n_q > 0) {
             fill_inline_items(s, n_req, metas.data(), groups, items, bm, part_stride, per_item0, gq, inl);
         }
-        const uint64_t need = (uint64_t)n_slots * bm * (g.head_dim + 2) * sizeof(float);
+        const uint64_t need = (uint64_t)n_slots * (uint64_t)part_slot_bytes(bm, g.head_dim, 1);
         const uint64_t bytes = metas.size() * sizeof(ReqMeta) + groups.size() * sizeof(AttnGroup) +
                                items.size() * sizeof(AttnItem) + tiles.size() * sizeof(AttnTile) + 6 * 64;
         // every check comes before the entry is touched: a call that fails has changed nothing

@@ -282,12 +282,14 @@ def test_failed_calls_change_nothing_on_device(gpu_device):
     q = torch.zeros(4, 32, 128, dtype=torch.bfloat16, device="cuda")
     kn = torch.zeros(4, 8, 128, dtype=torch.bfloat16, device="cuda")
     out = torch.full_like(q, 9.0)
-    cache.ctx_len[0] = 10
+    big = kvp.Cache.contiguous(store, 1, 4096)               # a context long enough to be split: partial rows need a workspace
+    big.k.fill_(3.0)
+    big.ctx_len[0] = 3000
     with pytest.raises(kvp.KvpError) as e:                   # workspace too small
-        kvp.kvp_query_prefill(store, cache, 0, q, kn, kn, [0, 4], ws, out)
+        kvp.kvp_query_prefill(store, big, 0, q, kn, kn, [0, 4], ws, out)
     assert e.value.code == kvp.KVP_E_CAPACITY
     torch.cuda.synchronize()
-    assert bool((out == 9.0).all()) and bool((cache.k == 3.0).all())
+    assert bool((out == 9.0).all()) and bool((big.k == 3.0).all()) and bool((cache.k == 3.0).all())
 
 
 def test_a_failed_prefill_call_keeps_the_kept_plans(gpu_device):

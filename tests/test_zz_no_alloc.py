@@ -85,12 +85,20 @@ def test_two_calls_in_a_row_the_second_smaller(gpu_device, kind):
 def test_sizes_beyond_the_scratch_are_rejected(gpu_device):
     import paper_2604_13226_amd as kvp
     dev = "cuda:0"
-    w = W.llama_long_b8(n_layers=1, n_packets=16, batch=8, k=2, n_q=128)   # 256 partial slots of 256 rows: 34 MB
-    store = build_store(w, kvp, dev)
+    import os
+    w = W.llama_long_b8(n_layers=1, n_packets=16, batch=16, k=2, n_q=128)
+    # (the planner's own split counts keep the partial rows of any call under the scratch's size; a
+    # finer cut than it would choose -- 4 kv ranges for each of 256 row blocks: 1024 slots of 256
+    # fp16 rows, 69 MB -- does not fit)
+    os.environ["KVP_ATTN_TARGET_ITEMS"] = "1024"
+    try:
+        store = build_store(w, kvp, dev)
+    finally:
+        del os.environ["KVP_ATTN_TARGET_ITEMS"]
     cache = make_cache(w, kvp, store, dev)
     reqs = [(rq.packet_ids, rq.base_pos) for rq in w.requests]
     kvp.kvp_assemble(store, reqs, cache)
-    q_off = np.arange(9, dtype=np.int32) * 128
+    q_off = np.arange(17, dtype=np.int32) * 128
     q, kn, vn = _inputs(w, 0, dev)
     out = torch.full_like(q, 5.0)
     k_before = cache.k.clone()
@@ -100,7 +108,7 @@ def test_sizes_beyond_the_scratch_are_rejected(gpu_device):
     torch.cuda.synchronize()
     assert bool((out == 5.0).all()) and torch.equal(cache.k, k_before)      # nothing was launched
     # the same call fits a caller workspace
-    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, 8, 1024, 1056 + 128), dev)
+    ws = kvp.alloc_workspace(kvp.kvp_prefill_workspace_bytes(store, 16, 2048, 1056 + 128), dev)
     kvp.kvp_query_prefill(store, cache, 0, q, kn, vn, q_off, ws, out)
     torch.cuda.synchronize()
     assert not bool((out == 5.0).all())
